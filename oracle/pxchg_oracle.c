@@ -1,0 +1,199 @@
+/*
+ * CPU oracle for the per-GPU arithmetic of the parameter exchange.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file defines what the exchange computes, as
+ * scalar loops, one element at a time, in the order the paper's exchange is
+ * stated.  It is slow on purpose and is never part of the product path: only
+ * the tests, the smoke check and the CPU-baseline leg of the benchmark may call
+ * it.  It shares no code, header, table or constant with the HIP library.
+ *
+ * What the paper fixes (Section 3.2): every rank receives all k ranks' copies
+ * of its slice, sums them on the GPU ("Alltoall-sum-Allgather"), and the
+ * half-precision variant moves the data as 16-bit floats while the sum itself
+ * is carried out at full (32-bit) precision.  Section 4 fixes what is summed:
+ * parameter updates/gradients before descent (SUBGD), or weights and momentum
+ * after it (AWAGD, an average), with momentum SGD as the optimiser, and the
+ * elastic-averaging update with moving rate alpha for the asynchronous mode.
+ * The paper prints none of the formulas; the readings taken are stated at each
+ * function.
+ *
+ * Precision: the method's own precision is binary32 with a binary16 wire
+ * format, so the oracle computes in `float` with every operation rounded
+ * separately.  Build with -ffp-contract=off and without fast-math.
+ *
+ * Parity pins (tests/test_oracle_*.py): binary16 conversion against the
+ * IEEE-754 definition (exhaustive widen/narrow round trip, every tie between
+ * adjacent halves, range boundaries) and against numpy's own conversion; the
+ * sum against exact rational arithmetic and order-sensitive hand cases; the
+ * momentum update against its closed form and torch.optim.SGD on the CPU; the
+ * elastic update against conservation, midpoint and geometric-decay closed
+ * forms.  No function here is unpinned.
+ */
+#include <stdint.h>
+#include <string.h>
+
+enum { ORACLE_F32 = 0, ORACLE_F16 = 1 };
+enum { ORACLE_AVG = 0, ORACLE_SUM = 1 };
+
+static uint32_t bits_of(float f) { uint32_t u; memcpy(&u, &f, 4); return u; }
+static float float_of(uint32_t u) { float f; memcpy(&f, &u, 4); return f; }
+
+/*
+ * binary32 -> binary16, round to nearest, ties to even (the reduced-precision
+ * transfer of Section 3.2; the paper says only "half precision", IEEE's default
+ * rounding is the reading).  Works on the bit patterns:
+ *   - NaN stays NaN (sign kept, quiet bit set, top payload bits kept);
+ *   - magnitudes that round to 2^16 or more become infinity;
+ *   - results below 2^-14 are binary16 subnormals (gradual underflow);
+ *   - magnitudes of 2^-25 or less round to zero, sign kept.
+ */
+uint16_t oracle_f32_to_f16_bits(uint32_t x)
+{
+    uint16_t sign = (uint16_t)((x >> 16) & 0x8000u);
+    uint32_t mag = x & 0x7fffffffu;
+
+    if (mag >= 0x7f800000u) {                 /* infinity or NaN */
+        if (mag == 0x7f800000u) return (uint16_t)(sign | 0x7c00u);
+        return (uint16_t)(sign | 0x7e00u | ((mag >> 13) & 0x01ffu));
+    }
+    int32_t e = (int32_t)(mag >> 23) - 127;   /* unbiased exponent */
+    uint32_t m = mag & 0x007fffffu;
+
+    if (e >= 16) return (uint16_t)(sign | 0x7c00u);
+
+    if (e >= -14) {                           /* lands in the normal range */
+        uint32_t h = ((uint32_t)(e + 15) << 10) | (m >> 13);
+        uint32_t rest = m & 0x1fffu;          /* the 13 bits dropped */
+        if (rest > 0x1000u || (rest == 0x1000u && (h & 1u))) h += 1u;
+        /* a carry out of the mantissa bumps the exponent; 0x7c00 is infinity */
+        return (uint16_t)(sign | h);
+    }
+    if (e < -25) return sign;                 /* below half the smallest subnormal */
+
+    /* subnormal result: value = M * 2^(e-23) with M the 24-bit significand,
+     * to be expressed in units of 2^-24, so shift right by (-e - 1) bits. */
+    uint32_t M = m | 0x00800000u;
+    int shift = -e - 1;                       /* 14 .. 24 */
+    uint32_t h = M >> shift;
+    uint32_t rest = M & ((1u << shift) - 1u);
+    uint32_t half = 1u << (shift - 1);
+    if (rest > half || (rest == half && (h & 1u))) h += 1u;
+    return (uint16_t)(sign | h);              /* h == 0x0400 is the smallest normal */
+}
+
+/* binary16 -> binary32: exact for every input (Section 3.2: the sum is done at
+ * full precision, so received halves are widened first). */
+uint32_t oracle_f16_to_f32_bits(uint16_t h)
+{
+    uint32_t sign = ((uint32_t)h & 0x8000u) << 16;
+    uint32_t e = ((uint32_t)h >> 10) & 0x1fu;
+    uint32_t m = (uint32_t)h & 0x03ffu;
+
+    if (e == 0x1fu) return sign | 0x7f800000u | (m << 13);       /* inf / NaN */
+    if (e != 0) return sign | ((e + 112u) << 23) | (m << 13);     /* normal */
+    if (m == 0) return sign;                                      /* zero */
+    /* subnormal: m * 2^-24; normalise */
+    int p = 9;
+    while (!(m & (1u << p))) --p;            /* top set bit of m, 0..9 */
+    uint32_t frac = (m << (23 - p)) & 0x007fffffu;
+    return sign | ((uint32_t)(p - 24 + 127) << 23) | frac;
+}
+
+static float widen(uint16_t h) { return float_of(oracle_f16_to_f32_bits(h)); }
+static uint16_t narrow(float f) { return oracle_f32_to_f16_bits(bits_of(f)); }
+
+/* Step "pack": h[j] = half(g[j]) (Section 3.2, half-precision transfer). */
+void oracle_pack_fp16(const float *g, uint16_t *h, int64_t n)
+{
+    for (int64_t j = 0; j < n; ++j) h[j] = narrow(g[j]);
+}
+
+/* Step "unpack": exact widening of what was received. */
+void oracle_unpack_fp16(const uint16_t *h, float *g, int64_t n)
+{
+    for (int64_t j = 0; j < n; ++j) g[j] = widen(h[j]);
+}
+
+/*
+ * Step "sum" of Alltoall-sum-Allgather (Section 3.2), on one rank's slice:
+ *   s = c_0[j];  s = s + c_i[j] for i = 1 .. k-1, in worker order, in binary32,
+ *   rounded after every addition (halves are widened exactly first);
+ *   mode AVG: a = s / (float)k, one correctly rounded division (the average of
+ *   Section 4's weight averaging, and the 1/k of averaged gradients);
+ *   mode SUM: a = s (Section 4's summed updates, taken literally);
+ *   the result leaves as binary32, or rounded once to binary16 for the second
+ *   transfer leg.
+ * The running sum starts from c_0 itself, not from zero, so a lone -0 stays -0.
+ */
+int oracle_reduce_avg(int k, const void *const *contrib, int in_dtype,
+                      void *out, int out_dtype, int mode, int64_t n)
+{
+    if (k < 1 || !contrib || !out || n < 0) return 1;
+    if ((in_dtype != ORACLE_F32 && in_dtype != ORACLE_F16) ||
+        (out_dtype != ORACLE_F32 && out_dtype != ORACLE_F16) ||
+        (mode != ORACLE_AVG && mode != ORACLE_SUM)) return 1;
+    const float kf = (float)k;
+    for (int64_t j = 0; j < n; ++j) {
+        float s;
+        if (in_dtype == ORACLE_F32) {
+            s = ((const float *)contrib[0])[j];
+            for (int i = 1; i < k; ++i) s = s + ((const float *)contrib[i])[j];
+        } else {
+            s = widen(((const uint16_t *)contrib[0])[j]);
+            for (int i = 1; i < k; ++i) s = s + widen(((const uint16_t *)contrib[i])[j]);
+        }
+        float a = (mode == ORACLE_AVG) ? s / kf : s;
+        if (out_dtype == ORACLE_F32) ((float *)out)[j] = a;
+        else ((uint16_t *)out)[j] = narrow(a);
+    }
+    return 0;
+}
+
+/*
+ * Momentum SGD (Section 4 names the optimiser, prints no formula).  Reading:
+ * the form of the AlexNet paper the report builds on, weight decay folded into
+ * the gradient:
+ *      gg = a + wd * w
+ *      v' = mu * v - lr * gg
+ *      w' = w + v'
+ * `a` is the exchanged gradient, binary32 or binary16 (widened exactly).
+ * Every product, sum and difference is rounded to binary32 on its own.
+ */
+int oracle_sgd_momentum(const void *a, int a_dtype, float *w, float *v,
+                        float lr, float mu, float wd, int64_t n)
+{
+    if (!a || !w || !v || n < 0) return 1;
+    if (a_dtype != ORACLE_F32 && a_dtype != ORACLE_F16) return 1;
+    for (int64_t j = 0; j < n; ++j) {
+        float g = (a_dtype == ORACLE_F32) ? ((const float *)a)[j]
+                                          : widen(((const uint16_t *)a)[j]);
+        float dw = wd * w[j];
+        float gg = g + dw;
+        float mv = mu * v[j];
+        float lg = lr * gg;
+        float vn = mv - lg;
+        v[j] = vn;
+        w[j] = w[j] + vn;
+    }
+    return 0;
+}
+
+/*
+ * Elastic averaging between one worker's parameters x and the center c
+ * (Section 4, asynchronous mode, moving rate alpha; formula not printed).
+ * Reading: the symmetric elastic pull with the same alpha on both sides,
+ *      d = alpha * (x - c);   x' = x - d;   c' = c + d
+ * each operation rounded to binary32.  Workers meet the center one at a time,
+ * so a round is k calls in arrival order with c carried from one to the next.
+ */
+int oracle_easgd(float *x, float *c, float alpha, int64_t n)
+{
+    if (!x || !c || n < 0) return 1;
+    for (int64_t j = 0; j < n; ++j) {
+        float diff = x[j] - c[j];
+        float d = alpha * diff;
+        x[j] = x[j] - d;
+        c[j] = c[j] + d;
+    }
+    return 0;
+}
