@@ -1,0 +1,190 @@
+/*
+ * libpxchg -- the per-GPU arithmetic of a data-parallel parameter exchange,
+ * hand-written for AMD MI355X (gfx950).
+ *
+ * The operations are the ones the Theano-MPI report (arXiv 1605.08325) places
+ * on each GPU during an exchange:
+ *   - Section 3.2, "Alltoall-sum-Allgather": every rank receives the k ranks'
+ *     copies of its slice and sums them on the GPU; in the half-precision
+ *     variant the data travels as 16-bit floats and is summed at full precision;
+ *   - Section 4: what is exchanged (weights, momentum, raw gradients), summing
+ *     updates before descent versus averaging weights after it, momentum SGD as
+ *     the optimiser, and elastic averaging (EASGD, moving rate alpha) for the
+ *     asynchronous mode.
+ *
+ * Conventions
+ *   - Plain C ABI.  Every function returns a PXCHG_* status (0 = success) unless
+ *     stated otherwise; nothing throws, aborts or synchronises the device.
+ *   - "host" / "device" says where a pointer must live.  Data buffers are device
+ *     memory owned by the caller; the library owns only tables and buffer sets.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Work is enqueued on it and the call returns without waiting.
+ *   - A parameter set is a list of tensors (one device array per layer weight or
+ *     bias, as in Section 3.1).  A `pxchg_table` fixes the element count of each
+ *     tensor; a `pxchg_bufset` is one device pointer per tensor, all of one
+ *     element type (a worker's gradients, its packed copy, the parameters, ...).
+ *     Both are created once; steady-state calls do no per-tensor host work, no
+ *     allocation and no host-to-device copies, and each call is ONE kernel
+ *     launch however many tensors the set has.
+ *   - Pointers must be aligned to their element size.  16-byte alignment is the
+ *     fast path; other alignments are handled by a slower element-wise path.
+ *   - Inputs must not overlap outputs except where a function says "in place".
+ *   - All calls for one table must be made with the table's device current.
+ */
+#ifndef PXCHG_H
+#define PXCHG_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define PXCHG_MAX_K 64 /* most workers one call can combine */
+
+enum pxchg_status {
+    PXCHG_OK = 0,
+    PXCHG_ERR_INVALID_ARG = 1,    /* null pointer, bad enum, negative count, misaligned pointer */
+    PXCHG_ERR_SHAPE_MISMATCH = 2, /* buffer set belongs to another table, or wrong element type */
+    PXCHG_ERR_UNSUPPORTED = 3,    /* k outside 1..PXCHG_MAX_K, size beyond a stated limit */
+    PXCHG_ERR_NO_DEVICE = 4,      /* no usable GPU, or the table's device is not current */
+    PXCHG_ERR_RUNTIME = 5,        /* a HIP call failed (allocation, copy, launch) */
+    PXCHG_ERR_OUT_OF_RANGE = 6    /* a tensor does not fit inside the device allocation it points into */
+};
+
+enum pxchg_dtype { PXCHG_F32 = 0, PXCHG_F16 = 1 }; /* IEEE binary32 / binary16 */
+enum pxchg_mode { PXCHG_AVG = 0, PXCHG_SUM = 1 };  /* divide the sum by k, or not */
+
+/* Launch-shape controls (see pxchg_set_option). */
+enum pxchg_option {
+    PXCHG_OPT_CHUNK_ELEMS = 0,   /* elements per work chunk for tables created afterwards;
+                                    multiple of 2048, 2048..1048576 */
+    PXCHG_OPT_BLOCKS_PER_CU = 1, /* 0: one workgroup per chunk; n>0: n persistent workgroups per
+                                    compute unit, each looping over chunks */
+    PXCHG_OPT_CHECK_RANGES = 2,  /* 1 (default): pxchg_bufset_create verifies that each tensor lies
+                                    inside one device allocation */
+    PXCHG_OPT_NONTEMPORAL = 3    /* 1: streaming loads/stores carry the non-temporal hint */
+};
+
+typedef struct pxchg_table pxchg_table;
+typedef struct pxchg_bufset pxchg_bufset;
+
+/* Text for a status code; never NULL; static storage. */
+const char *pxchg_status_string(int status);
+
+/* Library version as major*10000 + minor*100 + patch. */
+int pxchg_version(void);
+
+/* Set / read a launch-shape control.  Process-wide, not thread-safe against
+ * concurrent calls into the library.  pxchg_get_option returns -1 for an
+ * unknown option. */
+int pxchg_set_option(int option, int64_t value);
+int64_t pxchg_get_option(int option);
+
+/*
+ * Host-only planning helper (no GPU needed): splits tensors of `counts[t]`
+ * elements into chunks of at most `chunk_elems` elements that never straddle
+ * two tensors; empty tensors produce no chunk.  Writes up to `cap` chunks into
+ * the three host arrays (any of which may be NULL when cap == 0) and the total
+ * number of chunks into *n_chunks.  This is the work list the kernels walk.
+ */
+int pxchg_plan_chunks(int n_tensors, const int64_t *counts /*host*/, int64_t chunk_elems,
+                      int64_t cap, int32_t *chunk_tensor /*host*/, int64_t *chunk_start /*host*/,
+                      int32_t *chunk_len /*host*/, int64_t *n_chunks /*host*/);
+
+/*
+ * Tensor table: element counts of the parameter set's tensors (Section 3.1: the
+ * model's parameters are arrays in GPU memory, one per weight or bias).
+ * `counts` is a host array of n_tensors non-negative counts (zero allowed).
+ * The table is bound to the device current at creation; the library keeps a
+ * device copy of the chunk list.  Destroying a table or a buffer set waits for
+ * the device to go idle first (launches may still be reading their device-side
+ * lists); these are the only calls that synchronise.
+ */
+int pxchg_table_create(int n_tensors, const int64_t *counts /*host*/, pxchg_table **out);
+int pxchg_table_destroy(pxchg_table *table);
+int64_t pxchg_table_total(const pxchg_table *table);   /* sum of counts; -1 if NULL */
+int pxchg_table_n_tensors(const pxchg_table *table);   /* -1 if NULL */
+int64_t pxchg_table_n_chunks(const pxchg_table *table); /* -1 if NULL */
+
+/*
+ * Buffer set: `ptrs` is a HOST array of n_tensors DEVICE pointers, tensor t
+ * holding counts[t] contiguous elements of `dtype`.  The pointer values are
+ * copied (host and device side); the memory they point to stays the caller's
+ * and must outlive every call that uses the set.  A NULL pointer is accepted
+ * only for an empty tensor.
+ */
+int pxchg_bufset_create(const pxchg_table *table, int dtype, const void *const *ptrs /*host array of device ptrs*/,
+                        pxchg_bufset **out);
+int pxchg_bufset_destroy(pxchg_bufset *set);
+
+/*
+ * Section 3.2, half-precision transfer, sending side: for each of k workers,
+ * dst[i][j] = binary16(src[i][j]), IEEE round-to-nearest-even, overflow to
+ * infinity, gradual underflow, NaN stays NaN.  src[i] are F32 sets, dst[i] F16
+ * sets, given as host arrays of k set handles.  One launch for all k workers
+ * and all tensors.
+ */
+int pxchg_pack_fp16(const pxchg_table *table, int k, const pxchg_bufset *const *src_f32 /*host*/,
+                    pxchg_bufset *const *dst_f16 /*host*/, void *stream);
+
+/* Receiving side of the same transfer: dst[i][j] = (binary32) src[i][j], exact. */
+int pxchg_unpack_fp16(const pxchg_table *table, int k, const pxchg_bufset *const *src_f16 /*host*/,
+                      pxchg_bufset *const *dst_f32 /*host*/, void *stream);
+
+/*
+ * Section 3.2, the sum step of Alltoall-sum-Allgather on this rank's slice, and
+ * Section 4's averaging: for every element j,
+ *     s = contrib[0][j]; s = s + contrib[i][j] for i = 1..k-1 (binary32, this order)
+ *     a = s / k (mode PXCHG_AVG, one correctly rounded division) or s (PXCHG_SUM)
+ *     out[j] = a, rounded to binary16 (nearest-even) if `out` is an F16 set.
+ * contrib[] is a host array of k sets, all F32 or all F16 (F16 is widened
+ * exactly before the sum).  `out` may be one of the contrib sets of the same
+ * element type (in place); otherwise it must not overlap them.
+ */
+int pxchg_reduce_avg(const pxchg_table *table, int k, const pxchg_bufset *const *contrib /*host*/,
+                     pxchg_bufset *out, int mode, void *stream);
+
+/*
+ * Section 4, momentum SGD on the exchanged gradient, in place on param and vel
+ * (both F32 sets):   gg = grad + wd * param;  vel = mu * vel - lr * gg;
+ *                    param = param + vel
+ * with every product and sum rounded to binary32 separately (no fused
+ * multiply-add).  `grad` is an F32 set or an F16 set (widened exactly, the
+ * unpack of the second transfer leg).
+ */
+int pxchg_sgd_momentum(const pxchg_table *table, const pxchg_bufset *grad, pxchg_bufset *param,
+                       pxchg_bufset *vel, float lr, float mu, float wd, void *stream);
+
+/*
+ * Section 4, asynchronous mode: one elastic-averaging meeting of a worker's
+ * parameters x with the center c, in place on both (F32 sets):
+ *     d = alpha * (x - c);  x = x - d;  c = c + d      (each op rounded to binary32)
+ */
+int pxchg_easgd(const pxchg_table *table, pxchg_bufset *x, pxchg_bufset *c, float alpha, void *stream);
+
+/*
+ * A whole round of the same: workers x[0], x[1], ..., x[k-1] (host array of k
+ * distinct F32 sets, in their order of arrival) meet the center one after the
+ * other.  Bit-identical to k calls of pxchg_easgd in that order.  Up to 8
+ * workers take one launch that reads and writes the center once; more workers
+ * take one launch per group of 8.
+ */
+int pxchg_easgd_round(const pxchg_table *table, int k, pxchg_bufset *const *x /*host*/, pxchg_bufset *c,
+                      float alpha, void *stream);
+
+/*
+ * pxchg_reduce_avg followed by pxchg_sgd_momentum in one launch, without the
+ * intermediate buffer.  `wire_dtype` says how the average would have travelled
+ * on the second transfer leg: PXCHG_F16 rounds it once to binary16 and widens it
+ * again before the update, PXCHG_F32 uses it as is.  Bit-identical to the two
+ * separate calls with an `out` set of that type.
+ */
+int pxchg_reduce_avg_sgd_momentum(const pxchg_table *table, int k, const pxchg_bufset *const *contrib /*host*/,
+                                  int mode, int wire_dtype, pxchg_bufset *param, pxchg_bufset *vel,
+                                  float lr, float mu, float wd, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PXCHG_H */

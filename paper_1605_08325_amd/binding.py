@@ -1,0 +1,262 @@
+"""ctypes binding of libpxchg.so.  Same names as the C ABI (include/pxchg.h);
+each function only converts its arguments and checks the returned status."""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import List, Optional, Sequence, Tuple
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libpxchg.so")
+
+AVG, SUM = 0, 1
+F32, F16 = 0, 1
+MAX_K = 64
+OPT_CHUNK_ELEMS, OPT_BLOCKS_PER_CU, OPT_CHECK_RANGES, OPT_NONTEMPORAL = 0, 1, 2, 3
+
+_i64 = ctypes.c_int64
+_vp = ctypes.c_void_p
+_int = ctypes.c_int
+_f = ctypes.c_float
+_pp = ctypes.POINTER(_vp)
+
+# name -> (restype, argtypes); also the list of symbols the header declares
+SIGNATURES = {
+    "pxchg_status_string": (ctypes.c_char_p, [_int]),
+    "pxchg_version": (_int, []),
+    "pxchg_set_option": (_int, [_int, _i64]),
+    "pxchg_get_option": (_i64, [_int]),
+    "pxchg_plan_chunks": (_int, [_int, ctypes.POINTER(_i64), _i64, _i64, ctypes.POINTER(ctypes.c_int32),
+                                 ctypes.POINTER(_i64), ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(_i64)]),
+    "pxchg_table_create": (_int, [_int, ctypes.POINTER(_i64), _pp]),
+    "pxchg_table_destroy": (_int, [_vp]),
+    "pxchg_table_total": (_i64, [_vp]),
+    "pxchg_table_n_tensors": (_int, [_vp]),
+    "pxchg_table_n_chunks": (_i64, [_vp]),
+    "pxchg_bufset_create": (_int, [_vp, _int, _pp, _pp]),
+    "pxchg_bufset_destroy": (_int, [_vp]),
+    "pxchg_pack_fp16": (_int, [_vp, _int, _pp, _pp, _vp]),
+    "pxchg_unpack_fp16": (_int, [_vp, _int, _pp, _pp, _vp]),
+    "pxchg_reduce_avg": (_int, [_vp, _int, _pp, _vp, _int, _vp]),
+    "pxchg_sgd_momentum": (_int, [_vp, _vp, _vp, _vp, _f, _f, _f, _vp]),
+    "pxchg_easgd": (_int, [_vp, _vp, _vp, _f, _vp]),
+    "pxchg_easgd_round": (_int, [_vp, _int, _pp, _vp, _f, _vp]),
+    "pxchg_reduce_avg_sgd_momentum": (_int, [_vp, _int, _pp, _int, _int, _vp, _vp, _f, _f, _f, _vp]),
+}
+
+
+class PxchgError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} (status {status})")
+
+
+_lib: Optional[ctypes.CDLL] = None
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load() -> ctypes.CDLL:
+    """Load libpxchg.so.  Raises if it has not been built: there is no fallback."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise ImportError(
+                f"{_LIB_PATH} is missing: build it with `python -m paper_1605_08325_amd.build` "
+                "(hipcc, gfx950); this package has no CPU or eager fallback")
+        lib = ctypes.CDLL(_LIB_PATH)
+        for name, (res, args) in SIGNATURES.items():
+            fn = getattr(lib, name)
+            fn.restype = res
+            fn.argtypes = args
+        _lib = lib
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return load().pxchg_status_string(int(status)).decode()
+
+
+def _check(status: int, where: str) -> None:
+    if status != 0:
+        raise PxchgError(status, where)
+
+
+def version() -> int:
+    return int(load().pxchg_version())
+
+
+def set_option(option: int, value: int) -> None:
+    _check(load().pxchg_set_option(option, value), "pxchg_set_option")
+
+
+def get_option(option: int) -> int:
+    return int(load().pxchg_get_option(option))
+
+
+def plan_chunks(counts: Sequence[int], chunk_elems: int) -> Tuple[List[int], List[int], List[int]]:
+    """Host-only: (tensor, start, len) of every chunk."""
+    lib = load()
+    n = len(counts)
+    c = (_i64 * max(n, 1))(*counts)
+    total = _i64(0)
+    _check(lib.pxchg_plan_chunks(n, c, chunk_elems, 0, None, None, None, ctypes.byref(total)), "pxchg_plan_chunks")
+    m = total.value
+    t = (ctypes.c_int32 * max(m, 1))()
+    s = (_i64 * max(m, 1))()
+    ln = (ctypes.c_int32 * max(m, 1))()
+    _check(lib.pxchg_plan_chunks(n, c, chunk_elems, m, t, s, ln, ctypes.byref(total)), "pxchg_plan_chunks")
+    return list(t[:m]), list(s[:m]), list(ln[:m])
+
+
+def _stream_ptr(stream) -> Optional[int]:
+    """None -> torch's current stream; an int is taken as a hipStream_t."""
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream or None
+    if isinstance(stream, int):
+        return stream or None
+    return stream.cuda_stream or None
+
+
+class Table:
+    """pxchg_table: element counts of the parameter set's tensors."""
+
+    def __init__(self, counts: Sequence[int]):
+        self.counts = [int(c) for c in counts]
+        self._h = _vp()
+        arr = (_i64 * max(len(self.counts), 1))(*self.counts)
+        _check(load().pxchg_table_create(len(self.counts), arr, ctypes.byref(self._h)), "pxchg_table_create")
+
+    @property
+    def handle(self):
+        return self._h
+
+    @property
+    def total(self) -> int:
+        return int(load().pxchg_table_total(self._h))
+
+    @property
+    def n_tensors(self) -> int:
+        return int(load().pxchg_table_n_tensors(self._h))
+
+    @property
+    def n_chunks(self) -> int:
+        return int(load().pxchg_table_n_chunks(self._h))
+
+    def bufset(self, tensors, dtype: Optional[int] = None) -> "BufSet":
+        return BufSet(self, tensors, dtype)
+
+    def close(self) -> None:
+        if self._h:
+            load().pxchg_table_destroy(self._h)
+            self._h = _vp()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class BufSet:
+    """pxchg_bufset: one device pointer per tensor.  `tensors` is a sequence of
+    torch CUDA tensors (kept alive by this object) or of raw device addresses
+    (then `dtype` is required)."""
+
+    def __init__(self, table: Table, tensors, dtype: Optional[int] = None):
+        self.table = table
+        self._keep = None
+        ptrs = []
+        if len(tensors) != len(table.counts):
+            raise ValueError("one tensor per table entry expected")
+        if all(isinstance(t, int) for t in tensors):
+            if dtype is None:
+                raise ValueError("dtype is required with raw addresses")
+            ptrs = [int(t) for t in tensors]
+        else:
+            import torch
+            want = None
+            for t, c in zip(tensors, table.counts):
+                if not t.is_cuda or not t.is_contiguous() or t.numel() != c:
+                    raise ValueError("contiguous CUDA tensors with the table's element counts expected")
+                d = {torch.float32: F32, torch.float16: F16}.get(t.dtype)
+                if d is None or (want is not None and d != want):
+                    raise ValueError("all tensors must be float32, or all float16")
+                want = d
+                ptrs.append(t.data_ptr() if c else 0)
+            if dtype is not None and dtype != want:
+                raise ValueError("dtype does not match the tensors")
+            dtype = want
+            self._keep = list(tensors)
+        self.dtype = dtype
+        self._h = _vp()
+        arr = (_vp * max(len(ptrs), 1))(*[p or None for p in ptrs])
+        _check(load().pxchg_bufset_create(table.handle, dtype, arr, ctypes.byref(self._h)), "pxchg_bufset_create")
+
+    @property
+    def handle(self):
+        return self._h
+
+    @property
+    def tensors(self):
+        return self._keep
+
+    def close(self) -> None:
+        if self._h:
+            load().pxchg_bufset_destroy(self._h)
+            self._h = _vp()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def _handles(sets: Sequence[BufSet]):
+    return (_vp * max(len(sets), 1))(*[s.handle for s in sets])
+
+
+def pack_fp16(table: Table, src_f32: Sequence[BufSet], dst_f16: Sequence[BufSet], stream=None) -> None:
+    if len(src_f32) != len(dst_f16):
+        raise ValueError("as many destinations as sources expected")
+    _check(load().pxchg_pack_fp16(table.handle, len(src_f32), _handles(src_f32), _handles(dst_f16),
+                                  _stream_ptr(stream)), "pxchg_pack_fp16")
+
+
+def unpack_fp16(table: Table, src_f16: Sequence[BufSet], dst_f32: Sequence[BufSet], stream=None) -> None:
+    if len(src_f16) != len(dst_f32):
+        raise ValueError("as many destinations as sources expected")
+    _check(load().pxchg_unpack_fp16(table.handle, len(src_f16), _handles(src_f16), _handles(dst_f32),
+                                    _stream_ptr(stream)), "pxchg_unpack_fp16")
+
+
+def reduce_avg(table: Table, contrib: Sequence[BufSet], out: BufSet, mode: int = AVG, stream=None) -> None:
+    _check(load().pxchg_reduce_avg(table.handle, len(contrib), _handles(contrib), out.handle, mode,
+                                   _stream_ptr(stream)), "pxchg_reduce_avg")
+
+
+def sgd_momentum(table: Table, grad: BufSet, param: BufSet, vel: BufSet, lr: float, mu: float,
+                 wd: float = 0.0, stream=None) -> None:
+    _check(load().pxchg_sgd_momentum(table.handle, grad.handle, param.handle, vel.handle, lr, mu, wd,
+                                     _stream_ptr(stream)), "pxchg_sgd_momentum")
+
+
+def easgd(table: Table, x: BufSet, c: BufSet, alpha: float, stream=None) -> None:
+    _check(load().pxchg_easgd(table.handle, x.handle, c.handle, alpha, _stream_ptr(stream)), "pxchg_easgd")
+
+
+def easgd_round(table: Table, x: Sequence[BufSet], c: BufSet, alpha: float, stream=None) -> None:
+    _check(load().pxchg_easgd_round(table.handle, len(x), _handles(x), c.handle, alpha, _stream_ptr(stream)),
+           "pxchg_easgd_round")
+
+
+def reduce_avg_sgd_momentum(table: Table, contrib: Sequence[BufSet], param: BufSet, vel: BufSet, lr: float,
+                            mu: float, wd: float = 0.0, mode: int = AVG, wire_dtype: int = F32,
+                            stream=None) -> None:
+    _check(load().pxchg_reduce_avg_sgd_momentum(table.handle, len(contrib), _handles(contrib), mode, wire_dtype,
+                                                param.handle, vel.handle, lr, mu, wd, _stream_ptr(stream)),
+           "pxchg_reduce_avg_sgd_momentum")

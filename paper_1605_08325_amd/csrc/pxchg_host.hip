@@ -1,0 +1,247 @@
+// Host-side objects of libpxchg: options, chunk planning, tensor tables and
+// buffer sets.  Everything here runs at set-up time; the per-exchange calls live
+// beside the kernels.
+#include <algorithm>
+#include <mutex>
+#include <new>
+
+#include "pxchg_internal.h"
+
+namespace {
+
+constexpr int64_t kMinChunk = 2048;
+constexpr int64_t kMaxChunk = 1 << 20;
+
+}  // namespace
+
+PxOptions &px_options() {
+    static PxOptions o = {/*chunk_elems=*/8192, /*blocks_per_cu=*/0, /*check_ranges=*/1, /*nontemporal=*/1};
+    return o;
+}
+
+int px_cu_count(int device) {
+    static std::mutex mu;
+    static std::vector<int> cache;
+    std::lock_guard<std::mutex> lock(mu);
+    if (device < 0) return 0;
+    if ((size_t)device >= cache.size()) cache.resize(device + 1, 0);
+    if (cache[device] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess || n <= 0) n = 256;
+        cache[device] = n;
+    }
+    return cache[device];
+}
+
+extern "C" {
+
+const char *pxchg_status_string(int status) {
+    switch (status) {
+        case PXCHG_OK: return "ok";
+        case PXCHG_ERR_INVALID_ARG: return "invalid argument";
+        case PXCHG_ERR_SHAPE_MISMATCH: return "buffer set does not match the table or has the wrong element type";
+        case PXCHG_ERR_UNSUPPORTED: return "unsupported size or worker count";
+        case PXCHG_ERR_NO_DEVICE: return "no usable GPU, or the table's device is not current";
+        case PXCHG_ERR_RUNTIME: return "HIP runtime call failed";
+        case PXCHG_ERR_OUT_OF_RANGE: return "tensor does not fit inside its device allocation";
+        default: return "unknown status";
+    }
+}
+
+int pxchg_version(void) { return 100; }
+
+int pxchg_set_option(int option, int64_t value) {
+    PxOptions &o = px_options();
+    switch (option) {
+        case PXCHG_OPT_CHUNK_ELEMS:
+            if (value < kMinChunk || value > kMaxChunk || value % kMinChunk) return PXCHG_ERR_INVALID_ARG;
+            o.chunk_elems = value;
+            return PXCHG_OK;
+        case PXCHG_OPT_BLOCKS_PER_CU:
+            if (value < 0 || value > 64) return PXCHG_ERR_INVALID_ARG;
+            o.blocks_per_cu = value;
+            return PXCHG_OK;
+        case PXCHG_OPT_CHECK_RANGES:
+            if (value != 0 && value != 1) return PXCHG_ERR_INVALID_ARG;
+            o.check_ranges = value;
+            return PXCHG_OK;
+        case PXCHG_OPT_NONTEMPORAL:
+            if (value != 0 && value != 1) return PXCHG_ERR_INVALID_ARG;
+            o.nontemporal = value;
+            return PXCHG_OK;
+        default:
+            return PXCHG_ERR_INVALID_ARG;
+    }
+}
+
+int64_t pxchg_get_option(int option) {
+    const PxOptions &o = px_options();
+    switch (option) {
+        case PXCHG_OPT_CHUNK_ELEMS: return o.chunk_elems;
+        case PXCHG_OPT_BLOCKS_PER_CU: return o.blocks_per_cu;
+        case PXCHG_OPT_CHECK_RANGES: return o.check_ranges;
+        case PXCHG_OPT_NONTEMPORAL: return o.nontemporal;
+        default: return -1;
+    }
+}
+
+int pxchg_plan_chunks(int n_tensors, const int64_t *counts, int64_t chunk_elems, int64_t cap,
+                      int32_t *chunk_tensor, int64_t *chunk_start, int32_t *chunk_len, int64_t *n_chunks) {
+    if (n_tensors < 1 || !counts || !n_chunks || cap < 0) return PXCHG_ERR_INVALID_ARG;
+    if (chunk_elems < kMinChunk || chunk_elems > kMaxChunk || chunk_elems % kMinChunk) return PXCHG_ERR_INVALID_ARG;
+    if (cap > 0 && (!chunk_tensor || !chunk_start || !chunk_len)) return PXCHG_ERR_INVALID_ARG;
+    int64_t n = 0;
+    for (int t = 0; t < n_tensors; ++t) {
+        if (counts[t] < 0) return PXCHG_ERR_INVALID_ARG;
+        for (int64_t s = 0; s < counts[t]; s += chunk_elems) {
+            if (n < cap) {
+                chunk_tensor[n] = t;
+                chunk_start[n] = s;
+                chunk_len[n] = (int32_t)std::min<int64_t>(chunk_elems, counts[t] - s);
+            }
+            ++n;
+        }
+    }
+    *n_chunks = n;
+    return PXCHG_OK;
+}
+
+int pxchg_table_create(int n_tensors, const int64_t *counts, pxchg_table **out) {
+    if (!out) return PXCHG_ERR_INVALID_ARG;
+    *out = nullptr;
+    if (n_tensors < 1 || n_tensors > (1 << 24) || !counts) return PXCHG_ERR_INVALID_ARG;
+    int64_t total = 0;
+    for (int t = 0; t < n_tensors; ++t) {
+        if (counts[t] < 0) return PXCHG_ERR_INVALID_ARG;
+        if (counts[t] > ((int64_t)1 << 40) || total > ((int64_t)1 << 40)) return PXCHG_ERR_UNSUPPORTED;
+        total += counts[t];
+    }
+    const int64_t chunk_elems = px_options().chunk_elems;
+    int64_t n_chunks = 0;
+    int rc = pxchg_plan_chunks(n_tensors, counts, chunk_elems, 0, nullptr, nullptr, nullptr, &n_chunks);
+    if (rc != PXCHG_OK) return rc;
+    // the grid (times up to PXCHG_MAX_K workers) must stay a 31-bit number
+    if (n_chunks > ((int64_t)1 << 24)) return PXCHG_ERR_UNSUPPORTED;
+
+    int device = -1;
+    if (hipGetDevice(&device) != hipSuccess || device < 0) {
+        (void)hipGetLastError();
+        return PXCHG_ERR_NO_DEVICE;
+    }
+
+    pxchg_table *t = new (std::nothrow) pxchg_table();
+    if (!t) return PXCHG_ERR_RUNTIME;
+    t->magic = PX_TABLE_MAGIC;
+    t->device = device;
+    t->n_tensors = n_tensors;
+    t->total = total;
+    t->chunk_elems = chunk_elems;
+    t->n_chunks = n_chunks;
+    t->counts.assign(counts, counts + n_tensors);
+    t->d_chunks = nullptr;
+
+    if (n_chunks > 0) {
+        std::vector<PxChunk> h(n_chunks);
+        int64_t n = 0;
+        for (int i = 0; i < n_tensors; ++i)
+            for (int64_t s = 0; s < counts[i]; s += chunk_elems) {
+                h[n].start = s;
+                h[n].len = (int32_t)std::min<int64_t>(chunk_elems, counts[i] - s);
+                h[n].tensor = i;
+                ++n;
+            }
+        if (hipMalloc((void **)&t->d_chunks, n_chunks * sizeof(PxChunk)) != hipSuccess ||
+            hipMemcpy(t->d_chunks, h.data(), n_chunks * sizeof(PxChunk), hipMemcpyHostToDevice) != hipSuccess) {
+            (void)hipGetLastError();
+            if (t->d_chunks) (void)hipFree(t->d_chunks);
+            t->magic = 0;
+            delete t;
+            return PXCHG_ERR_RUNTIME;
+        }
+    }
+    *out = t;
+    return PXCHG_OK;
+}
+
+int pxchg_table_destroy(pxchg_table *table) {
+    if (!table) return PXCHG_OK;
+    if (!px_valid(table)) return PXCHG_ERR_INVALID_ARG;
+    int rc = PXCHG_OK;
+    (void)hipDeviceSynchronize();  // launches still reading the chunk list must finish first
+    if (table->d_chunks && hipFree(table->d_chunks) != hipSuccess) {
+        (void)hipGetLastError();
+        rc = PXCHG_ERR_RUNTIME;
+    }
+    table->magic = 0;
+    delete table;
+    return rc;
+}
+
+int64_t pxchg_table_total(const pxchg_table *table) { return px_valid(table) ? table->total : -1; }
+int pxchg_table_n_tensors(const pxchg_table *table) { return px_valid(table) ? table->n_tensors : -1; }
+int64_t pxchg_table_n_chunks(const pxchg_table *table) { return px_valid(table) ? table->n_chunks : -1; }
+
+int pxchg_bufset_create(const pxchg_table *table, int dtype, const void *const *ptrs, pxchg_bufset **out) {
+    if (!out) return PXCHG_ERR_INVALID_ARG;
+    *out = nullptr;
+    if (!px_valid(table) || !ptrs) return PXCHG_ERR_INVALID_ARG;
+    if (dtype != PXCHG_F32 && dtype != PXCHG_F16) return PXCHG_ERR_INVALID_ARG;
+    const size_t es = dtype == PXCHG_F32 ? 4 : 2;
+    int device = -1;
+    if (hipGetDevice(&device) != hipSuccess || device != table->device) {
+        (void)hipGetLastError();
+        return PXCHG_ERR_NO_DEVICE;
+    }
+    for (int t = 0; t < table->n_tensors; ++t) {
+        const int64_t n = table->counts[t];
+        if (n == 0) continue;
+        const uintptr_t a = (uintptr_t)ptrs[t];
+        if (a == 0 || a % es) return PXCHG_ERR_INVALID_ARG;
+        if (px_options().check_ranges) {
+            // The kernels trust counts[t]; make sure the whole tensor lies inside one
+            // device allocation so that no launch can touch unmapped memory.
+            hipDeviceptr_t base = nullptr;
+            size_t size = 0;
+            if (hipMemGetAddressRange(&base, &size, (hipDeviceptr_t)ptrs[t]) != hipSuccess) {
+                (void)hipGetLastError();
+                return PXCHG_ERR_OUT_OF_RANGE;
+            }
+            const uintptr_t b = (uintptr_t)base;
+            if (a < b || a + (uintptr_t)n * es > b + size) return PXCHG_ERR_OUT_OF_RANGE;
+        }
+    }
+    pxchg_bufset *s = new (std::nothrow) pxchg_bufset();
+    if (!s) return PXCHG_ERR_RUNTIME;
+    s->magic = PX_BUFSET_MAGIC;
+    s->table = table;
+    s->dtype = dtype;
+    s->h_ptrs.assign(ptrs, ptrs + table->n_tensors);
+    s->d_ptrs = nullptr;
+    const size_t bytes = (size_t)table->n_tensors * sizeof(void *);
+    if (hipMalloc((void **)&s->d_ptrs, bytes) != hipSuccess ||
+        hipMemcpy(s->d_ptrs, s->h_ptrs.data(), bytes, hipMemcpyHostToDevice) != hipSuccess) {
+        (void)hipGetLastError();
+        if (s->d_ptrs) (void)hipFree(s->d_ptrs);
+        s->magic = 0;
+        delete s;
+        return PXCHG_ERR_RUNTIME;
+    }
+    *out = s;
+    return PXCHG_OK;
+}
+
+int pxchg_bufset_destroy(pxchg_bufset *set) {
+    if (!set) return PXCHG_OK;
+    if (!px_valid(set)) return PXCHG_ERR_INVALID_ARG;
+    int rc = PXCHG_OK;
+    (void)hipDeviceSynchronize();  // launches still reading the pointer table must finish first
+    if (set->d_ptrs && hipFree(set->d_ptrs) != hipSuccess) {
+        (void)hipGetLastError();
+        rc = PXCHG_ERR_RUNTIME;
+    }
+    set->magic = 0;
+    delete set;
+    return rc;
+}
+
+}  // extern "C"

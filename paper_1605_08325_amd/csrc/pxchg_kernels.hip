@@ -1,0 +1,806 @@
+// gfx950 kernels of libpxchg and the C-ABI calls that launch them.
+//
+// Every operation here is element-wise over a parameter set that is scattered
+// over many separately allocated tensors, and every one is bound by HBM
+// bandwidth (a handful of flops per 18..48 bytes moved).  So the design is about
+// memory traffic only:
+//   * one launch per call: workgroups walk a device-resident list of chunks
+//     (tensor, start, length), so 16 tensors or 116 cost the same single launch;
+//   * each lane moves 16-byte vectors (8 halves or 4 floats per load/store) and
+//     issues all loads of a step before the first use, so a lane keeps up to
+//     k x 16 bytes in flight;
+//   * no LDS staging and no cross-lane traffic: lanes are independent, which
+//     also makes the fixed worker order of the sum trivially bit-exact;
+//   * streaming accesses may carry the non-temporal hint (nothing is reused
+//     inside one launch).
+// There is no matrix-core work here on purpose: there is no contraction.
+//
+// Floating point: compiled with -ffp-contract=off and `fp contract(off)` below,
+// so every product and sum is rounded to binary32 on its own, exactly as the
+// definition of each operation in pxchg.h states.  binary32 -> binary16 uses the
+// hardware convert under the default round-to-nearest-even mode with binary16
+// denormals enabled; the packed round-toward-zero convert is never used.
+#include <type_traits>
+
+#include "pxchg_internal.h"
+
+#pragma clang fp contract(off)
+
+namespace {
+
+constexpr int BLOCK = 256;  // four wave64 per workgroup
+constexpr int UNIT = 8;     // elements one lane handles per vector step
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+
+// Data pointers come out of pointer tables in memory, so the compiler cannot
+// know they are global addresses; say so, to get global (not flat) memory
+// instructions.  The pointer tables themselves are read-only for the lifetime
+// of a launch and uniform per workgroup: reading them through the constant
+// address space turns those reads into scalar loads.
+#define PX_GLOBAL __attribute__((address_space(1)))
+#define PX_CONST __attribute__((address_space(4)))
+
+template <typename T>
+__device__ __forceinline__ T *table_ptr(const void *const *table, int tensor) {
+    return (T *)((const void *const PX_CONST *)table)[tensor];
+}
+template <typename T>
+__device__ __forceinline__ T *table_ptr(void *const *table, int tensor) {
+    return (T *)((void *const PX_CONST *)table)[tensor];
+}
+
+struct F8 {
+    float v[UNIT];
+};
+
+template <bool NT, typename V>
+__device__ __forceinline__ V ldv(const PX_GLOBAL V *p) {
+    if constexpr (NT)
+        return __builtin_nontemporal_load(p);
+    else
+        return *p;
+}
+template <bool NT, typename V>
+__device__ __forceinline__ void stv(PX_GLOBAL V *p, V x) {
+    if constexpr (NT)
+        __builtin_nontemporal_store(x, p);
+    else
+        *p = x;
+}
+
+// 8 consecutive elements as binary32; p is 16-byte aligned.
+template <bool NT>
+__device__ __forceinline__ F8 load8(const float *p) {
+    const f32x4 a = ldv<NT>((const PX_GLOBAL f32x4 *)p);
+    const f32x4 b = ldv<NT>((const PX_GLOBAL f32x4 *)p + 1);
+    F8 r;
+    r.v[0] = a.x; r.v[1] = a.y; r.v[2] = a.z; r.v[3] = a.w;
+    r.v[4] = b.x; r.v[5] = b.y; r.v[6] = b.z; r.v[7] = b.w;
+    return r;
+}
+template <bool NT>
+__device__ __forceinline__ F8 load8(const _Float16 *p) {
+    const f16x8 h = ldv<NT>((const PX_GLOBAL f16x8 *)p);
+    F8 r;
+#pragma unroll
+    for (int i = 0; i < UNIT; ++i) r.v[i] = (float)h[i];  // exact widening
+    return r;
+}
+template <bool NT>
+__device__ __forceinline__ void store8(float *p, const F8 &x) {
+    f32x4 a, b;
+    a.x = x.v[0]; a.y = x.v[1]; a.z = x.v[2]; a.w = x.v[3];
+    b.x = x.v[4]; b.y = x.v[5]; b.z = x.v[6]; b.w = x.v[7];
+    stv<NT>((PX_GLOBAL f32x4 *)p, a);
+    stv<NT>((PX_GLOBAL f32x4 *)p + 1, b);
+}
+template <bool NT>
+__device__ __forceinline__ void store8(_Float16 *p, const F8 &x) {
+    f16x8 h;
+#pragma unroll
+    for (int i = 0; i < UNIT; ++i) h[i] = (_Float16)x.v[i];  // round to nearest even
+    stv<NT>((PX_GLOBAL f16x8 *)p, h);
+}
+__device__ __forceinline__ float load1(const float *p) { return *(const PX_GLOBAL float *)p; }
+__device__ __forceinline__ float load1(const _Float16 *p) { return (float)*(const PX_GLOBAL _Float16 *)p; }
+__device__ __forceinline__ void store1(float *p, float x) { *(PX_GLOBAL float *)p = x; }
+__device__ __forceinline__ void store1(_Float16 *p, float x) { *(PX_GLOBAL _Float16 *)p = (_Float16)x; }
+
+// Number of leading elements after which `a` is 16-byte aligned.
+__device__ __forceinline__ int head_of(uintptr_t a, int es) { return (int)(((16u - (unsigned)(a & 15u)) & 15u) / (unsigned)es); }
+__device__ __forceinline__ bool aligned_after(uintptr_t a, int es, int head) { return ((a + (uintptr_t)head * es) & 15u) == 0; }
+
+// Walks one chunk: an element-wise head until every operand is 16-byte aligned,
+// 8-element vector steps, an element-wise tail.  `head` < 0 means the operands
+// cannot be aligned together and the whole chunk goes element by element.
+template <class Op>
+__device__ __forceinline__ void run_chunk(Op &op, int len, int head) {
+    const int tid = threadIdx.x;
+    if (head < 0 || head > len) {
+        for (int i = tid; i < len; i += BLOCK) op.scalar(i);
+        return;
+    }
+    for (int i = tid; i < head; i += BLOCK) op.scalar(i);
+    const int nvec = (len - head) / UNIT;
+    for (int u = tid; u < nvec; u += BLOCK) op.vector(head + u * UNIT);
+    for (int i = head + nvec * UNIT + tid; i < len; i += BLOCK) op.scalar(i);
+}
+
+__device__ __forceinline__ void scale_sum8(F8 &s, int use_div, float kf, float scale);
+__device__ __forceinline__ float scale_sum(float s, int use_div, float kf, float scale) {
+    // AVG with k a power of two and SUM multiply by an exactly representable
+    // factor (1/k or 1), which gives the correctly rounded quotient; other k take
+    // the correctly rounded division itself.
+    return use_div ? s / kf : s * scale;
+}
+
+__device__ __forceinline__ void scale_sum8(F8 &s, int use_div, float kf, float scale) {
+    if (use_div) {  // uniform branch
+#pragma unroll
+        for (int e = 0; e < UNIT; ++e) s.v[e] = s.v[e] / kf;
+    } else {
+#pragma unroll
+        for (int e = 0; e < UNIT; ++e) s.v[e] = s.v[e] * scale;
+    }
+}
+
+__device__ __forceinline__ void momentum_step(float g, float &w, float &v, float lr, float mu, float wd) {
+    const float dw = wd * w;
+    const float gg = g + dw;
+    const float mv = mu * v;
+    const float lg = lr * gg;
+    v = mv - lg;
+    w = w + v;
+}
+
+__device__ __forceinline__ void elastic_step(float &x, float &c, float alpha) {
+    const float diff = x - c;
+    const float d = alpha * diff;
+    x = x - d;
+    c = c + d;
+}
+
+// ---------------------------------------------------------------- pack / unpack
+
+struct ConvertArgs {
+    const void *const *src[PXCHG_MAX_K];
+    void *const *dst[PXCHG_MAX_K];
+};
+
+template <typename TI, typename TO, bool NT>
+struct ConvertOp {
+    const TI *src;
+    TO *dst;
+    __device__ __forceinline__ void scalar(int i) { store1(dst + i, load1(src + i)); }
+    __device__ __forceinline__ void vector(int i) { store8<NT>(dst + i, load8<NT>(src + i)); }
+};
+
+// Converts every tensor of every worker between binary32 and binary16.  The
+// grid covers k x n_chunks virtual chunks, worker-major.
+template <typename TI, typename TO, bool NT>
+__global__ __launch_bounds__(BLOCK) void pxchg_convert_kernel(const PxChunk *__restrict__ chunks, int n_chunks,
+                                                              int64_t n_virtual, ConvertArgs args) {
+    for (int64_t vc = blockIdx.x; vc < n_virtual; vc += gridDim.x) {
+        const int w = (int)(vc / n_chunks);
+        const PxChunk ch = chunks[vc - (int64_t)w * n_chunks];
+        ConvertOp<TI, TO, NT> op;
+        op.src = table_ptr<const TI>(args.src[w], ch.tensor) + ch.start;
+        op.dst = table_ptr<TO>(args.dst[w], ch.tensor) + ch.start;
+        int head = head_of((uintptr_t)op.dst, sizeof(TO));
+        if (!aligned_after((uintptr_t)op.src, sizeof(TI), head)) head = -1;
+        run_chunk(op, ch.len, head);
+    }
+}
+
+// ---------------------------------------------------------------- reduce + average
+
+struct ReduceArgs {
+    const void *const *contrib[PXCHG_MAX_K];
+    void *const *out;
+    int k;
+    int use_div;
+    float kf;
+    float scale;
+};
+
+template <int K, typename TI, typename TO, bool NT>
+struct ReduceOp {
+    const TI *src[K];
+    TO *dst;
+    int use_div;
+    float kf, scale;
+    __device__ __forceinline__ void scalar(int i) {
+        float s = load1(src[0] + i);
+#pragma unroll
+        for (int w = 1; w < K; ++w) s = s + load1(src[w] + i);
+        store1(dst + i, scale_sum(s, use_div, kf, scale));
+    }
+    __device__ __forceinline__ void vector(int i) {
+        F8 c[K];
+#pragma unroll
+        for (int w = 0; w < K; ++w) c[w] = load8<NT>(src[w] + i);  // all loads first
+        F8 s = c[0];
+#pragma unroll
+        for (int w = 1; w < K; ++w)
+#pragma unroll
+            for (int e = 0; e < UNIT; ++e) s.v[e] = s.v[e] + c[w].v[e];  // worker order
+        scale_sum8(s, use_div, kf, scale);
+        store8<NT>(dst + i, s);
+    }
+};
+
+// Any k up to PXCHG_MAX_K: the chunk's k source pointers sit in LDS.
+template <typename TI, typename TO, bool NT>
+struct ReduceOpAnyK {
+    const TI *const *src;  // LDS
+    TO *dst;
+    int k, use_div;
+    float kf, scale;
+    __device__ __forceinline__ void scalar(int i) {
+        float s = load1(src[0] + i);
+        for (int w = 1; w < k; ++w) s = s + load1(src[w] + i);
+        store1(dst + i, scale_sum(s, use_div, kf, scale));
+    }
+    __device__ __forceinline__ void vector(int i) {
+        F8 s = load8<NT>(src[0] + i);
+        int w = 1;
+        for (; w + 4 <= k; w += 4) {
+            F8 c[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) c[q] = load8<NT>(src[w + q] + i);
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+#pragma unroll
+                for (int e = 0; e < UNIT; ++e) s.v[e] = s.v[e] + c[q].v[e];
+        }
+        for (; w < k; ++w) {
+            const F8 c = load8<NT>(src[w] + i);
+#pragma unroll
+            for (int e = 0; e < UNIT; ++e) s.v[e] = s.v[e] + c.v[e];
+        }
+        scale_sum8(s, use_div, kf, scale);
+        store8<NT>(dst + i, s);
+    }
+};
+
+template <int K, typename TI, typename TO, bool NT>
+__global__ __launch_bounds__(BLOCK) void pxchg_reduce_avg_kernel(const PxChunk *__restrict__ chunks, int n_chunks,
+                                                                 ReduceArgs args) {
+    for (int c = blockIdx.x; c < n_chunks; c += gridDim.x) {
+        const PxChunk ch = chunks[c];
+        ReduceOp<K, TI, TO, NT> op;
+        op.dst = table_ptr<TO>(args.out, ch.tensor) + ch.start;
+        op.use_div = args.use_div;
+        op.kf = args.kf;
+        op.scale = args.scale;
+        int head = head_of((uintptr_t)op.dst, sizeof(TO));
+#pragma unroll
+        for (int w = 0; w < K; ++w) {
+            op.src[w] = table_ptr<const TI>(args.contrib[w], ch.tensor) + ch.start;
+            if (!aligned_after((uintptr_t)op.src[w], sizeof(TI), head)) head = -1;
+        }
+        run_chunk(op, ch.len, head);
+    }
+}
+
+template <typename TI, typename TO, bool NT>
+__global__ __launch_bounds__(BLOCK) void pxchg_reduce_avg_anyk_kernel(const PxChunk *__restrict__ chunks, int n_chunks,
+                                                                      ReduceArgs args) {
+    __shared__ const TI *sp[PXCHG_MAX_K];
+    __shared__ int s_head;
+    for (int c = blockIdx.x; c < n_chunks; c += gridDim.x) {
+        const PxChunk ch = chunks[c];
+        ReduceOpAnyK<TI, TO, NT> op;
+        op.dst = table_ptr<TO>(args.out, ch.tensor) + ch.start;
+        op.k = args.k;
+        op.use_div = args.use_div;
+        op.kf = args.kf;
+        op.scale = args.scale;
+        const int head0 = head_of((uintptr_t)op.dst, sizeof(TO));
+        __syncthreads();  // previous chunk's readers are done with sp
+        if (threadIdx.x == 0) s_head = head0;
+        __syncthreads();
+        if ((int)threadIdx.x < args.k) {
+            const TI *p = table_ptr<const TI>(args.contrib[threadIdx.x], ch.tensor) + ch.start;
+            sp[threadIdx.x] = p;
+            if (!aligned_after((uintptr_t)p, sizeof(TI), head0)) s_head = -1;  // benign race: all write -1
+        }
+        __syncthreads();
+        op.src = sp;
+        run_chunk(op, ch.len, s_head);
+    }
+}
+
+// ---------------------------------------------------------------- momentum SGD
+
+struct UpdateArgs {
+    const void *const *grad;
+    void *const *param;
+    void *const *vel;
+    float lr, mu, wd;
+};
+
+template <typename TG, bool NT>
+struct UpdateOp {
+    const TG *g;
+    float *w, *v;
+    float lr, mu, wd;
+    __device__ __forceinline__ void scalar(int i) {
+        float wi = load1(w + i), vi = load1(v + i);
+        momentum_step(load1(g + i), wi, vi, lr, mu, wd);
+        store1(v + i, vi);
+        store1(w + i, wi);
+    }
+    __device__ __forceinline__ void vector(int i) {
+        const F8 a = load8<NT>(g + i);
+        F8 ww = load8<NT>(w + i);
+        F8 vv = load8<NT>(v + i);
+#pragma unroll
+        for (int e = 0; e < UNIT; ++e) momentum_step(a.v[e], ww.v[e], vv.v[e], lr, mu, wd);
+        store8<NT>(v + i, vv);
+        store8<NT>(w + i, ww);
+    }
+};
+
+template <typename TG, bool NT>
+__global__ __launch_bounds__(BLOCK) void pxchg_sgd_momentum_kernel(const PxChunk *__restrict__ chunks, int n_chunks,
+                                                                   UpdateArgs args) {
+    for (int c = blockIdx.x; c < n_chunks; c += gridDim.x) {
+        const PxChunk ch = chunks[c];
+        UpdateOp<TG, NT> op;
+        op.g = table_ptr<const TG>(args.grad, ch.tensor) + ch.start;
+        op.w = table_ptr<float>(args.param, ch.tensor) + ch.start;
+        op.v = table_ptr<float>(args.vel, ch.tensor) + ch.start;
+        op.lr = args.lr;
+        op.mu = args.mu;
+        op.wd = args.wd;
+        int head = head_of((uintptr_t)op.g, sizeof(TG));
+        if (!aligned_after((uintptr_t)op.w, 4, head) || !aligned_after((uintptr_t)op.v, 4, head)) head = -1;
+        run_chunk(op, ch.len, head);
+    }
+}
+
+// ---------------------------------------------------------------- fused reduce + update
+
+struct FusedArgs {
+    const void *const *contrib[PXCHG_MAX_K];
+    void *const *param;
+    void *const *vel;
+    int k;
+    int use_div;
+    float kf, scale;
+    float lr, mu, wd;
+};
+
+template <int K, typename TI, bool WIRE16, bool NT>
+struct FusedOp {
+    const TI *src[K];
+    float *w, *v;
+    int use_div;
+    float kf, scale, lr, mu, wd;
+    __device__ __forceinline__ static float wire(float a) {
+        if constexpr (WIRE16)
+            return (float)(_Float16)a;  // what the second transfer leg would have carried
+        else
+            return a;
+    }
+    __device__ __forceinline__ void scalar(int i) {
+        float s = load1(src[0] + i);
+#pragma unroll
+        for (int q = 1; q < K; ++q) s = s + load1(src[q] + i);
+        float wi = load1(w + i), vi = load1(v + i);
+        momentum_step(wire(scale_sum(s, use_div, kf, scale)), wi, vi, lr, mu, wd);
+        store1(v + i, vi);
+        store1(w + i, wi);
+    }
+    __device__ __forceinline__ void vector(int i) {
+        F8 c[K];
+#pragma unroll
+        for (int q = 0; q < K; ++q) c[q] = load8<NT>(src[q] + i);
+        F8 ww = load8<NT>(w + i);
+        F8 vv = load8<NT>(v + i);
+        F8 s = c[0];
+#pragma unroll
+        for (int q = 1; q < K; ++q)
+#pragma unroll
+            for (int e = 0; e < UNIT; ++e) s.v[e] = s.v[e] + c[q].v[e];
+        scale_sum8(s, use_div, kf, scale);
+#pragma unroll
+        for (int e = 0; e < UNIT; ++e) momentum_step(wire(s.v[e]), ww.v[e], vv.v[e], lr, mu, wd);
+        store8<NT>(v + i, vv);
+        store8<NT>(w + i, ww);
+    }
+};
+
+template <int K, typename TI, bool WIRE16, bool NT>
+__global__ __launch_bounds__(BLOCK) void pxchg_reduce_avg_sgd_momentum_kernel(const PxChunk *__restrict__ chunks,
+                                                                              int n_chunks, FusedArgs args) {
+    for (int c = blockIdx.x; c < n_chunks; c += gridDim.x) {
+        const PxChunk ch = chunks[c];
+        FusedOp<K, TI, WIRE16, NT> op;
+        op.w = table_ptr<float>(args.param, ch.tensor) + ch.start;
+        op.v = table_ptr<float>(args.vel, ch.tensor) + ch.start;
+        op.use_div = args.use_div;
+        op.kf = args.kf;
+        op.scale = args.scale;
+        op.lr = args.lr;
+        op.mu = args.mu;
+        op.wd = args.wd;
+        op.src[0] = table_ptr<const TI>(args.contrib[0], ch.tensor) + ch.start;
+        int head = head_of((uintptr_t)op.src[0], sizeof(TI));
+#pragma unroll
+        for (int q = 1; q < K; ++q) {
+            op.src[q] = table_ptr<const TI>(args.contrib[q], ch.tensor) + ch.start;
+            if (!aligned_after((uintptr_t)op.src[q], sizeof(TI), head)) head = -1;
+        }
+        if (!aligned_after((uintptr_t)op.w, 4, head) || !aligned_after((uintptr_t)op.v, 4, head)) head = -1;
+        run_chunk(op, ch.len, head);
+    }
+}
+
+// ---------------------------------------------------------------- elastic averaging
+
+struct ElasticArgs {
+    void *const *x[PXCHG_MAX_K];
+    void *const *c;
+    int k;
+    float alpha;
+};
+
+template <int K, bool NT>
+struct ElasticOp {
+    float *x[K];
+    float *c;
+    float alpha;
+    __device__ __forceinline__ void scalar(int i) {
+        float ci = load1(c + i);
+#pragma unroll
+        for (int q = 0; q < K; ++q) {
+            float xi = load1(x[q] + i);
+            elastic_step(xi, ci, alpha);
+            store1(x[q] + i, xi);
+        }
+        store1(c + i, ci);
+    }
+    __device__ __forceinline__ void vector(int i) {
+        F8 xs[K];
+#pragma unroll
+        for (int q = 0; q < K; ++q) xs[q] = load8<NT>(x[q] + i);
+        F8 cc = load8<NT>(c + i);
+#pragma unroll
+        for (int q = 0; q < K; ++q) {  // arrival order: the center carries over
+#pragma unroll
+            for (int e = 0; e < UNIT; ++e) elastic_step(xs[q].v[e], cc.v[e], alpha);
+            store8<NT>(x[q] + i, xs[q]);
+        }
+        store8<NT>(c + i, cc);
+    }
+};
+
+template <int K, bool NT>
+__global__ __launch_bounds__(BLOCK) void pxchg_easgd_kernel(const PxChunk *__restrict__ chunks, int n_chunks,
+                                                            ElasticArgs args) {
+    for (int c = blockIdx.x; c < n_chunks; c += gridDim.x) {
+        const PxChunk ch = chunks[c];
+        ElasticOp<K, NT> op;
+        op.c = table_ptr<float>(args.c, ch.tensor) + ch.start;
+        op.alpha = args.alpha;
+        int head = head_of((uintptr_t)op.c, 4);
+#pragma unroll
+        for (int q = 0; q < K; ++q) {
+            op.x[q] = table_ptr<float>(args.x[q], ch.tensor) + ch.start;
+            if (!aligned_after((uintptr_t)op.x[q], 4, head)) head = -1;
+        }
+        run_chunk(op, ch.len, head);
+    }
+}
+
+// ---------------------------------------------------------------- launch helpers
+
+struct Launch {
+    dim3 grid;
+    bool nt;
+};
+
+Launch launch_shape(const pxchg_table *t, int64_t n_virtual) {
+    const PxOptions &o = px_options();
+    int64_t g = n_virtual;
+    if (o.blocks_per_cu > 0) g = std::min<int64_t>(g, (int64_t)px_cu_count(t->device) * o.blocks_per_cu);
+    Launch l;
+    l.grid = dim3((unsigned)g, 1, 1);
+    l.nt = o.nontemporal != 0;
+    return l;
+}
+
+int check_table(const pxchg_table *t) {
+    if (!px_valid(t)) return PXCHG_ERR_INVALID_ARG;
+    int device = -1;
+    if (hipGetDevice(&device) != hipSuccess || device != t->device) {
+        (void)hipGetLastError();
+        return PXCHG_ERR_NO_DEVICE;
+    }
+    return PXCHG_OK;
+}
+
+int check_set(const pxchg_table *t, const pxchg_bufset *s, int dtype /* -1: either */) {
+    if (!px_valid(s)) return PXCHG_ERR_INVALID_ARG;
+    if (s->table != t) return PXCHG_ERR_SHAPE_MISMATCH;
+    if (dtype >= 0 && s->dtype != dtype) return PXCHG_ERR_SHAPE_MISMATCH;
+    return PXCHG_OK;
+}
+
+int after_launch() {
+    const hipError_t e = hipGetLastError();
+    return e == hipSuccess ? PXCHG_OK : PXCHG_ERR_RUNTIME;
+}
+
+bool is_pow2(int k) { return k > 0 && (k & (k - 1)) == 0; }
+
+template <typename TI, typename TO>
+int launch_convert(const pxchg_table *t, int k, const pxchg_bufset *const *src, pxchg_bufset *const *dst,
+                   int src_dtype, int dst_dtype, hipStream_t stream) {
+    int rc = check_table(t);
+    if (rc) return rc;
+    if (!src || !dst) return PXCHG_ERR_INVALID_ARG;
+    if (k < 1 || k > PXCHG_MAX_K) return PXCHG_ERR_UNSUPPORTED;
+    ConvertArgs a;
+    for (int i = 0; i < k; ++i) {
+        if ((rc = check_set(t, src[i], src_dtype))) return rc;
+        if ((rc = check_set(t, dst[i], dst_dtype))) return rc;
+        a.src[i] = (const void *const *)src[i]->d_ptrs;
+        a.dst[i] = (void *const *)dst[i]->d_ptrs;
+    }
+    for (int i = 0; i < k; ++i)
+        for (int j = i + 1; j < k; ++j)
+            if (dst[i] == dst[j]) return PXCHG_ERR_INVALID_ARG;
+    if (t->n_chunks == 0) return PXCHG_OK;
+    const int64_t n_virtual = t->n_chunks * k;
+    const Launch l = launch_shape(t, n_virtual);
+    if (l.nt)
+        hipLaunchKernelGGL((pxchg_convert_kernel<TI, TO, true>), l.grid, dim3(BLOCK), 0, stream, t->d_chunks,
+                           (int)t->n_chunks, n_virtual, a);
+    else
+        hipLaunchKernelGGL((pxchg_convert_kernel<TI, TO, false>), l.grid, dim3(BLOCK), 0, stream, t->d_chunks,
+                           (int)t->n_chunks, n_virtual, a);
+    return after_launch();
+}
+
+template <int K, typename TI, typename TO>
+void launch_reduce_k(const pxchg_table *t, const Launch &l, const ReduceArgs &a, hipStream_t stream) {
+    if (l.nt)
+        hipLaunchKernelGGL((pxchg_reduce_avg_kernel<K, TI, TO, true>), l.grid, dim3(BLOCK), 0, stream, t->d_chunks,
+                           (int)t->n_chunks, a);
+    else
+        hipLaunchKernelGGL((pxchg_reduce_avg_kernel<K, TI, TO, false>), l.grid, dim3(BLOCK), 0, stream, t->d_chunks,
+                           (int)t->n_chunks, a);
+}
+
+template <typename TI, typename TO>
+void launch_reduce(const pxchg_table *t, int k, const ReduceArgs &a, hipStream_t stream) {
+    const Launch l = launch_shape(t, t->n_chunks);
+    switch (k) {
+        case 1: launch_reduce_k<1, TI, TO>(t, l, a, stream); break;
+        case 2: launch_reduce_k<2, TI, TO>(t, l, a, stream); break;
+        case 3: launch_reduce_k<3, TI, TO>(t, l, a, stream); break;
+        case 4: launch_reduce_k<4, TI, TO>(t, l, a, stream); break;
+        case 5: launch_reduce_k<5, TI, TO>(t, l, a, stream); break;
+        case 6: launch_reduce_k<6, TI, TO>(t, l, a, stream); break;
+        case 7: launch_reduce_k<7, TI, TO>(t, l, a, stream); break;
+        case 8: launch_reduce_k<8, TI, TO>(t, l, a, stream); break;
+        default:
+            if (l.nt)
+                hipLaunchKernelGGL((pxchg_reduce_avg_anyk_kernel<TI, TO, true>), l.grid, dim3(BLOCK), 0, stream,
+                                   t->d_chunks, (int)t->n_chunks, a);
+            else
+                hipLaunchKernelGGL((pxchg_reduce_avg_anyk_kernel<TI, TO, false>), l.grid, dim3(BLOCK), 0, stream,
+                                   t->d_chunks, (int)t->n_chunks, a);
+    }
+}
+
+template <int K, typename TI>
+void launch_fused_k(const pxchg_table *t, const Launch &l, const FusedArgs &a, bool wire16, hipStream_t stream) {
+#define PX_FUSED(W, N)                                                                                              \
+    hipLaunchKernelGGL((pxchg_reduce_avg_sgd_momentum_kernel<K, TI, W, N>), l.grid, dim3(BLOCK), 0, stream,         \
+                       t->d_chunks, (int)t->n_chunks, a)
+    if (wire16) {
+        if (l.nt) PX_FUSED(true, true); else PX_FUSED(true, false);
+    } else {
+        if (l.nt) PX_FUSED(false, true); else PX_FUSED(false, false);
+    }
+#undef PX_FUSED
+}
+
+template <typename TI>
+int launch_fused(const pxchg_table *t, int k, const FusedArgs &a, bool wire16, hipStream_t stream) {
+    const Launch l = launch_shape(t, t->n_chunks);
+    switch (k) {
+        case 1: launch_fused_k<1, TI>(t, l, a, wire16, stream); break;
+        case 2: launch_fused_k<2, TI>(t, l, a, wire16, stream); break;
+        case 3: launch_fused_k<3, TI>(t, l, a, wire16, stream); break;
+        case 4: launch_fused_k<4, TI>(t, l, a, wire16, stream); break;
+        case 5: launch_fused_k<5, TI>(t, l, a, wire16, stream); break;
+        case 6: launch_fused_k<6, TI>(t, l, a, wire16, stream); break;
+        case 7: launch_fused_k<7, TI>(t, l, a, wire16, stream); break;
+        case 8: launch_fused_k<8, TI>(t, l, a, wire16, stream); break;
+        default: return PXCHG_ERR_UNSUPPORTED;
+    }
+    return after_launch();
+}
+
+template <int K>
+void launch_elastic_k(const pxchg_table *t, const Launch &l, const ElasticArgs &a, hipStream_t stream) {
+    if (l.nt)
+        hipLaunchKernelGGL((pxchg_easgd_kernel<K, true>), l.grid, dim3(BLOCK), 0, stream, t->d_chunks, (int)t->n_chunks, a);
+    else
+        hipLaunchKernelGGL((pxchg_easgd_kernel<K, false>), l.grid, dim3(BLOCK), 0, stream, t->d_chunks, (int)t->n_chunks, a);
+}
+
+void fill_scale(int k, int mode, int *use_div, float *kf, float *scale) {
+    *kf = (float)k;
+    if (mode == PXCHG_SUM) {
+        *use_div = 0;
+        *scale = 1.0f;
+    } else if (is_pow2(k)) {
+        *use_div = 0;
+        *scale = 1.0f / (float)k;  // exact
+    } else {
+        *use_div = 1;
+        *scale = 1.0f;
+    }
+}
+
+}  // namespace
+
+extern "C" {
+
+int pxchg_pack_fp16(const pxchg_table *table, int k, const pxchg_bufset *const *src_f32, pxchg_bufset *const *dst_f16,
+                    void *stream) {
+    return launch_convert<float, _Float16>(table, k, src_f32, dst_f16, PXCHG_F32, PXCHG_F16, (hipStream_t)stream);
+}
+
+int pxchg_unpack_fp16(const pxchg_table *table, int k, const pxchg_bufset *const *src_f16, pxchg_bufset *const *dst_f32,
+                      void *stream) {
+    return launch_convert<_Float16, float>(table, k, src_f16, dst_f32, PXCHG_F16, PXCHG_F32, (hipStream_t)stream);
+}
+
+int pxchg_reduce_avg(const pxchg_table *table, int k, const pxchg_bufset *const *contrib, pxchg_bufset *out, int mode,
+                     void *stream) {
+    int rc = check_table(table);
+    if (rc) return rc;
+    if (!contrib) return PXCHG_ERR_INVALID_ARG;
+    if (mode != PXCHG_AVG && mode != PXCHG_SUM) return PXCHG_ERR_INVALID_ARG;
+    if (k < 1 || k > PXCHG_MAX_K) return PXCHG_ERR_UNSUPPORTED;
+    if ((rc = check_set(table, out, -1))) return rc;
+    if ((rc = check_set(table, contrib[0], -1))) return rc;
+    const int in_dtype = contrib[0]->dtype;
+    ReduceArgs a;
+    for (int i = 0; i < k; ++i) {
+        if ((rc = check_set(table, contrib[i], in_dtype))) return rc;
+        a.contrib[i] = (const void *const *)contrib[i]->d_ptrs;
+    }
+    a.out = (void *const *)out->d_ptrs;
+    a.k = k;
+    fill_scale(k, mode, &a.use_div, &a.kf, &a.scale);
+    if (table->n_chunks == 0) return PXCHG_OK;
+    hipStream_t s = (hipStream_t)stream;
+    if (in_dtype == PXCHG_F32 && out->dtype == PXCHG_F32) launch_reduce<float, float>(table, k, a, s);
+    else if (in_dtype == PXCHG_F32) launch_reduce<float, _Float16>(table, k, a, s);
+    else if (out->dtype == PXCHG_F32) launch_reduce<_Float16, float>(table, k, a, s);
+    else launch_reduce<_Float16, _Float16>(table, k, a, s);
+    return after_launch();
+}
+
+int pxchg_sgd_momentum(const pxchg_table *table, const pxchg_bufset *grad, pxchg_bufset *param, pxchg_bufset *vel,
+                       float lr, float mu, float wd, void *stream) {
+    int rc = check_table(table);
+    if (rc) return rc;
+    if ((rc = check_set(table, grad, -1))) return rc;
+    if ((rc = check_set(table, param, PXCHG_F32))) return rc;
+    if ((rc = check_set(table, vel, PXCHG_F32))) return rc;
+    if (param == vel || (const pxchg_bufset *)param == grad || (const pxchg_bufset *)vel == grad)
+        return PXCHG_ERR_INVALID_ARG;
+    if (table->n_chunks == 0) return PXCHG_OK;
+    UpdateArgs a;
+    a.grad = (const void *const *)grad->d_ptrs;
+    a.param = (void *const *)param->d_ptrs;
+    a.vel = (void *const *)vel->d_ptrs;
+    a.lr = lr;
+    a.mu = mu;
+    a.wd = wd;
+    const Launch l = launch_shape(table, table->n_chunks);
+    hipStream_t s = (hipStream_t)stream;
+#define PX_UPD(T, N)                                                                                       \
+    hipLaunchKernelGGL((pxchg_sgd_momentum_kernel<T, N>), l.grid, dim3(BLOCK), 0, s, table->d_chunks,       \
+                       (int)table->n_chunks, a)
+    if (grad->dtype == PXCHG_F32) {
+        if (l.nt) PX_UPD(float, true); else PX_UPD(float, false);
+    } else {
+        if (l.nt) PX_UPD(_Float16, true); else PX_UPD(_Float16, false);
+    }
+#undef PX_UPD
+    return after_launch();
+}
+
+int pxchg_reduce_avg_sgd_momentum(const pxchg_table *table, int k, const pxchg_bufset *const *contrib, int mode,
+                                  int wire_dtype, pxchg_bufset *param, pxchg_bufset *vel, float lr, float mu, float wd,
+                                  void *stream) {
+    int rc = check_table(table);
+    if (rc) return rc;
+    if (!contrib) return PXCHG_ERR_INVALID_ARG;
+    if (mode != PXCHG_AVG && mode != PXCHG_SUM) return PXCHG_ERR_INVALID_ARG;
+    if (wire_dtype != PXCHG_F32 && wire_dtype != PXCHG_F16) return PXCHG_ERR_INVALID_ARG;
+    if (k < 1 || k > PXCHG_MAX_K) return PXCHG_ERR_UNSUPPORTED;
+    if (k > 8) return PXCHG_ERR_UNSUPPORTED;  // the fused form is specialised for 1..8 workers
+    if ((rc = check_set(table, param, PXCHG_F32))) return rc;
+    if ((rc = check_set(table, vel, PXCHG_F32))) return rc;
+    if (param == vel) return PXCHG_ERR_INVALID_ARG;
+    if ((rc = check_set(table, contrib[0], -1))) return rc;
+    const int in_dtype = contrib[0]->dtype;
+    FusedArgs a;
+    for (int i = 0; i < k; ++i) {
+        if ((rc = check_set(table, contrib[i], in_dtype))) return rc;
+        if (contrib[i] == (const pxchg_bufset *)param || contrib[i] == (const pxchg_bufset *)vel)
+            return PXCHG_ERR_INVALID_ARG;
+        a.contrib[i] = (const void *const *)contrib[i]->d_ptrs;
+    }
+    a.param = (void *const *)param->d_ptrs;
+    a.vel = (void *const *)vel->d_ptrs;
+    a.k = k;
+    fill_scale(k, mode, &a.use_div, &a.kf, &a.scale);
+    a.lr = lr;
+    a.mu = mu;
+    a.wd = wd;
+    if (table->n_chunks == 0) return PXCHG_OK;
+    hipStream_t s = (hipStream_t)stream;
+    if (in_dtype == PXCHG_F32) return launch_fused<float>(table, k, a, wire_dtype == PXCHG_F16, s);
+    return launch_fused<_Float16>(table, k, a, wire_dtype == PXCHG_F16, s);
+}
+
+int pxchg_easgd_round(const pxchg_table *table, int k, pxchg_bufset *const *x, pxchg_bufset *c, float alpha,
+                      void *stream) {
+    int rc = check_table(table);
+    if (rc) return rc;
+    if (!x) return PXCHG_ERR_INVALID_ARG;
+    if (k < 1 || k > PXCHG_MAX_K) return PXCHG_ERR_UNSUPPORTED;
+    if ((rc = check_set(table, c, PXCHG_F32))) return rc;
+    for (int i = 0; i < k; ++i) {
+        if ((rc = check_set(table, x[i], PXCHG_F32))) return rc;
+        if (x[i] == c) return PXCHG_ERR_INVALID_ARG;
+        for (int j = 0; j < i; ++j)
+            if (x[i] == x[j]) return PXCHG_ERR_INVALID_ARG;
+    }
+    if (table->n_chunks == 0) return PXCHG_OK;
+    hipStream_t s = (hipStream_t)stream;
+    const Launch l = launch_shape(table, table->n_chunks);
+    // More than 8 workers: successive launches of up to 8, the center carried
+    // through memory between them (same arithmetic, same order).
+    for (int i0 = 0; i0 < k; i0 += 8) {
+        const int kk = std::min(8, k - i0);
+        ElasticArgs a;
+        for (int i = 0; i < kk; ++i) a.x[i] = (void *const *)x[i0 + i]->d_ptrs;
+        a.c = (void *const *)c->d_ptrs;
+        a.k = kk;
+        a.alpha = alpha;
+        switch (kk) {
+            case 1: launch_elastic_k<1>(table, l, a, s); break;
+            case 2: launch_elastic_k<2>(table, l, a, s); break;
+            case 3: launch_elastic_k<3>(table, l, a, s); break;
+            case 4: launch_elastic_k<4>(table, l, a, s); break;
+            case 5: launch_elastic_k<5>(table, l, a, s); break;
+            case 6: launch_elastic_k<6>(table, l, a, s); break;
+            case 7: launch_elastic_k<7>(table, l, a, s); break;
+            default: launch_elastic_k<8>(table, l, a, s); break;
+        }
+        if ((rc = after_launch())) return rc;
+    }
+    return PXCHG_OK;
+}
+
+int pxchg_easgd(const pxchg_table *table, pxchg_bufset *x, pxchg_bufset *c, float alpha, void *stream) {
+    pxchg_bufset *xs[1] = {x};
+    return pxchg_easgd_round(table, 1, xs, c, alpha, stream);
+}
+
+}  // extern "C"

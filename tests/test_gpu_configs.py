@@ -1,0 +1,151 @@
+"""GPU parity on the five benchmark configurations at their full sizes, in the
+default launch configuration (the one bench.py times).  One-step configurations
+are compared on every element; the multi-step loops are compared on a fixed
+sample of elements per tensor (the operations are element-wise, so the oracle
+run on the gathered sample is the same arithmetic), which always includes each
+tensor's first and last elements and the elements around chunk boundaries."""
+import numpy as np
+import pytest
+
+import workloads as wl
+from gpu_util import assert_bits_equal, assert_close_params, empty_like_device, to_device, to_host
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def px():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    import paper_1605_08325_amd as px
+    px.load()
+    return px
+
+
+def sample_indices(counts, per_tensor, seed, chunk):
+    rng = np.random.default_rng(seed)
+    out = []
+    for c in counts:
+        if c <= per_tensor:
+            out.append(np.arange(c))
+            continue
+        idx = [rng.integers(0, c, per_tensor), np.arange(0, 64), np.arange(c - 64, c)]
+        for b in range(chunk, c, chunk * max(1, (c // chunk) // 16)):     # around some chunk boundaries
+            idx.append(np.arange(max(0, b - 16), min(c, b + 16)))
+        out.append(np.unique(np.concatenate(idx)))
+    return out
+
+
+def gather(tensors, idx):
+    return [np.ascontiguousarray(t[i]) for t, i in zip(tensors, idx)]
+
+
+def gather_device(tensors, idx):
+    import torch
+    return [t[torch.from_numpy(i).to("cuda")].cpu().numpy() for t, i in zip(tensors, idx)]
+
+
+def sync_exchange(px, oracle_mod, cfg, steps, full):
+    """pack (if half-precision transfer) -> reduce+average -> update, `steps` times."""
+    import torch
+    counts = list(cfg.counts)
+    table = px.Table(counts)
+    half = cfg.transfer == "f16"
+    wire = np.float16 if half else np.float32
+    w = [a.copy() for a in wl.gaussian_tensors(counts, cfg.param_sigma, cfg.seed, "param")]
+    v = wl.zeros_tensors(counts)
+    d_w, d_v = to_device(w), to_device(v)
+    sw, sv = table.bufset(d_w), table.bufset(d_v)
+    d_avg = empty_like_device(counts, wire)
+    s_avg = table.bufset(d_avg)
+    idx = None if full else sample_indices(counts, 20_000, cfg.seed, px.get_option(px.OPT_CHUNK_ELEMS))
+    if idx is not None:
+        w, v = gather(w, idx), gather(v, idx)
+    for step in range(steps):
+        grads = wl.gaussian_workers(counts, cfg.grad_sigma, cfg.seed, "grad", cfg.k, step)
+        d_g = [to_device(g) for g in grads]
+        s_g = [table.bufset(g) for g in d_g]
+        if half:
+            d_h = [empty_like_device(counts, np.float16) for _ in range(cfg.k)]
+            s_h = [table.bufset(h) for h in d_h]
+            px.pack_fp16(table, s_g, s_h)
+            contrib_sets = s_h
+        else:
+            contrib_sets = s_g
+        px.reduce_avg(table, contrib_sets, s_avg)
+        px.sgd_momentum(table, s_avg, sw, sv, cfg.lr, cfg.mu, cfg.wd)
+        torch.cuda.synchronize()
+        # oracle on all elements, or on the gathered sample
+        if idx is not None:
+            grads = [gather(g, idx) for g in grads]
+        contrib = [oracle_mod.pack_fp16_tensors(g) for g in grads] if half else grads
+        if half and step == 0:
+            for i in (0, cfg.k - 1):
+                got = to_host(d_h[i]) if idx is None else gather_device(d_h[i], idx)
+                assert_bits_equal(got, contrib[i], f"{cfg.name} packed worker {i}")
+        avg = oracle_mod.reduce_avg_tensors(contrib, wire)
+        got = to_host(d_avg) if idx is None else gather_device(d_avg, idx)
+        assert_bits_equal(got, avg, f"{cfg.name} average step {step}")
+        oracle_mod.sgd_momentum_tensors(avg, w, v, cfg.lr, cfg.mu, cfg.wd)
+        del d_g, s_g
+    got_w = to_host(d_w) if idx is None else gather_device(d_w, idx)
+    got_v = to_host(d_v) if idx is None else gather_device(d_v, idx)
+    assert_close_params(got_w, w, cfg.name)          # the stated tolerance
+    assert_bits_equal(got_w, w, f"{cfg.name} params")  # and in fact bit-exact
+    assert_bits_equal(got_v, v, f"{cfg.name} velocity")
+
+
+def test_config1_tiny_sync(px, oracle_mod):
+    sync_exchange(px, oracle_mod, wl.config(1), steps=1, full=True)
+
+
+def test_config2_alexnet_k2_f32(px, oracle_mod):
+    sync_exchange(px, oracle_mod, wl.config(2), steps=1, full=True)
+
+
+def test_config3_alexnet_k8_f16_one_step_all_elements(px, oracle_mod):
+    sync_exchange(px, oracle_mod, wl.config(3), steps=1, full=True)
+
+
+def test_config3_alexnet_k8_f16_ten_steps_sampled(px, oracle_mod):
+    cfg = wl.config(3)
+    sync_exchange(px, oracle_mod, cfg, steps=cfg.steps, full=False)
+
+
+def test_config4_many_small_tensors_one_launch_per_stage(px, oracle_mod):
+    cfg = wl.config(4)
+    assert len(cfg.counts) == 116 and cfg.n == 7_000_000
+    sync_exchange(px, oracle_mod, cfg, steps=2, full=True)
+
+
+def test_config5_easgd_100_rounds_sampled(px, oracle_mod):
+    import torch
+    cfg = wl.config(5)
+    counts = list(cfg.counts)
+    table = px.Table(counts)
+    xs = wl.gaussian_workers(counts, cfg.param_sigma, cfg.seed, "worker", cfg.k)
+    c = wl.gaussian_tensors(counts, cfg.param_sigma, cfg.seed, "center")
+    d_xs = [to_device(x) for x in xs]
+    d_c = to_device(c)
+    s_xs = [table.bufset(x) for x in d_xs]
+    s_c = table.bufset(d_c)
+    idx = sample_indices(counts, 20_000, cfg.seed, px.get_option(px.OPT_CHUNK_ELEMS))
+    xs = [gather(x, idx) for x in xs]
+    c = gather(c, idx)
+    orders = wl.worker_orders(cfg.seed, cfg.k, cfg.rounds)
+    alpha = np.float32(cfg.alpha)
+    # first half of the rounds as single worker-center meetings, second half as fused rounds
+    for r, order in enumerate(orders):
+        if r < cfg.rounds // 2:
+            for i in order:
+                px.easgd(table, s_xs[i], s_c, float(alpha))
+        else:
+            px.easgd_round(table, [s_xs[i] for i in order], s_c, float(alpha))
+        for i in order:
+            oracle_mod.easgd_tensors(xs[i], c, alpha)
+    torch.cuda.synchronize()
+    for i in range(cfg.k):
+        got = gather_device(d_xs[i], idx)
+        assert_close_params(got, xs[i], f"worker {i}")
+        assert_bits_equal(got, xs[i], f"worker {i}")
+    assert_bits_equal(gather_device(d_c, idx), c, "center")

@@ -1,0 +1,411 @@
+"""GPU parity: every libpxchg call against the CPU oracle, element by element, on
+shapes that span several chunks, ragged tails, tiny tensors and misaligned
+pointers.  Bit-exact for the binary16 conversion and the fixed-order sums; the
+updates are compared bit-exactly too (both sides round every operation to
+binary32), which is stricter than the stated 1e-6 tolerance."""
+import numpy as np
+import pytest
+
+import workloads as wl
+from gpu_util import (assert_bits_equal, assert_close_params, empty_like_device, to_device,
+                      to_host)
+
+pytestmark = pytest.mark.gpu
+
+# several full chunks + ragged tails + tiny tensors + an empty one
+RAGGED = [1, 3, 63, 64, 65, 0, 8 * 1000 + 1, 20_000, 2 * 8192 + 5, 8192, 8191, 70_001]
+
+
+@pytest.fixture(scope="module")
+def px():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    import paper_1605_08325_amd as px
+    px.load()
+    return px
+
+
+def _gauss(counts, seed, worker=0, sigma=0.01, role="grad"):
+    return [a.copy() for a in wl.gaussian_tensors(counts, sigma, seed, role, worker)]
+
+
+# ------------------------------------------------------------------ pack / unpack
+
+def test_unpack_all_halves_then_pack_back(px, oracle_mod):
+    hs = np.arange(1 << 16, dtype=np.uint32).astype(np.uint16).view(np.float16)
+    table = px.Table([hs.size])
+    d_h = to_device([hs])
+    d_w = empty_like_device([hs.size], np.float32)
+    d_b = empty_like_device([hs.size], np.float16)
+    sh, sw, sb = table.bufset(d_h), table.bufset(d_w), table.bufset(d_b)
+    px.unpack_fp16(table, [sh], [sw])
+    px.pack_fp16(table, [sw], [sb])
+    wide = to_host(d_w)
+    assert_bits_equal(wide, [oracle_mod.unpack_fp16(hs)], "unpack", nan_as_class=True)
+    back = to_host(d_b)
+    assert_bits_equal(back, [oracle_mod.pack_fp16(oracle_mod.unpack_fp16(hs))], "round trip",
+                      nan_as_class=True)
+    # NaN keeps its sign through both directions
+    nan = np.isnan(hs)
+    assert np.array_equal(back[0].view(np.uint16)[nan] & 0x8000, hs.view(np.uint16)[nan] & 0x8000)
+
+
+def test_pack_ties_and_boundaries(px, oracle_mod):
+    lo = np.arange(0, 0x7C00, dtype=np.uint32).astype(np.uint16).view(np.float16).astype(np.float64)
+    hi = np.append(lo[1:], 65536.0)
+    mid = ((lo + hi) / 2).astype(np.float32)
+    vals = np.concatenate([
+        mid, np.nextafter(mid, np.float32(-np.inf)), np.nextafter(mid, np.float32(np.inf)),
+        np.array([65504.0, 65519.996, 65520.0, 65536.0, 3e38, 2.0 ** -14, 2.0 ** -24, 2.0 ** -25,
+                  2.0 ** -26, 0.0, 1e-45, 1.1754942e-38, np.inf], np.float32)])
+    vals = np.concatenate([vals, -vals]).astype(np.float32)
+    table = px.Table([vals.size])
+    d_in = to_device([vals])
+    d_out = empty_like_device([vals.size], np.float16)
+    px.pack_fp16(table, [table.bufset(d_in)], [table.bufset(d_out)])
+    assert_bits_equal(to_host(d_out), [oracle_mod.pack_fp16(vals)], "ties and boundaries")
+
+
+def test_pack_random_bit_patterns(px, oracle_mod):
+    rng = np.random.default_rng(11)
+    x = rng.integers(0, 1 << 32, 6_000_001, dtype=np.uint64).astype(np.uint32).view(np.float32)
+    table = px.Table([x.size])
+    d_in = to_device([x])
+    d_out = empty_like_device([x.size], np.float16)
+    px.pack_fp16(table, [table.bufset(d_in)], [table.bufset(d_out)])
+    assert_bits_equal(to_host(d_out), [oracle_mod.pack_fp16(x)], "random bits", nan_as_class=True)
+
+
+@pytest.mark.parametrize("offset", [0, 1, 3])
+def test_pack_many_workers_ragged(px, oracle_mod, offset):
+    k = 5
+    table = px.Table(RAGGED)
+    src = [_gauss(RAGGED, 100 + offset, w) for w in range(k)]
+    d_src = [to_device(s, offset) for s in src]
+    d_dst = [empty_like_device(RAGGED, np.float16, offset, fill=7.0) for _ in range(k)]
+    px.pack_fp16(table, [table.bufset(s) for s in d_src], [table.bufset(d) for d in d_dst])
+    for w in range(k):
+        assert_bits_equal(to_host(d_dst[w]), oracle_mod.pack_fp16_tensors(src[w]), f"worker {w}")
+    # nothing outside the tensors was written (guard elements keep their fill)
+    for w in range(k):
+        for t in d_dst[w]:
+            base = t._base if t._base is not None else t
+            host = base.cpu().numpy()
+            assert np.all(host[:offset] == 7.0) and np.all(host[offset + t.numel():] == 7.0)
+
+
+def test_pack_mixed_alignment_uses_elementwise_path(px, oracle_mod):
+    """Source 4 bytes off, destination 16-byte aligned: no common vector alignment."""
+    counts = [5000, 17, 8192 + 3]
+    table = px.Table(counts)
+    src = _gauss(counts, 42)
+    d_src = to_device(src, 1)
+    d_dst = empty_like_device(counts, np.float16, 0)
+    px.pack_fp16(table, [table.bufset(d_src)], [table.bufset(d_dst)])
+    assert_bits_equal(to_host(d_dst), oracle_mod.pack_fp16_tensors(src), "mixed alignment")
+    d_dst2 = empty_like_device(counts, np.float16, 2)     # 4-byte offset on the half side
+    px.pack_fp16(table, [table.bufset(d_src)], [table.bufset(d_dst2)])
+    assert_bits_equal(to_host(d_dst2), oracle_mod.pack_fp16_tensors(src), "mixed alignment 2")
+
+
+# ------------------------------------------------------------------ reduce + average
+
+@pytest.mark.parametrize("k", [1, 2, 3, 5, 8, 9, 13, 16, 64])
+@pytest.mark.parametrize("in_dt,out_dt", [(np.float32, np.float32), (np.float16, np.float16),
+                                          (np.float16, np.float32), (np.float32, np.float16)])
+def test_reduce_avg_ragged(px, oracle_mod, k, in_dt, out_dt):
+    counts = RAGGED if k <= 16 else [1, 65, 8192 + 9, 3000]
+    table = px.Table(counts)
+    contrib = []
+    for w in range(k):
+        g = _gauss(counts, 200 + k, w)
+        contrib.append([a.astype(in_dt) for a in g])
+    d_c = [to_device(c) for c in contrib]
+    sets = [table.bufset(c) for c in d_c]
+    for mode in (px.AVG, px.SUM):
+        d_out = empty_like_device(counts, out_dt)
+        px.reduce_avg(table, sets, table.bufset(d_out), mode)
+        want = oracle_mod.reduce_avg_tensors(contrib, out_dt, mode)
+        assert_bits_equal(to_host(d_out), want, f"k={k} mode={mode}")
+
+
+@pytest.mark.parametrize("offset", [1, 2])
+def test_reduce_avg_misaligned(px, oracle_mod, offset):
+    k = 8
+    table = px.Table(RAGGED)
+    contrib = [[a.astype(np.float16) for a in _gauss(RAGGED, 300, w)] for w in range(k)]
+    d_c = [to_device(c, offset) for c in contrib]
+    d_out = empty_like_device(RAGGED, np.float16, offset)
+    px.reduce_avg(table, [table.bufset(c) for c in d_c], table.bufset(d_out))
+    assert_bits_equal(to_host(d_out), oracle_mod.reduce_avg_tensors(contrib, np.float16), "misaligned")
+
+
+def test_reduce_order_sensitive_float32(px, oracle_mod):
+    """k = 8, binary32 transfer: the sequential order is visible in the last bit."""
+    k, counts = 8, [100_003, 8192 * 3 + 1]
+    table = px.Table(counts)
+    contrib = [_gauss(counts, 400, w) for w in range(k)]
+    d_c = [to_device(c) for c in contrib]
+    d_out = empty_like_device(counts, np.float32)
+    px.reduce_avg(table, [table.bufset(c) for c in d_c], table.bufset(d_out))
+    got = to_host(d_out)
+    assert_bits_equal(got, oracle_mod.reduce_avg_tensors(contrib), "fp32 order")
+    rev = oracle_mod.reduce_avg_tensors(contrib[::-1])
+    assert np.mean(got[0] != rev[0]) > 0.05          # a reversed order would be caught
+
+
+def test_reduce_order_sensitive_wide_range_halves(px, oracle_mod):
+    k, counts = 8, [100_003, 8192 * 3 + 1]
+    table = px.Table(counts)
+    contrib = [[a.astype(np.float16) for a in wl.wide_range_halves(counts, 500, w)] for w in range(k)]
+    d_c = [to_device(c) for c in contrib]
+    for out_dt in (np.float32, np.float16):
+        d_out = empty_like_device(counts, out_dt)
+        px.reduce_avg(table, [table.bufset(c) for c in d_c], table.bufset(d_out), px.SUM)
+        got = to_host(d_out)
+        assert_bits_equal(got, oracle_mod.reduce_avg_tensors(contrib, out_dt, px.SUM), "wide halves")
+    rev = oracle_mod.reduce_avg_tensors(contrib[::-1], np.float32, px.SUM)
+    d_out = empty_like_device(counts, np.float32)
+    px.reduce_avg(table, [table.bufset(c) for c in d_c], table.bufset(d_out), px.SUM)
+    assert np.mean(to_host(d_out)[0] != rev[0]) > 0.01
+
+
+def test_reduce_special_values(px, oracle_mod):
+    """Signed zeros, infinities, NaN, subnormals: s starts from the first contribution."""
+    sp = np.array([0.0, -0.0, np.inf, -np.inf, np.nan, 1e-45, -1e-45, 1.1754942e-38, 3e38, -3e38,
+                   65504.0, 2.0 ** -24, 2.0 ** -25, 1.0], np.float32)
+    a = np.repeat(sp, sp.size)
+    b = np.tile(sp, sp.size)
+    table = px.Table([a.size])
+    for k_extra in (0, 1):
+        contrib = [[a], [b]] + [[np.full_like(a, -0.0)]] * k_extra
+        d_c = [to_device(c) for c in contrib]
+        for out_dt in (np.float32, np.float16):
+            for mode in (px.AVG, px.SUM):
+                d_out = empty_like_device([a.size], out_dt)
+                px.reduce_avg(table, [table.bufset(c) for c in d_c], table.bufset(d_out), mode)
+                assert_bits_equal(to_host(d_out), oracle_mod.reduce_avg_tensors(contrib, out_dt, mode),
+                                  f"special k={2 + k_extra}", nan_as_class=True)
+    # k = 1: a lone -0 stays -0
+    d_c = to_device([a])
+    d_out = empty_like_device([a.size], np.float32)
+    px.reduce_avg(table, [table.bufset(d_c)], table.bufset(d_out))
+    assert_bits_equal(to_host(d_out), [oracle_mod.reduce_avg([a])], "k=1", nan_as_class=True)
+
+
+def test_reduce_in_place_into_first_contribution(px, oracle_mod):
+    """Weight averaging writes the mean back over worker 0's copy."""
+    k, counts = 4, [10_000, 33]
+    table = px.Table(counts)
+    contrib = [_gauss(counts, 600, w, role="param") for w in range(k)]
+    d_c = [to_device(c) for c in contrib]
+    sets = [table.bufset(c) for c in d_c]
+    px.reduce_avg(table, sets, sets[0])
+    assert_bits_equal(to_host(d_c[0]), oracle_mod.reduce_avg_tensors(contrib), "in place")
+
+
+# ------------------------------------------------------------------ momentum SGD
+
+@pytest.mark.parametrize("g_dt", [np.float32, np.float16])
+@pytest.mark.parametrize("wd", [0.0, 5e-4])
+@pytest.mark.parametrize("offset", [0, 1])
+def test_sgd_momentum_steps(px, oracle_mod, g_dt, wd, offset):
+    table = px.Table(RAGGED)
+    w = _gauss(RAGGED, 700, role="param")
+    v = _gauss(RAGGED, 701, sigma=1e-3, role="velocity")
+    d_w, d_v = to_device(w, offset), to_device(v, offset)
+    sw, sv = table.bufset(d_w), table.bufset(d_v)
+    g_off = offset                                      # same element offset: a common head exists
+    for step in range(3):
+        g = [a.astype(g_dt) for a in _gauss(RAGGED, 702, worker=step)]
+        d_g = to_device(g, g_off)
+        px.sgd_momentum(table, table.bufset(d_g), sw, sv, 0.01, 0.9, wd)
+        oracle_mod.sgd_momentum_tensors(g, w, v, 0.01, 0.9, wd)
+        assert_bits_equal(to_host(d_w), w, f"w step {step}")
+        assert_bits_equal(to_host(d_v), v, f"v step {step}")
+    assert_close_params(to_host(d_w), w)
+
+
+def test_sgd_momentum_operands_without_common_alignment(px, oracle_mod):
+    counts = [8192 + 77, 5]
+    table = px.Table(counts)
+    w, v, g = _gauss(counts, 710, role="param"), _gauss(counts, 711, role="velocity"), _gauss(counts, 712)
+    d_w, d_v, d_g = to_device(w, 1), to_device(v, 0), to_device(g, 2)
+    px.sgd_momentum(table, table.bufset(d_g), table.bufset(d_w), table.bufset(d_v), 0.01, 0.9, 5e-4)
+    oracle_mod.sgd_momentum_tensors(g, w, v, 0.01, 0.9, 5e-4)
+    assert_bits_equal(to_host(d_w), w, "w")
+    assert_bits_equal(to_host(d_v), v, "v")
+
+
+def test_sgd_momentum_tiny_values_keep_subnormals(px, oracle_mod):
+    counts = [4099]
+    rng = np.random.default_rng(8)
+    w = [(rng.standard_normal(counts[0]) * 1e-38).astype(np.float32)]
+    v = [(rng.standard_normal(counts[0]) * 1e-39).astype(np.float32)]
+    g = [(rng.standard_normal(counts[0]) * 1e-37).astype(np.float32)]
+    table = px.Table(counts)
+    d_w, d_v, d_g = to_device(w), to_device(v), to_device(g)
+    px.sgd_momentum(table, table.bufset(d_g), table.bufset(d_w), table.bufset(d_v), 0.01, 0.9, 5e-4)
+    oracle_mod.sgd_momentum_tensors(g, w, v, 0.01, 0.9, 5e-4)
+    assert_bits_equal(to_host(d_w), w, "subnormal w")
+    assert_bits_equal(to_host(d_v), v, "subnormal v")
+    assert np.any((np.abs(v[0]) < 1.1754944e-38) & (v[0] != 0))     # subnormals did occur
+
+
+# ------------------------------------------------------------------ fused reduce + update
+
+@pytest.mark.parametrize("k", [1, 2, 3, 8])
+@pytest.mark.parametrize("in_dt", [np.float32, np.float16])
+@pytest.mark.parametrize("wire", ["f32", "f16"])
+def test_fused_reduce_update_equals_two_calls_and_oracle(px, oracle_mod, k, in_dt, wire):
+    table = px.Table(RAGGED)
+    contrib = [[a.astype(in_dt) for a in _gauss(RAGGED, 800 + k, w)] for w in range(k)]
+    w0 = _gauss(RAGGED, 801, role="param")
+    v0 = _gauss(RAGGED, 802, sigma=1e-3, role="velocity")
+    wire_np = np.float16 if wire == "f16" else np.float32
+    wire_px = px.F16 if wire == "f16" else px.F32
+    sets = [table.bufset(to_device(c)) for c in contrib]
+    # oracle: two steps
+    w_o, v_o = [a.copy() for a in w0], [a.copy() for a in v0]
+    avg = oracle_mod.reduce_avg_tensors(contrib, wire_np)
+    oracle_mod.sgd_momentum_tensors(avg, w_o, v_o, 0.01, 0.9, 5e-4)
+    # GPU: two calls
+    d_w2, d_v2 = to_device(w0), to_device(v0)
+    d_avg = empty_like_device(RAGGED, wire_np)
+    s_avg = table.bufset(d_avg)
+    px.reduce_avg(table, sets, s_avg)
+    px.sgd_momentum(table, s_avg, table.bufset(d_w2), table.bufset(d_v2), 0.01, 0.9, 5e-4)
+    # GPU: fused
+    d_w1, d_v1 = to_device(w0), to_device(v0)
+    px.reduce_avg_sgd_momentum(table, sets, table.bufset(d_w1), table.bufset(d_v1), 0.01, 0.9, 5e-4,
+                               px.AVG, wire_px)
+    assert_bits_equal(to_host(d_w1), w_o, "fused w vs oracle")
+    assert_bits_equal(to_host(d_v1), v_o, "fused v vs oracle")
+    assert_bits_equal(to_host(d_w2), w_o, "two-call w vs oracle")
+    assert_bits_equal(to_host(d_v2), v_o, "two-call v vs oracle")
+
+
+# ------------------------------------------------------------------ elastic averaging
+
+@pytest.mark.parametrize("offset", [0, 1])
+def test_easgd_pair(px, oracle_mod, offset):
+    table = px.Table(RAGGED)
+    x = _gauss(RAGGED, 900, role="worker")
+    c = _gauss(RAGGED, 901, role="center")
+    d_x, d_c = to_device(x, offset), to_device(c, offset)
+    sx, sc = table.bufset(d_x), table.bufset(d_c)
+    for _ in range(3):
+        px.easgd(table, sx, sc, 0.0625)
+        oracle_mod.easgd_tensors(x, c, 0.0625)
+    assert_bits_equal(to_host(d_x), x, "x")
+    assert_bits_equal(to_host(d_c), c, "c")
+
+
+@pytest.mark.parametrize("k", [1, 2, 5, 8, 11])
+def test_easgd_round_equals_k_pairs_in_order(px, oracle_mod, k):
+    counts = RAGGED
+    table = px.Table(counts)
+    xs = [_gauss(counts, 910, w, role="worker") for w in range(k)]
+    c = _gauss(counts, 911, role="center")
+    d_xs = [to_device(x) for x in xs]
+    d_c = to_device(c)
+    sets = [table.bufset(x) for x in d_xs]
+    sc = table.bufset(d_c)
+    orders = wl.worker_orders(912, k, 4)
+    for order in orders:
+        px.easgd_round(table, [sets[i] for i in order], sc, 0.5 / k)
+        for i in order:
+            oracle_mod.easgd_tensors(xs[i], c, np.float32(0.5 / k))
+    for i in range(k):
+        assert_bits_equal(to_host(d_xs[i]), xs[i], f"x[{i}]")
+    assert_bits_equal(to_host(d_c), c, "center")
+    # the order matters: a fixed order gives a different center
+    if k >= 5:
+        xs2 = [_gauss(counts, 910, w, role="worker") for w in range(k)]
+        c2 = _gauss(counts, 911, role="center")
+        for _ in orders:
+            for i in range(k):
+                oracle_mod.easgd_tensors(xs2[i], c2, np.float32(0.5 / k))
+        assert any(np.any(a != b) for a, b in zip(c, c2))
+
+
+# ------------------------------------------------------------------ launch shapes
+
+@pytest.mark.parametrize("chunk,bpc", [(2048, 0), (32768, 0), (8192, 2), (4096, 8)])
+def test_results_do_not_depend_on_launch_shape(px, oracle_mod, chunk, bpc):
+    old = (px.get_option(px.OPT_CHUNK_ELEMS), px.get_option(px.OPT_BLOCKS_PER_CU))
+    try:
+        px.set_option(px.OPT_CHUNK_ELEMS, chunk)
+        px.set_option(px.OPT_BLOCKS_PER_CU, bpc)
+        k = 8
+        table = px.Table(RAGGED)
+        contrib = [[a.astype(np.float16) for a in _gauss(RAGGED, 950, w)] for w in range(k)]
+        sets = [table.bufset(to_device(c)) for c in contrib]
+        d_out = empty_like_device(RAGGED, np.float16)
+        px.reduce_avg(table, sets, table.bufset(d_out))
+        assert_bits_equal(to_host(d_out), oracle_mod.reduce_avg_tensors(contrib, np.float16), "launch shape")
+        src = [_gauss(RAGGED, 951, w) for w in range(3)]
+        d_dst = [empty_like_device(RAGGED, np.float16) for _ in range(3)]
+        px.pack_fp16(table, [table.bufset(to_device(s)) for s in src], [table.bufset(d) for d in d_dst])
+        for w in range(3):
+            assert_bits_equal(to_host(d_dst[w]), oracle_mod.pack_fp16_tensors(src[w]), "pack launch shape")
+    finally:
+        px.set_option(px.OPT_CHUNK_ELEMS, old[0])
+        px.set_option(px.OPT_BLOCKS_PER_CU, old[1])
+
+
+def test_nontemporal_off_gives_same_bits(px, oracle_mod):
+    old = px.get_option(px.OPT_NONTEMPORAL)
+    try:
+        px.set_option(px.OPT_NONTEMPORAL, 0)
+        table = px.Table(RAGGED)
+        x = _gauss(RAGGED, 960, role="worker")
+        c = _gauss(RAGGED, 961, role="center")
+        d_x, d_c = to_device(x), to_device(c)
+        px.easgd(table, table.bufset(d_x), table.bufset(d_c), 0.0625)
+        oracle_mod.easgd_tensors(x, c, 0.0625)
+        assert_bits_equal(to_host(d_x), x, "x")
+        assert_bits_equal(to_host(d_c), c, "c")
+    finally:
+        px.set_option(px.OPT_NONTEMPORAL, old)
+
+
+# ------------------------------------------------------------------ argument errors on a live device
+
+def test_argument_errors(px):
+    import torch
+    table = px.Table([100, 200])
+    other = px.Table([100, 200])
+    a = [torch.zeros(100, device="cuda"), torch.zeros(200, device="cuda")]
+    h = [torch.zeros(100, device="cuda", dtype=torch.float16),
+         torch.zeros(200, device="cuda", dtype=torch.float16)]
+    sa, sh = table.bufset(a), table.bufset(h)
+    so = other.bufset(a)
+    with pytest.raises(px.PxchgError) as e:
+        px.reduce_avg(table, [sa, so], sa)
+    assert e.value.status == 2                         # set of another table
+    with pytest.raises(px.PxchgError) as e:
+        px.reduce_avg(table, [sa, sh], sa)
+    assert e.value.status == 2                         # mixed element types
+    with pytest.raises(px.PxchgError) as e:
+        px.reduce_avg(table, [sa] * 65, sa)
+    assert e.value.status == 3                         # k too large
+    with pytest.raises(px.PxchgError) as e:
+        px.sgd_momentum(table, sa, sa, sa, 0.1, 0.9)
+    assert e.value.status == 1                         # aliasing operands
+    with pytest.raises(px.PxchgError) as e:
+        px.pack_fp16(table, [sh], [sa])
+    assert e.value.status == 2
+    with pytest.raises(px.PxchgError) as e:
+        px.easgd(table, sa, sa, 0.1)
+    assert e.value.status == 1
+    # a tensor that does not fit its allocation is refused at set creation
+    big = torch.zeros(16 << 20, device="cuda")          # 64 MiB, an allocation of its own
+    too_long = px.Table([(16 << 20) + (4 << 20)])       # claims 16 MiB more than that
+    with pytest.raises(px.PxchgError) as e:
+        px.BufSet(too_long, [big.data_ptr()], px.F32)
+    assert e.value.status == 6
+    # misaligned for the element type
+    with pytest.raises(px.PxchgError) as e:
+        px.BufSet(table, [a[0].data_ptr() + 2, a[1].data_ptr()], px.F32)
+    assert e.value.status == 1

@@ -199,3 +199,12 @@ def config(i: int) -> Config:
         return Config("alexnet_easgd_k8", tuple(alexnet_counts()), 8, "f32",
                       alpha=0.5 / 8, rounds=100, seed=s)
     raise ValueError(f"no configuration {i}")
+
+
+def gaussian_workers(counts: Sequence[int], sigma: float, seed: int, role: str, k: int,
+                     step: int = 0, threads: int = 8) -> List[List[np.ndarray]]:
+    """gaussian_tensors for workers 0..k-1, drawn concurrently (each worker has
+    its own generator, so the values do not depend on the thread count)."""
+    from concurrent.futures import ThreadPoolExecutor
+    with ThreadPoolExecutor(max(1, min(threads, k))) as ex:
+        return list(ex.map(lambda w: gaussian_tensors(counts, sigma, seed, role, w, step), range(k)))
