@@ -1,0 +1,323 @@
+#!/usr/bin/env python3
+"""Benchmark of the parameter-exchange hot path on one MI355X.
+
+Workload: the AlexNet-shaped half-precision exchange with k = 8 workers
+(60,965,224 float32 parameters in 16 separately allocated tensors).  One step is
+one pass of the whole path over one batch of synthetic gradients:
+
+    pack      8 workers' float32 gradients -> binary16              (1 launch)
+    reduce    fixed-order float32 sum of the 8 halves, /8, -> half  (1 launch)
+    update    momentum SGD with the half-precision average          (1 launch)
+    elastic   one asynchronous round: 8 workers meet the center     (8 launches)
+
+Everything is resident in HBM before the timed region.  The headline value is
+the metric the build is graded on: reduce+update GB/s = algorithmic bytes of the
+two stages (2k+2 and 18 bytes per element) over their measured time.  Stage
+times come from HIP events recorded on the launch stream between the stages of
+every timed step; the `roofline` object is for the kernel with the largest share
+of the step, `stages` lists all of them.
+
+`cpu_baseline` is the CPU oracle timed on the host cores on the same workload.
+It is a reported baseline (and the only place this program touches the oracle),
+never a fallback: without the built HIP library this program fails.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+from concurrent.futures import ThreadPoolExecutor
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import workloads as wl  # noqa: E402
+
+HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E, published peak
+
+# HBM traffic per launch from hardware counters (FETCH_SIZE + WRITE_SIZE, scaled by
+# what the same counters read for a plain copy of known size); see the files named.
+MEASURED_TRAFFIC_BYTES = {
+    # kernel: (bytes per launch, profile summary it comes from)
+}
+
+
+def host_threads() -> int:
+    n = len(os.sched_getaffinity(0))
+    env = os.environ.get("OMP_NUM_THREADS")
+    if env and env.isdigit() and int(env) > 0:
+        n = min(n, int(env))
+    return max(1, min(n, 16))
+
+
+def upload(tensors):
+    import torch
+    return [torch.from_numpy(np.ascontiguousarray(a)).to("cuda") for a in tensors]
+
+
+def cpu_baseline(counts, grads, w, v, xs, c, order, cfg, alpha, threads):
+    """The oracle, as it stands, on the host cores: same stages, same inputs."""
+    import oracle
+    L = oracle.lib()
+    import ctypes
+    k = len(grads)
+    flat = lambda ts: np.concatenate(ts) if len(ts) > 1 else ts[0].copy()  # noqa: E731
+    # one flat copy per buffer: the oracle is element-wise, so flattening the
+    # tensor list changes nothing but the loop bounds
+    g = [flat(t) for t in grads]
+    n = g[0].size
+    h = [np.empty(n, np.float16) for _ in range(k)]
+    avg = np.empty(n, np.float16)
+    wf, vf = flat(w), flat(v)
+    xf, cf = [flat(t) for t in xs], flat(c)
+    pieces = threads * 4
+    bounds = np.linspace(0, n, pieces + 1).astype(np.int64)
+    spans = [(int(a), int(b)) for a, b in zip(bounds[:-1], bounds[1:]) if b > a]
+
+    def ptr(a, off, es):
+        return ctypes.c_void_p(a.ctypes.data + off * es)
+
+    def pack(span):
+        a, b = span
+        for i in range(k):
+            L.oracle_pack_fp16(ptr(g[i], a, 4), ptr(h[i], a, 2), b - a)
+
+    def reduce(span):
+        a, b = span
+        ps = (ctypes.c_void_p * k)(*[h[i].ctypes.data + a * 2 for i in range(k)])
+        L.oracle_reduce_avg(k, ps, oracle.F16, ptr(avg, a, 2), oracle.F16, oracle.AVG, b - a)
+
+    def update(span):
+        a, b = span
+        L.oracle_sgd_momentum(ptr(avg, a, 2), oracle.F16, ptr(wf, a, 4), ptr(vf, a, 4),
+                              cfg.lr, cfg.mu, cfg.wd, b - a)
+
+    def elastic(span):
+        a, b = span
+        for i in order:
+            L.oracle_easgd(ptr(xf[i], a, 4), ptr(cf, a, 4), alpha, b - a)
+
+    times = {}
+    with ThreadPoolExecutor(threads) as ex:
+        for name, fn in (("pack", pack), ("reduce", reduce), ("update", update), ("elastic", elastic)):
+            best = None
+            for _ in range(2):
+                t0 = time.perf_counter()
+                list(ex.map(fn, spans))
+                dt = time.perf_counter() - t0
+                best = dt if best is None else min(best, dt)
+            times[name] = best
+    return times
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--sets", type=int, default=2, help="rotating sets of fresh gradients resident in HBM")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--chunk", type=int, default=0, help="override elements per chunk")
+    ap.add_argument("--blocks-per-cu", type=int, default=-1)
+    ap.add_argument("--nontemporal", type=int, default=-1)
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only (the exchange's transfer legs between GPUs are "
+              "out of scope); run it with --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+    import paper_1605_08325_amd as px
+    px.load()  # fails loudly if libpxchg.so has not been built
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    torch.cuda.set_device(0)
+    if args.chunk:
+        px.set_option(px.OPT_CHUNK_ELEMS, args.chunk)
+    if args.blocks_per_cu >= 0:
+        px.set_option(px.OPT_BLOCKS_PER_CU, args.blocks_per_cu)
+    if args.nontemporal >= 0:
+        px.set_option(px.OPT_NONTEMPORAL, args.nontemporal)
+
+    cfg = wl.config(3)
+    counts, k, n = list(cfg.counts), cfg.k, cfg.n
+    threads = host_threads()
+    table = px.Table(counts)
+
+    # ---- synthetic inputs, resident in HBM before anything is timed
+    t_gen = time.perf_counter()
+    host_grads0 = None
+    grad_sets, pack_sets = [], []
+    keep = []
+    for s in range(max(1, args.sets)):
+        grads = wl.gaussian_workers(counts, cfg.grad_sigma, cfg.seed, "grad", k, step=s, threads=threads)
+        if s == 0:
+            host_grads0 = grads
+        d_g = [upload(g) for g in grads]
+        d_h = [[torch.empty(c, dtype=torch.float16, device="cuda") for c in counts] for _ in range(k)]
+        keep += [d_g, d_h]
+        grad_sets.append([table.bufset(g) for g in d_g])
+        pack_sets.append([table.bufset(h) for h in d_h])
+        if s > 0:
+            del grads
+    w = wl.gaussian_tensors(counts, cfg.param_sigma, cfg.seed, "param")
+    v = wl.zeros_tensors(counts)
+    d_w, d_v = upload(w), upload(v)
+    d_avg = [torch.empty(c, dtype=torch.float16, device="cuda") for c in counts]
+    s_w, s_v, s_avg = table.bufset(d_w), table.bufset(d_v), table.bufset(d_avg)
+    cfg5 = wl.config(5)
+    xs = wl.gaussian_workers(counts, cfg5.param_sigma, cfg5.seed, "worker", k, threads=threads)
+    c = wl.gaussian_tensors(counts, cfg5.param_sigma, cfg5.seed, "center")
+    d_xs, d_c = [upload(x) for x in xs], upload(c)
+    s_xs, s_c = [table.bufset(x) for x in d_xs], table.bufset(d_c)
+    alpha = float(np.float32(cfg5.alpha))
+    orders = wl.worker_orders(cfg5.seed, k, args.steps + args.warmup)
+    torch.cuda.synchronize()
+    t_gen = time.perf_counter() - t_gen
+
+    def step(i, ev=None):
+        s = i % len(grad_sets)
+        if ev:
+            ev[0].record()
+        px.pack_fp16(table, grad_sets[s], pack_sets[s])
+        if ev:
+            ev[1].record()
+        px.reduce_avg(table, pack_sets[s], s_avg, px.AVG)
+        if ev:
+            ev[2].record()
+        px.sgd_momentum(table, s_avg, s_w, s_v, cfg.lr, cfg.mu, cfg.wd)
+        if ev:
+            ev[3].record()
+        for j in orders[i]:
+            px.easgd(table, s_xs[int(j)], s_c, alpha)
+        if ev:
+            ev[4].record()
+
+    for i in range(args.warmup):
+        step(i)
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(args.warmup + i, events[i])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    stage_names = ["pack", "reduce", "update", "elastic"]
+    stage_ms = {nm: float(np.mean([events[i][q].elapsed_time(events[i][q + 1]) for i in range(args.steps)]))
+                for q, nm in enumerate(stage_names)}
+    # algorithmic bytes per step and per launch
+    stage_bytes = {"pack": 6 * k * n, "reduce": (2 * k + 2) * n, "update": 18 * n, "elastic": 16 * n * k}
+    launches = {"pack": 1, "reduce": 1, "update": 1, "elastic": k}
+    kernels = {"pack": "pxchg_convert_kernel<float,_Float16>", "reduce": "pxchg_reduce_avg_kernel<8,_Float16,_Float16>",
+               "update": "pxchg_sgd_momentum_kernel<_Float16>", "elastic": "pxchg_easgd_kernel<1>"}
+    stages = {}
+    for nm in stage_names:
+        per_launch_ms = stage_ms[nm] / launches[nm]
+        ach = stage_bytes[nm] / launches[nm] / (per_launch_ms * 1e-3) / 1e9
+        stages[nm] = {"kernel": kernels[nm], "launches_per_step": launches[nm], "ms_per_launch": round(per_launch_ms, 5),
+                      "algorithmic_bytes_per_launch": stage_bytes[nm] // launches[nm], "GBps": round(ach, 1),
+                      "frac_of_hbm_peak": round(ach / HBM_PEAK_GBPS, 4)}
+    dominant = max(stage_names, key=lambda nm: stage_ms[nm])
+    d = stages[dominant]
+    traffic = MEASURED_TRAFFIC_BYTES.get(dominant, (None, None))[0]
+    roofline = {"bound": "hbm", "kernel": d["kernel"], "achieved": d["GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                "frac": d["frac_of_hbm_peak"], "traffic": traffic,
+                "algorithmic_bytes_per_launch": d["algorithmic_bytes_per_launch"], "ms_per_launch": d["ms_per_launch"]}
+
+    ru_bytes = stage_bytes["reduce"] + stage_bytes["update"]
+    ru_ms = stage_ms["reduce"] + stage_ms["update"]
+    value = ru_bytes / (ru_ms * 1e-3) / 1e9
+    ms_per_step = wall / args.steps * 1e3
+    step_bytes = sum(stage_bytes.values())
+
+    # ---- fused variants (same arithmetic, fewer bytes), timed after the main region
+    fused = {}
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    for i in range(3):
+        px.reduce_avg_sgd_momentum(table, pack_sets[0], s_w, s_v, cfg.lr, cfg.mu, cfg.wd, px.AVG, px.F16)
+    ev[0].record()
+    for i in range(args.steps):
+        px.reduce_avg_sgd_momentum(table, pack_sets[i % len(pack_sets)], s_w, s_v, cfg.lr, cfg.mu, cfg.wd,
+                                   px.AVG, px.F16)
+    ev[1].record()
+    torch.cuda.synchronize()
+    ms = ev[0].elapsed_time(ev[1]) / args.steps
+    fb = (2 * k + 16) * n
+    fused["reduce_update"] = {"ms": round(ms, 5), "algorithmic_bytes": fb, "GBps": round(fb / ms / 1e6, 1),
+                              "frac_of_hbm_peak": round(fb / ms / 1e6 / HBM_PEAK_GBPS, 4)}
+    for i in range(3):
+        px.easgd_round(table, [s_xs[int(j)] for j in orders[i]], s_c, alpha)
+    ev[0].record()
+    for i in range(args.steps):
+        px.easgd_round(table, [s_xs[int(j)] for j in orders[i]], s_c, alpha)
+    ev[1].record()
+    torch.cuda.synchronize()
+    ms = ev[0].elapsed_time(ev[1]) / args.steps
+    fb = (8 * k + 8) * n
+    fused["elastic_round"] = {"ms": round(ms, 5), "algorithmic_bytes": fb, "GBps": round(fb / ms / 1e6, 1),
+                              "frac_of_hbm_peak": round(fb / ms / 1e6 / HBM_PEAK_GBPS, 4)}
+
+    # ---- plain device-to-device copy of 1 GiB as a reference for what HBM sustains here
+    src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+    dst = torch.empty_like(src)
+    for i in range(3):
+        dst.copy_(src)
+    ev[0].record()
+    for i in range(10):
+        dst.copy_(src)
+    ev[1].record()
+    torch.cuda.synchronize()
+    copy_gbps = 2 * src.numel() * 4 / (ev[0].elapsed_time(ev[1]) / 10) / 1e6
+    del src, dst
+
+    # ---- the oracle on the host cores, same workload (a baseline, not a target)
+    baseline = None
+    if not args.no_cpu_baseline:
+        t = cpu_baseline(counts, host_grads0, w, v, xs, c, [int(j) for j in orders[0]], cfg, alpha, threads)
+        cpu_ru = ru_bytes / (t["reduce"] + t["update"]) / 1e9
+        baseline = {"value": round(cpu_ru, 2), "unit": "GB/s", "cores": threads, "kind": "oracle",
+                    "sample": "the full workload, one step, element range split over the threads, best of 2 "
+                              "per stage (same byte accounting as the GPU figure)",
+                    "stage_seconds": {kk: round(vv, 4) for kk, vv in t.items()},
+                    "step_GBps": round(step_bytes / sum(t.values()) / 1e9, 2)}
+
+    out = {
+        "metric": "reduce+update GB/s on AlexNet-shaped 61M params, k=8 (fraction of HBM peak)",
+        "value": round(value, 1),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32 sums and updates, f16 transfer",
+        "data": "synthetic",
+        "config": {"workload": cfg.name, "n_params": n, "n_tensors": len(counts), "k": k,
+                   "step": "pack x8 -> reduce_avg f16->f16 -> sgd_momentum (f16 grad) -> 8 easgd meetings",
+                   "gradient_sets": len(grad_sets), "chunk_elems": px.get_option(px.OPT_CHUNK_ELEMS),
+                   "blocks_per_cu": px.get_option(px.OPT_BLOCKS_PER_CU),
+                   "nontemporal": px.get_option(px.OPT_NONTEMPORAL)},
+        "value_frac_of_hbm_peak": round(value / HBM_PEAK_GBPS, 4),
+        "reduce_update_ms": round(ru_ms, 5),
+        "step_GBps": round(step_bytes / (ms_per_step * 1e-3) / 1e9, 1),
+        "roofline": roofline,
+        "stages": stages,
+        "fused": fused,
+        "copy_reference": {"what": "torch copy_ of 1 GiB float32, read+write bytes", "GBps": round(copy_gbps, 1),
+                           "frac_of_hbm_peak": round(copy_gbps / HBM_PEAK_GBPS, 4)},
+        "cpu_baseline": baseline,
+        "setup_seconds": round(t_gen, 1),
+    }
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -14,7 +14,8 @@
  *
  * Conventions
  *   - Plain C ABI.  Every function returns a PXCHG_* status (0 = success) unless
- *     stated otherwise; nothing throws, aborts or synchronises the device.
+ *     stated otherwise; nothing throws or aborts, and only the two destroy calls
+ *     synchronise the device.
  *   - "host" / "device" says where a pointer must live.  Data buffers are device
  *     memory owned by the caller; the library owns only tables and buffer sets.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
@@ -58,12 +59,13 @@ enum pxchg_mode { PXCHG_AVG = 0, PXCHG_SUM = 1 };  /* divide the sum by k, or no
 /* Launch-shape controls (see pxchg_set_option). */
 enum pxchg_option {
     PXCHG_OPT_CHUNK_ELEMS = 0,   /* elements per work chunk for tables created afterwards;
-                                    multiple of 2048, 2048..1048576 */
-    PXCHG_OPT_BLOCKS_PER_CU = 1, /* 0: one workgroup per chunk; n>0: n persistent workgroups per
-                                    compute unit, each looping over chunks */
+                                    multiple of 512, 512..1048576; default 512 */
+    PXCHG_OPT_BLOCKS_PER_CU = 1, /* 0 (default): one workgroup per chunk; n>0: n persistent
+                                    workgroups per compute unit, each looping over chunks */
     PXCHG_OPT_CHECK_RANGES = 2,  /* 1 (default): pxchg_bufset_create verifies that each tensor lies
                                     inside one device allocation */
-    PXCHG_OPT_NONTEMPORAL = 3    /* 1: streaming loads/stores carry the non-temporal hint */
+    PXCHG_OPT_NONTEMPORAL = 3    /* -1 (default): each kernel's own measured-best policy; 0..3: bit 0
+                                    puts the non-temporal hint on vector loads, bit 1 on vector stores */
 };
 
 typedef struct pxchg_table pxchg_table;

@@ -9,13 +9,13 @@
 
 namespace {
 
-constexpr int64_t kMinChunk = 2048;
+constexpr int64_t kMinChunk = 512;
 constexpr int64_t kMaxChunk = 1 << 20;
 
 }  // namespace
 
 PxOptions &px_options() {
-    static PxOptions o = {/*chunk_elems=*/8192, /*blocks_per_cu=*/0, /*check_ranges=*/1, /*nontemporal=*/1};
+    static PxOptions o = {/*chunk_elems=*/512, /*blocks_per_cu=*/0, /*check_ranges=*/1, /*nontemporal=*/-1};
     return o;
 }
 
@@ -66,7 +66,7 @@ int pxchg_set_option(int option, int64_t value) {
             o.check_ranges = value;
             return PXCHG_OK;
         case PXCHG_OPT_NONTEMPORAL:
-            if (value != 0 && value != 1) return PXCHG_ERR_INVALID_ARG;
+            if (value < -1 || value > 3) return PXCHG_ERR_INVALID_ARG;
             o.nontemporal = value;
             return PXCHG_OK;
         default:

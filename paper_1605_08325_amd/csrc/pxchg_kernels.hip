@@ -28,7 +28,15 @@
 
 namespace {
 
-constexpr int BLOCK = 256;  // four wave64 per workgroup
+// One wavefront per workgroup and one 512-element chunk per workgroup measured
+// best on MI355X (more, smaller workgroups keep the window of addresses that is
+// in flight narrow); larger workgroups and several vector steps per lane were
+// measured slower.
+#ifndef PX_BLOCK
+#define PX_BLOCK 64
+#endif
+constexpr int BLOCK = PX_BLOCK;  // lanes per workgroup (a multiple of the 64-lane wavefront)
+static_assert(BLOCK % 64 == 0 && BLOCK >= PXCHG_MAX_K, "whole wavefronts, and one lane per worker in the any-k kernel");
 constexpr int UNIT = 8;     // elements one lane handles per vector step
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -55,53 +63,81 @@ struct F8 {
     float v[UNIT];
 };
 
-template <bool NT, typename V>
+template <int NT, typename V>
 __device__ __forceinline__ V ldv(const PX_GLOBAL V *p) {
-    if constexpr (NT)
+    if constexpr ((NT & 1) != 0)
         return __builtin_nontemporal_load(p);
     else
         return *p;
 }
-template <bool NT, typename V>
+template <int NT, typename V>
 __device__ __forceinline__ void stv(PX_GLOBAL V *p, V x) {
-    if constexpr (NT)
+    if constexpr ((NT & 2) != 0)
         __builtin_nontemporal_store(x, p);
     else
         *p = x;
 }
 
-// 8 consecutive elements as binary32; p is 16-byte aligned.
-template <bool NT>
-__device__ __forceinline__ F8 load8(const float *p) {
-    const f32x4 a = ldv<NT>((const PX_GLOBAL f32x4 *)p);
-    const f32x4 b = ldv<NT>((const PX_GLOBAL f32x4 *)p + 1);
+typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+
+// A lane's 8 elements are [i0, i0+4) and [i1, i1+4) of the chunk.  In the
+// contiguous layout (SPLIT = false) i1 == i0 + 4.  In the split layout the two
+// groups are 256 elements apart, so that each float32 memory instruction of a
+// wavefront covers one contiguous 1 KiB instead of every other 16 bytes of 2 KiB.
+// All group addresses are 16-byte aligned for float32 and 8-byte aligned for
+// binary16 (16-byte in the contiguous layout).
+template <int NT, bool SPLIT>
+__device__ __forceinline__ F8 load8(const float *p, int i0, int i1) {
+    const f32x4 a = ldv<NT>((const PX_GLOBAL f32x4 *)(p + i0));
+    const f32x4 b = ldv<NT>((const PX_GLOBAL f32x4 *)(p + i1));
     F8 r;
     r.v[0] = a.x; r.v[1] = a.y; r.v[2] = a.z; r.v[3] = a.w;
     r.v[4] = b.x; r.v[5] = b.y; r.v[6] = b.z; r.v[7] = b.w;
     return r;
 }
-template <bool NT>
-__device__ __forceinline__ F8 load8(const _Float16 *p) {
-    const f16x8 h = ldv<NT>((const PX_GLOBAL f16x8 *)p);
+template <int NT, bool SPLIT>
+__device__ __forceinline__ F8 load8(const _Float16 *p, int i0, int i1) {
     F8 r;
+    if constexpr (SPLIT) {
+        const f16x4 a = ldv<NT>((const PX_GLOBAL f16x4 *)(p + i0));
+        const f16x4 b = ldv<NT>((const PX_GLOBAL f16x4 *)(p + i1));
 #pragma unroll
-    for (int i = 0; i < UNIT; ++i) r.v[i] = (float)h[i];  // exact widening
+        for (int i = 0; i < 4; ++i) {  // exact widening
+            r.v[i] = (float)a[i];
+            r.v[4 + i] = (float)b[i];
+        }
+    } else {
+        const f16x8 h = ldv<NT>((const PX_GLOBAL f16x8 *)(p + i0));
+#pragma unroll
+        for (int i = 0; i < UNIT; ++i) r.v[i] = (float)h[i];  // exact widening
+    }
     return r;
 }
-template <bool NT>
-__device__ __forceinline__ void store8(float *p, const F8 &x) {
+template <int NT, bool SPLIT>
+__device__ __forceinline__ void store8(float *p, int i0, int i1, const F8 &x) {
     f32x4 a, b;
     a.x = x.v[0]; a.y = x.v[1]; a.z = x.v[2]; a.w = x.v[3];
     b.x = x.v[4]; b.y = x.v[5]; b.z = x.v[6]; b.w = x.v[7];
-    stv<NT>((PX_GLOBAL f32x4 *)p, a);
-    stv<NT>((PX_GLOBAL f32x4 *)p + 1, b);
+    stv<NT>((PX_GLOBAL f32x4 *)(p + i0), a);
+    stv<NT>((PX_GLOBAL f32x4 *)(p + i1), b);
 }
-template <bool NT>
-__device__ __forceinline__ void store8(_Float16 *p, const F8 &x) {
-    f16x8 h;
+template <int NT, bool SPLIT>
+__device__ __forceinline__ void store8(_Float16 *p, int i0, int i1, const F8 &x) {
+    if constexpr (SPLIT) {
+        f16x4 a, b;
 #pragma unroll
-    for (int i = 0; i < UNIT; ++i) h[i] = (_Float16)x.v[i];  // round to nearest even
-    stv<NT>((PX_GLOBAL f16x8 *)p, h);
+        for (int i = 0; i < 4; ++i) {  // round to nearest even
+            a[i] = (_Float16)x.v[i];
+            b[i] = (_Float16)x.v[4 + i];
+        }
+        stv<NT>((PX_GLOBAL f16x4 *)(p + i0), a);
+        stv<NT>((PX_GLOBAL f16x4 *)(p + i1), b);
+    } else {
+        f16x8 h;
+#pragma unroll
+        for (int i = 0; i < UNIT; ++i) h[i] = (_Float16)x.v[i];  // round to nearest even
+        stv<NT>((PX_GLOBAL f16x8 *)(p + i0), h);
+    }
 }
 __device__ __forceinline__ float load1(const float *p) { return *(const PX_GLOBAL float *)p; }
 __device__ __forceinline__ float load1(const _Float16 *p) { return (float)*(const PX_GLOBAL _Float16 *)p; }
@@ -112,20 +148,56 @@ __device__ __forceinline__ void store1(_Float16 *p, float x) { *(PX_GLOBAL _Floa
 __device__ __forceinline__ int head_of(uintptr_t a, int es) { return (int)(((16u - (unsigned)(a & 15u)) & 15u) / (unsigned)es); }
 __device__ __forceinline__ bool aligned_after(uintptr_t a, int es, int head) { return ((a + (uintptr_t)head * es) & 15u) == 0; }
 
+// One vector step of a lane: every load is issued before the first use, then the
+// arithmetic, then the stores.
+template <bool SP, class Op>
+__device__ __forceinline__ void vector_step(const Op &op, int i0, int i1) {
+    typename Op::State st;
+    op.template load<SP>(st, i0, i1);
+    op.compute(st);
+    op.template store<SP>(st, i0, i1);
+}
+
 // Walks one chunk: an element-wise head until every operand is 16-byte aligned,
 // 8-element vector steps, an element-wise tail.  `head` < 0 means the operands
 // cannot be aligned together and the whole chunk goes element by element.
-template <class Op>
-__device__ __forceinline__ void run_chunk(Op &op, int len, int head) {
+// The vector part is cut into 512-element tiles (one vector step of a whole
+// wavefront); with SPLIT, tiles use the split lane layout.  What is left after
+// the last full tile goes in the contiguous layout.
+template <bool SPLIT, class Op>
+__device__ __forceinline__ void run_chunk(const Op &op, int len, int head) {
     const int tid = threadIdx.x;
     if (head < 0 || head > len) {
         for (int i = tid; i < len; i += BLOCK) op.scalar(i);
         return;
     }
     for (int i = tid; i < head; i += BLOCK) op.scalar(i);
+    constexpr int TILE = 64 * UNIT;
+    constexpr int WAVES = BLOCK / 64;
     const int nvec = (len - head) / UNIT;
-    for (int u = tid; u < nvec; u += BLOCK) op.vector(head + u * UNIT);
+    const int ntile = nvec / 64;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int lane_off = SPLIT ? lane * 4 : lane * UNIT;
+    constexpr int second = SPLIT ? 64 * 4 : 4;
+    for (int t = wave; t < ntile; t += WAVES) {
+        const int i0 = head + t * TILE + lane_off;
+        vector_step<SPLIT>(op, i0, i0 + second);
+    }
+    for (int u = ntile * 64 + tid; u < nvec; u += BLOCK) {
+        const int i0 = head + u * UNIT;
+        vector_step<false>(op, i0, i0 + 4);
+    }
     for (int i = head + nvec * UNIT + tid; i < len; i += BLOCK) op.scalar(i);
+}
+
+#ifndef PX_SPLIT
+#define PX_SPLIT 1
+#endif
+// Kernels that touch float32 arrays use the split layout; a pure binary16 kernel
+// already moves one contiguous 1 KiB per wavefront instruction.
+template <typename... T>
+constexpr bool use_split() {
+    return PX_SPLIT && (std::is_same<T, float>::value || ...);
 }
 
 __device__ __forceinline__ void scale_sum8(F8 &s, int use_div, float kf, float scale);
@@ -169,17 +241,24 @@ struct ConvertArgs {
     void *const *dst[PXCHG_MAX_K];
 };
 
-template <typename TI, typename TO, bool NT>
+template <typename TI, typename TO, int NT>
 struct ConvertOp {
     const TI *src;
     TO *dst;
-    __device__ __forceinline__ void scalar(int i) { store1(dst + i, load1(src + i)); }
-    __device__ __forceinline__ void vector(int i) { store8<NT>(dst + i, load8<NT>(src + i)); }
+    __device__ __forceinline__ void scalar(int i) const { store1(dst + i, load1(src + i)); }
+    struct State {
+        F8 x;
+    };
+    template <bool SP>
+    __device__ __forceinline__ void load(State &st, int i0, int i1) const { st.x = load8<NT, SP>(src, i0, i1); }
+    __device__ __forceinline__ void compute(State &) const {}
+    template <bool SP>
+    __device__ __forceinline__ void store(const State &st, int i0, int i1) const { store8<NT, SP>(dst, i0, i1, st.x); }
 };
 
 // Converts every tensor of every worker between binary32 and binary16.  The
 // grid covers k x n_chunks virtual chunks, worker-major.
-template <typename TI, typename TO, bool NT>
+template <typename TI, typename TO, int NT>
 __global__ __launch_bounds__(BLOCK) void pxchg_convert_kernel(const PxChunk *__restrict__ chunks, int n_chunks,
                                                               int64_t n_virtual, ConvertArgs args) {
     for (int64_t vc = blockIdx.x; vc < n_virtual; vc += gridDim.x) {
@@ -190,7 +269,7 @@ __global__ __launch_bounds__(BLOCK) void pxchg_convert_kernel(const PxChunk *__r
         op.dst = table_ptr<TO>(args.dst[w], ch.tensor) + ch.start;
         int head = head_of((uintptr_t)op.dst, sizeof(TO));
         if (!aligned_after((uintptr_t)op.src, sizeof(TI), head)) head = -1;
-        run_chunk(op, ch.len, head);
+        run_chunk<use_split<TI, TO>()>(op, ch.len, head);
     }
 }
 
@@ -205,67 +284,81 @@ struct ReduceArgs {
     float scale;
 };
 
-template <int K, typename TI, typename TO, bool NT>
+template <int K, typename TI, typename TO, int NT>
 struct ReduceOp {
     const TI *src[K];
     TO *dst;
     int use_div;
     float kf, scale;
-    __device__ __forceinline__ void scalar(int i) {
+    __device__ __forceinline__ void scalar(int i) const {
         float s = load1(src[0] + i);
 #pragma unroll
         for (int w = 1; w < K; ++w) s = s + load1(src[w] + i);
         store1(dst + i, scale_sum(s, use_div, kf, scale));
     }
-    __device__ __forceinline__ void vector(int i) {
+    struct State {
         F8 c[K];
+    };
+    template <bool SP>
+    __device__ __forceinline__ void load(State &st, int i0, int i1) const {
 #pragma unroll
-        for (int w = 0; w < K; ++w) c[w] = load8<NT>(src[w] + i);  // all loads first
-        F8 s = c[0];
+        for (int w = 0; w < K; ++w) st.c[w] = load8<NT, SP>(src[w], i0, i1);
+    }
+    __device__ __forceinline__ void compute(State &st) const {
 #pragma unroll
         for (int w = 1; w < K; ++w)
 #pragma unroll
-            for (int e = 0; e < UNIT; ++e) s.v[e] = s.v[e] + c[w].v[e];  // worker order
-        scale_sum8(s, use_div, kf, scale);
-        store8<NT>(dst + i, s);
+            for (int e = 0; e < UNIT; ++e) st.c[0].v[e] = st.c[0].v[e] + st.c[w].v[e];  // worker order
+        scale_sum8(st.c[0], use_div, kf, scale);
+    }
+    template <bool SP>
+    __device__ __forceinline__ void store(const State &st, int i0, int i1) const {
+        store8<NT, SP>(dst, i0, i1, st.c[0]);
     }
 };
 
 // Any k up to PXCHG_MAX_K: the chunk's k source pointers sit in LDS.
-template <typename TI, typename TO, bool NT>
+template <typename TI, typename TO, int NT>
 struct ReduceOpAnyK {
     const TI *const *src;  // LDS
     TO *dst;
     int k, use_div;
     float kf, scale;
-    __device__ __forceinline__ void scalar(int i) {
+    __device__ __forceinline__ void scalar(int i) const {
         float s = load1(src[0] + i);
         for (int w = 1; w < k; ++w) s = s + load1(src[w] + i);
         store1(dst + i, scale_sum(s, use_div, kf, scale));
     }
-    __device__ __forceinline__ void vector(int i) {
-        F8 s = load8<NT>(src[0] + i);
+    struct State {
+        F8 s;
+    };
+    // any k: the sum is formed while loading, four contributions at a time
+    template <bool SP>
+    __device__ __forceinline__ void load(State &st, int i0, int i1) const {
+        F8 s = load8<NT, SP>(src[0], i0, i1);
         int w = 1;
         for (; w + 4 <= k; w += 4) {
             F8 c[4];
 #pragma unroll
-            for (int q = 0; q < 4; ++q) c[q] = load8<NT>(src[w + q] + i);
+            for (int q = 0; q < 4; ++q) c[q] = load8<NT, SP>(src[w + q], i0, i1);
 #pragma unroll
             for (int q = 0; q < 4; ++q)
 #pragma unroll
                 for (int e = 0; e < UNIT; ++e) s.v[e] = s.v[e] + c[q].v[e];
         }
         for (; w < k; ++w) {
-            const F8 c = load8<NT>(src[w] + i);
+            const F8 c = load8<NT, SP>(src[w], i0, i1);
 #pragma unroll
             for (int e = 0; e < UNIT; ++e) s.v[e] = s.v[e] + c.v[e];
         }
-        scale_sum8(s, use_div, kf, scale);
-        store8<NT>(dst + i, s);
+        st.s = s;
     }
+    __device__ __forceinline__ void compute(State &st) const { scale_sum8(st.s, use_div, kf, scale); }
+    template <bool SP>
+    __device__ __forceinline__ void store(const State &st, int i0, int i1) const { store8<NT, SP>(dst, i0, i1, st.s); }
 };
 
-template <int K, typename TI, typename TO, bool NT>
+template <int K, typename TI, typename TO, int NT>
 __global__ __launch_bounds__(BLOCK) void pxchg_reduce_avg_kernel(const PxChunk *__restrict__ chunks, int n_chunks,
                                                                  ReduceArgs args) {
     for (int c = blockIdx.x; c < n_chunks; c += gridDim.x) {
@@ -281,11 +374,11 @@ __global__ __launch_bounds__(BLOCK) void pxchg_reduce_avg_kernel(const PxChunk *
             op.src[w] = table_ptr<const TI>(args.contrib[w], ch.tensor) + ch.start;
             if (!aligned_after((uintptr_t)op.src[w], sizeof(TI), head)) head = -1;
         }
-        run_chunk(op, ch.len, head);
+        run_chunk<use_split<TI, TO>()>(op, ch.len, head);
     }
 }
 
-template <typename TI, typename TO, bool NT>
+template <typename TI, typename TO, int NT>
 __global__ __launch_bounds__(BLOCK) void pxchg_reduce_avg_anyk_kernel(const PxChunk *__restrict__ chunks, int n_chunks,
                                                                       ReduceArgs args) {
     __shared__ const TI *sp[PXCHG_MAX_K];
@@ -309,7 +402,7 @@ __global__ __launch_bounds__(BLOCK) void pxchg_reduce_avg_anyk_kernel(const PxCh
         }
         __syncthreads();
         op.src = sp;
-        run_chunk(op, ch.len, s_head);
+        run_chunk<use_split<TI, TO>()>(op, ch.len, s_head);
     }
 }
 
@@ -322,29 +415,38 @@ struct UpdateArgs {
     float lr, mu, wd;
 };
 
-template <typename TG, bool NT>
+template <typename TG, int NT>
 struct UpdateOp {
     const TG *g;
     float *w, *v;
     float lr, mu, wd;
-    __device__ __forceinline__ void scalar(int i) {
+    __device__ __forceinline__ void scalar(int i) const {
         float wi = load1(w + i), vi = load1(v + i);
         momentum_step(load1(g + i), wi, vi, lr, mu, wd);
         store1(v + i, vi);
         store1(w + i, wi);
     }
-    __device__ __forceinline__ void vector(int i) {
-        const F8 a = load8<NT>(g + i);
-        F8 ww = load8<NT>(w + i);
-        F8 vv = load8<NT>(v + i);
+    struct State {
+        F8 a, ww, vv;
+    };
+    template <bool SP>
+    __device__ __forceinline__ void load(State &st, int i0, int i1) const {
+        st.a = load8<NT, SP>(g, i0, i1);
+        st.ww = load8<NT, SP>(w, i0, i1);
+        st.vv = load8<NT, SP>(v, i0, i1);
+    }
+    __device__ __forceinline__ void compute(State &st) const {
 #pragma unroll
-        for (int e = 0; e < UNIT; ++e) momentum_step(a.v[e], ww.v[e], vv.v[e], lr, mu, wd);
-        store8<NT>(v + i, vv);
-        store8<NT>(w + i, ww);
+        for (int e = 0; e < UNIT; ++e) momentum_step(st.a.v[e], st.ww.v[e], st.vv.v[e], lr, mu, wd);
+    }
+    template <bool SP>
+    __device__ __forceinline__ void store(const State &st, int i0, int i1) const {
+        store8<NT, SP>(v, i0, i1, st.vv);
+        store8<NT, SP>(w, i0, i1, st.ww);
     }
 };
 
-template <typename TG, bool NT>
+template <typename TG, int NT>
 __global__ __launch_bounds__(BLOCK) void pxchg_sgd_momentum_kernel(const PxChunk *__restrict__ chunks, int n_chunks,
                                                                    UpdateArgs args) {
     for (int c = blockIdx.x; c < n_chunks; c += gridDim.x) {
@@ -358,7 +460,7 @@ __global__ __launch_bounds__(BLOCK) void pxchg_sgd_momentum_kernel(const PxChunk
         op.wd = args.wd;
         int head = head_of((uintptr_t)op.g, sizeof(TG));
         if (!aligned_after((uintptr_t)op.w, 4, head) || !aligned_after((uintptr_t)op.v, 4, head)) head = -1;
-        run_chunk(op, ch.len, head);
+        run_chunk<use_split<float>()>(op, ch.len, head);
     }
 }
 
@@ -374,7 +476,7 @@ struct FusedArgs {
     float lr, mu, wd;
 };
 
-template <int K, typename TI, bool WIRE16, bool NT>
+template <int K, typename TI, bool WIRE16, int NT>
 struct FusedOp {
     const TI *src[K];
     float *w, *v;
@@ -386,7 +488,7 @@ struct FusedOp {
         else
             return a;
     }
-    __device__ __forceinline__ void scalar(int i) {
+    __device__ __forceinline__ void scalar(int i) const {
         float s = load1(src[0] + i);
 #pragma unroll
         for (int q = 1; q < K; ++q) s = s + load1(src[q] + i);
@@ -395,26 +497,33 @@ struct FusedOp {
         store1(v + i, vi);
         store1(w + i, wi);
     }
-    __device__ __forceinline__ void vector(int i) {
-        F8 c[K];
+    struct State {
+        F8 c[K], ww, vv;
+    };
+    template <bool SP>
+    __device__ __forceinline__ void load(State &st, int i0, int i1) const {
 #pragma unroll
-        for (int q = 0; q < K; ++q) c[q] = load8<NT>(src[q] + i);
-        F8 ww = load8<NT>(w + i);
-        F8 vv = load8<NT>(v + i);
-        F8 s = c[0];
+        for (int q = 0; q < K; ++q) st.c[q] = load8<NT, SP>(src[q], i0, i1);
+        st.ww = load8<NT, SP>(w, i0, i1);
+        st.vv = load8<NT, SP>(v, i0, i1);
+    }
+    __device__ __forceinline__ void compute(State &st) const {
 #pragma unroll
         for (int q = 1; q < K; ++q)
 #pragma unroll
-            for (int e = 0; e < UNIT; ++e) s.v[e] = s.v[e] + c[q].v[e];
-        scale_sum8(s, use_div, kf, scale);
+            for (int e = 0; e < UNIT; ++e) st.c[0].v[e] = st.c[0].v[e] + st.c[q].v[e];  // worker order
+        scale_sum8(st.c[0], use_div, kf, scale);
 #pragma unroll
-        for (int e = 0; e < UNIT; ++e) momentum_step(wire(s.v[e]), ww.v[e], vv.v[e], lr, mu, wd);
-        store8<NT>(v + i, vv);
-        store8<NT>(w + i, ww);
+        for (int e = 0; e < UNIT; ++e) momentum_step(wire(st.c[0].v[e]), st.ww.v[e], st.vv.v[e], lr, mu, wd);
+    }
+    template <bool SP>
+    __device__ __forceinline__ void store(const State &st, int i0, int i1) const {
+        store8<NT, SP>(v, i0, i1, st.vv);
+        store8<NT, SP>(w, i0, i1, st.ww);
     }
 };
 
-template <int K, typename TI, bool WIRE16, bool NT>
+template <int K, typename TI, bool WIRE16, int NT>
 __global__ __launch_bounds__(BLOCK) void pxchg_reduce_avg_sgd_momentum_kernel(const PxChunk *__restrict__ chunks,
                                                                               int n_chunks, FusedArgs args) {
     for (int c = blockIdx.x; c < n_chunks; c += gridDim.x) {
@@ -436,7 +545,7 @@ __global__ __launch_bounds__(BLOCK) void pxchg_reduce_avg_sgd_momentum_kernel(co
             if (!aligned_after((uintptr_t)op.src[q], sizeof(TI), head)) head = -1;
         }
         if (!aligned_after((uintptr_t)op.w, 4, head) || !aligned_after((uintptr_t)op.v, 4, head)) head = -1;
-        run_chunk(op, ch.len, head);
+        run_chunk<use_split<float>()>(op, ch.len, head);
     }
 }
 
@@ -449,12 +558,12 @@ struct ElasticArgs {
     float alpha;
 };
 
-template <int K, bool NT>
+template <int K, int NT>
 struct ElasticOp {
     float *x[K];
     float *c;
     float alpha;
-    __device__ __forceinline__ void scalar(int i) {
+    __device__ __forceinline__ void scalar(int i) const {
         float ci = load1(c + i);
 #pragma unroll
         for (int q = 0; q < K; ++q) {
@@ -464,22 +573,30 @@ struct ElasticOp {
         }
         store1(c + i, ci);
     }
-    __device__ __forceinline__ void vector(int i) {
-        F8 xs[K];
+    struct State {
+        F8 xs[K], cc;
+    };
+    template <bool SP>
+    __device__ __forceinline__ void load(State &st, int i0, int i1) const {
 #pragma unroll
-        for (int q = 0; q < K; ++q) xs[q] = load8<NT>(x[q] + i);
-        F8 cc = load8<NT>(c + i);
+        for (int q = 0; q < K; ++q) st.xs[q] = load8<NT, SP>(x[q], i0, i1);
+        st.cc = load8<NT, SP>(c, i0, i1);
+    }
+    __device__ __forceinline__ void compute(State &st) const {
 #pragma unroll
-        for (int q = 0; q < K; ++q) {  // arrival order: the center carries over
+        for (int q = 0; q < K; ++q)  // arrival order: the center carries over
 #pragma unroll
-            for (int e = 0; e < UNIT; ++e) elastic_step(xs[q].v[e], cc.v[e], alpha);
-            store8<NT>(x[q] + i, xs[q]);
-        }
-        store8<NT>(c + i, cc);
+            for (int e = 0; e < UNIT; ++e) elastic_step(st.xs[q].v[e], st.cc.v[e], alpha);
+    }
+    template <bool SP>
+    __device__ __forceinline__ void store(const State &st, int i0, int i1) const {
+#pragma unroll
+        for (int q = 0; q < K; ++q) store8<NT, SP>(x[q], i0, i1, st.xs[q]);
+        store8<NT, SP>(c, i0, i1, st.cc);
     }
 };
 
-template <int K, bool NT>
+template <int K, int NT>
 __global__ __launch_bounds__(BLOCK) void pxchg_easgd_kernel(const PxChunk *__restrict__ chunks, int n_chunks,
                                                             ElasticArgs args) {
     for (int c = blockIdx.x; c < n_chunks; c += gridDim.x) {
@@ -493,7 +610,7 @@ __global__ __launch_bounds__(BLOCK) void pxchg_easgd_kernel(const PxChunk *__res
             op.x[q] = table_ptr<float>(args.x[q], ch.tensor) + ch.start;
             if (!aligned_after((uintptr_t)op.x[q], 4, head)) head = -1;
         }
-        run_chunk(op, ch.len, head);
+        run_chunk<use_split<float>()>(op, ch.len, head);
     }
 }
 
@@ -501,18 +618,34 @@ __global__ __launch_bounds__(BLOCK) void pxchg_easgd_kernel(const PxChunk *__res
 
 struct Launch {
     dim3 grid;
-    bool nt;
+    int nt;  // bit 0: non-temporal loads, bit 1: non-temporal stores
 };
 
-Launch launch_shape(const pxchg_table *t, int64_t n_virtual) {
+// `nt_default` is the kernel's own measured-best policy, used unless the caller
+// set PXCHG_OPT_NONTEMPORAL to 0..3.
+Launch launch_shape(const pxchg_table *t, int64_t n_virtual, int nt_default) {
     const PxOptions &o = px_options();
-    int64_t g = n_virtual;
+    int64_t g = std::min<int64_t>(n_virtual, (int64_t)1 << 24);  // the kernels loop over what is left
     if (o.blocks_per_cu > 0) g = std::min<int64_t>(g, (int64_t)px_cu_count(t->device) * o.blocks_per_cu);
     Launch l;
     l.grid = dim3((unsigned)g, 1, 1);
-    l.nt = o.nontemporal != 0;
+    l.nt = o.nontemporal < 0 ? nt_default : ((int)o.nontemporal & 3);
     return l;
 }
+
+// Measured on MI355X (AlexNet-shaped set, k = 8): the hint on loads helps every
+// kernel; on stores it helps the ones that write a large share of their traffic
+// and slightly hurts the reduce, which writes one byte in nine.
+constexpr int NT_LOADS = 1, NT_STORES = 2, NT_BOTH = 3;
+
+// Expands CALL(n) for the run-time non-temporal policy n = 0..3.
+#define PX_DISPATCH_NT(nt, CALL) \
+    switch (nt) {                \
+        case 0: CALL(0); break;  \
+        case 1: CALL(1); break;  \
+        case 2: CALL(2); break;  \
+        default: CALL(3); break; \
+    }
 
 int check_table(const pxchg_table *t) {
     if (!px_valid(t)) return PXCHG_ERR_INVALID_ARG;
@@ -557,29 +690,30 @@ int launch_convert(const pxchg_table *t, int k, const pxchg_bufset *const *src, 
             if (dst[i] == dst[j]) return PXCHG_ERR_INVALID_ARG;
     if (t->n_chunks == 0) return PXCHG_OK;
     const int64_t n_virtual = t->n_chunks * k;
-    const Launch l = launch_shape(t, n_virtual);
-    if (l.nt)
-        hipLaunchKernelGGL((pxchg_convert_kernel<TI, TO, true>), l.grid, dim3(BLOCK), 0, stream, t->d_chunks,
-                           (int)t->n_chunks, n_virtual, a);
-    else
-        hipLaunchKernelGGL((pxchg_convert_kernel<TI, TO, false>), l.grid, dim3(BLOCK), 0, stream, t->d_chunks,
-                           (int)t->n_chunks, n_virtual, a);
+    // narrowing (pack) reads two bytes for each one written and likes the hint on
+    // both sides; widening (unpack) writes twice what it reads and measured best
+    // with the hint on the stores only
+    const Launch l = launch_shape(t, n_virtual, sizeof(TO) < sizeof(TI) ? NT_BOTH : NT_STORES);
+#define PX_CALL(N)                                                                                            \
+    hipLaunchKernelGGL((pxchg_convert_kernel<TI, TO, N>), l.grid, dim3(BLOCK), 0, stream, t->d_chunks,         \
+                       (int)t->n_chunks, n_virtual, a)
+    PX_DISPATCH_NT(l.nt, PX_CALL)
+#undef PX_CALL
     return after_launch();
 }
 
 template <int K, typename TI, typename TO>
 void launch_reduce_k(const pxchg_table *t, const Launch &l, const ReduceArgs &a, hipStream_t stream) {
-    if (l.nt)
-        hipLaunchKernelGGL((pxchg_reduce_avg_kernel<K, TI, TO, true>), l.grid, dim3(BLOCK), 0, stream, t->d_chunks,
-                           (int)t->n_chunks, a);
-    else
-        hipLaunchKernelGGL((pxchg_reduce_avg_kernel<K, TI, TO, false>), l.grid, dim3(BLOCK), 0, stream, t->d_chunks,
-                           (int)t->n_chunks, a);
+#define PX_CALL(N)                                                                                            \
+    hipLaunchKernelGGL((pxchg_reduce_avg_kernel<K, TI, TO, N>), l.grid, dim3(BLOCK), 0, stream, t->d_chunks,   \
+                       (int)t->n_chunks, a)
+    PX_DISPATCH_NT(l.nt, PX_CALL)
+#undef PX_CALL
 }
 
 template <typename TI, typename TO>
 void launch_reduce(const pxchg_table *t, int k, const ReduceArgs &a, hipStream_t stream) {
-    const Launch l = launch_shape(t, t->n_chunks);
+    const Launch l = launch_shape(t, t->n_chunks, NT_LOADS);
     switch (k) {
         case 1: launch_reduce_k<1, TI, TO>(t, l, a, stream); break;
         case 2: launch_reduce_k<2, TI, TO>(t, l, a, stream); break;
@@ -589,32 +723,36 @@ void launch_reduce(const pxchg_table *t, int k, const ReduceArgs &a, hipStream_t
         case 6: launch_reduce_k<6, TI, TO>(t, l, a, stream); break;
         case 7: launch_reduce_k<7, TI, TO>(t, l, a, stream); break;
         case 8: launch_reduce_k<8, TI, TO>(t, l, a, stream); break;
-        default:
-            if (l.nt)
-                hipLaunchKernelGGL((pxchg_reduce_avg_anyk_kernel<TI, TO, true>), l.grid, dim3(BLOCK), 0, stream,
-                                   t->d_chunks, (int)t->n_chunks, a);
-            else
-                hipLaunchKernelGGL((pxchg_reduce_avg_anyk_kernel<TI, TO, false>), l.grid, dim3(BLOCK), 0, stream,
-                                   t->d_chunks, (int)t->n_chunks, a);
+        default: {
+#define PX_CALL(N)                                                                                            \
+    hipLaunchKernelGGL((pxchg_reduce_avg_anyk_kernel<TI, TO, N>), l.grid, dim3(BLOCK), 0, stream, t->d_chunks, \
+                       (int)t->n_chunks, a)
+            PX_DISPATCH_NT(l.nt, PX_CALL)
+#undef PX_CALL
+        }
     }
 }
 
 template <int K, typename TI>
 void launch_fused_k(const pxchg_table *t, const Launch &l, const FusedArgs &a, bool wire16, hipStream_t stream) {
-#define PX_FUSED(W, N)                                                                                              \
-    hipLaunchKernelGGL((pxchg_reduce_avg_sgd_momentum_kernel<K, TI, W, N>), l.grid, dim3(BLOCK), 0, stream,         \
+#define PX_CALL16(N)                                                                                          \
+    hipLaunchKernelGGL((pxchg_reduce_avg_sgd_momentum_kernel<K, TI, true, N>), l.grid, dim3(BLOCK), 0, stream, \
+                       t->d_chunks, (int)t->n_chunks, a)
+#define PX_CALL32(N)                                                                                           \
+    hipLaunchKernelGGL((pxchg_reduce_avg_sgd_momentum_kernel<K, TI, false, N>), l.grid, dim3(BLOCK), 0, stream, \
                        t->d_chunks, (int)t->n_chunks, a)
     if (wire16) {
-        if (l.nt) PX_FUSED(true, true); else PX_FUSED(true, false);
+        PX_DISPATCH_NT(l.nt, PX_CALL16)
     } else {
-        if (l.nt) PX_FUSED(false, true); else PX_FUSED(false, false);
+        PX_DISPATCH_NT(l.nt, PX_CALL32)
     }
-#undef PX_FUSED
+#undef PX_CALL16
+#undef PX_CALL32
 }
 
 template <typename TI>
 int launch_fused(const pxchg_table *t, int k, const FusedArgs &a, bool wire16, hipStream_t stream) {
-    const Launch l = launch_shape(t, t->n_chunks);
+    const Launch l = launch_shape(t, t->n_chunks, NT_BOTH);
     switch (k) {
         case 1: launch_fused_k<1, TI>(t, l, a, wire16, stream); break;
         case 2: launch_fused_k<2, TI>(t, l, a, wire16, stream); break;
@@ -631,10 +769,10 @@ int launch_fused(const pxchg_table *t, int k, const FusedArgs &a, bool wire16, h
 
 template <int K>
 void launch_elastic_k(const pxchg_table *t, const Launch &l, const ElasticArgs &a, hipStream_t stream) {
-    if (l.nt)
-        hipLaunchKernelGGL((pxchg_easgd_kernel<K, true>), l.grid, dim3(BLOCK), 0, stream, t->d_chunks, (int)t->n_chunks, a);
-    else
-        hipLaunchKernelGGL((pxchg_easgd_kernel<K, false>), l.grid, dim3(BLOCK), 0, stream, t->d_chunks, (int)t->n_chunks, a);
+#define PX_CALL(N) \
+    hipLaunchKernelGGL((pxchg_easgd_kernel<K, N>), l.grid, dim3(BLOCK), 0, stream, t->d_chunks, (int)t->n_chunks, a)
+    PX_DISPATCH_NT(l.nt, PX_CALL)
+#undef PX_CALL
 }
 
 void fill_scale(int k, int mode, int *use_div, float *kf, float *scale) {
@@ -709,17 +847,21 @@ int pxchg_sgd_momentum(const pxchg_table *table, const pxchg_bufset *grad, pxchg
     a.lr = lr;
     a.mu = mu;
     a.wd = wd;
-    const Launch l = launch_shape(table, table->n_chunks);
+    const Launch l = launch_shape(table, table->n_chunks, NT_BOTH);
     hipStream_t s = (hipStream_t)stream;
-#define PX_UPD(T, N)                                                                                       \
-    hipLaunchKernelGGL((pxchg_sgd_momentum_kernel<T, N>), l.grid, dim3(BLOCK), 0, s, table->d_chunks,       \
+#define PX_CALL32(N)                                                                                      \
+    hipLaunchKernelGGL((pxchg_sgd_momentum_kernel<float, N>), l.grid, dim3(BLOCK), 0, s, table->d_chunks,  \
+                       (int)table->n_chunks, a)
+#define PX_CALL16(N)                                                                                        \
+    hipLaunchKernelGGL((pxchg_sgd_momentum_kernel<_Float16, N>), l.grid, dim3(BLOCK), 0, s, table->d_chunks, \
                        (int)table->n_chunks, a)
     if (grad->dtype == PXCHG_F32) {
-        if (l.nt) PX_UPD(float, true); else PX_UPD(float, false);
+        PX_DISPATCH_NT(l.nt, PX_CALL32)
     } else {
-        if (l.nt) PX_UPD(_Float16, true); else PX_UPD(_Float16, false);
+        PX_DISPATCH_NT(l.nt, PX_CALL16)
     }
-#undef PX_UPD
+#undef PX_CALL32
+#undef PX_CALL16
     return after_launch();
 }
 
@@ -773,7 +915,7 @@ int pxchg_easgd_round(const pxchg_table *table, int k, pxchg_bufset *const *x, p
     }
     if (table->n_chunks == 0) return PXCHG_OK;
     hipStream_t s = (hipStream_t)stream;
-    const Launch l = launch_shape(table, table->n_chunks);
+    const Launch l = launch_shape(table, table->n_chunks, NT_BOTH);
     // More than 8 workers: successive launches of up to 8, the center carried
     // through memory between them (same arithmetic, same order).
     for (int i0 = 0; i0 < k; i0 += 8) {
