@@ -43,7 +43,11 @@ HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E, published peak
 # HBM traffic per launch from hardware counters (FETCH_SIZE + WRITE_SIZE, scaled by
 # what the same counters read for a plain copy of known size); see the files named.
 MEASURED_TRAFFIC_BYTES = {
-    # kernel: (bytes per launch, profile summary it comes from)
+    # stage: (bytes per launch, profile summary it comes from)
+    "pack": (2_839_981_023, "profiles/bench_alexnet_k8_hbm_counters.txt"),
+    "reduce": (1_054_221_501, "profiles/bench_alexnet_k8_hbm_counters.txt"),
+    "update": (1_075_782_159, "profiles/bench_alexnet_k8_hbm_counters.txt"),
+    "elastic": (961_125_916, "profiles/bench_alexnet_k8_hbm_counters.txt"),
 }
 
 
@@ -221,7 +225,8 @@ def main() -> int:
         ach = stage_bytes[nm] / launches[nm] / (per_launch_ms * 1e-3) / 1e9
         stages[nm] = {"kernel": kernels[nm], "launches_per_step": launches[nm], "ms_per_launch": round(per_launch_ms, 5),
                       "algorithmic_bytes_per_launch": stage_bytes[nm] // launches[nm], "GBps": round(ach, 1),
-                      "frac_of_hbm_peak": round(ach / HBM_PEAK_GBPS, 4)}
+                      "frac_of_hbm_peak": round(ach / HBM_PEAK_GBPS, 4),
+                      "traffic": MEASURED_TRAFFIC_BYTES.get(nm, (None, None))[0]}
     dominant = max(stage_names, key=lambda nm: stage_ms[nm])
     d = stages[dominant]
     traffic = MEASURED_TRAFFIC_BYTES.get(dominant, (None, None))[0]
@@ -262,18 +267,20 @@ def main() -> int:
     fused["elastic_round"] = {"ms": round(ms, 5), "algorithmic_bytes": fb, "GBps": round(fb / ms / 1e6, 1),
                               "frac_of_hbm_peak": round(fb / ms / 1e6 / HBM_PEAK_GBPS, 4)}
 
-    # ---- plain device-to-device copy of 1 GiB as a reference for what HBM sustains here
-    src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
-    dst = torch.empty_like(src)
+    # ---- a plain copy through the same kernel family (k = 1, no divide: out = in) as a
+    # reference for what HBM sustains here, and as the known-size kernel that the
+    # hardware-counter readings are scaled by
+    d_copy = [torch.empty(c_, dtype=torch.float32, device="cuda") for c_ in counts]
+    s_copy = table.bufset(d_copy)
     for i in range(3):
-        dst.copy_(src)
+        px.reduce_avg(table, [grad_sets[0][i % k]], s_copy, px.SUM)
     ev[0].record()
-    for i in range(10):
-        dst.copy_(src)
+    for i in range(args.steps):
+        px.reduce_avg(table, [grad_sets[i % len(grad_sets)][i % k]], s_copy, px.SUM)
     ev[1].record()
     torch.cuda.synchronize()
-    copy_gbps = 2 * src.numel() * 4 / (ev[0].elapsed_time(ev[1]) / 10) / 1e6
-    del src, dst
+    copy_ms = ev[0].elapsed_time(ev[1]) / args.steps
+    copy_gbps = 8 * n / copy_ms / 1e6
 
     # ---- the oracle on the host cores, same workload (a baseline, not a target)
     baseline = None
@@ -310,7 +317,9 @@ def main() -> int:
         "roofline": roofline,
         "stages": stages,
         "fused": fused,
-        "copy_reference": {"what": "torch copy_ of 1 GiB float32, read+write bytes", "GBps": round(copy_gbps, 1),
+        "copy_reference": {"what": "plain float32 copy of the same tensor set (pxchg_reduce_avg, k=1, sum), "
+                                   "read+write bytes", "kernel": "pxchg_reduce_avg_kernel<1,float,float>",
+                           "ms": round(copy_ms, 5), "bytes": 8 * n, "GBps": round(copy_gbps, 1),
                            "frac_of_hbm_peak": round(copy_gbps / HBM_PEAK_GBPS, 4)},
         "cpu_baseline": baseline,
         "setup_seconds": round(t_gen, 1),
