@@ -186,6 +186,33 @@ int pxchg_reduce_avg_sgd_momentum(const pxchg_table *table, int k, const pxchg_b
                                   int mode, int wire_dtype, pxchg_bufset *param, pxchg_bufset *vel,
                                   float lr, float mu, float wd, void *stream);
 
+/*
+ * Diagnostics of one buffer set, for watching the reduced-precision exchange
+ * whose accuracy cost Section 4 reports (an overflow in the pack shows up as an
+ * infinity in the packed copy): over all elements of all tensors of `set` (F32,
+ * or F16 widened exactly),
+ *     nonfinite = number of infinities and NaNs,
+ *     max_abs   = largest magnitude among the finite elements (0 if none),
+ *     sum_sq    = sum of squares of the finite elements, accumulated in binary64
+ *                 (its square root is the L2 norm).
+ * `out` is DEVICE memory, 8-byte aligned, written by this call (no need to clear
+ * it); it is valid once the stream has reached this point.  Two launches: one
+ * that clears `out`, one that reads every element once and combines per-lane
+ * partial results across each wavefront before a single atomic update per
+ * wavefront.  nonfinite and max_abs are exact; sum_sq is summed in no fixed
+ * order, so it is reproducible only to binary64 rounding (like any binary64 sum
+ * of n non-negative terms it is within n * 2^-53 relative of the exact sum, and
+ * in practice within 1e-12).
+ */
+typedef struct pxchg_stats {
+    uint64_t nonfinite;
+    double sum_sq;
+    float max_abs;
+    uint32_t reserved;
+} pxchg_stats;
+
+int pxchg_buffer_stats(const pxchg_table *table, const pxchg_bufset *set, pxchg_stats *out /*device*/, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -63,6 +63,9 @@ def lib() -> ctypes.CDLL:
         L.oracle_sgd_momentum.restype = ctypes.c_int
         L.oracle_easgd.argtypes = [vp, vp, f, i64]
         L.oracle_easgd.restype = ctypes.c_int
+        L.oracle_stats.argtypes = [vp, ctypes.c_int, i64, ctypes.POINTER(ctypes.c_uint64),
+                                   ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_double)]
+        L.oracle_stats.restype = ctypes.c_int
         _lib = L
     return _lib
 
@@ -147,6 +150,26 @@ def easgd(x: np.ndarray, c: np.ndarray, alpha: float) -> None:
     rc = lib().oracle_easgd(x.ctypes.data, c.ctypes.data, alpha, x.size)
     if rc:
         raise ValueError("oracle_easgd rejected its arguments")
+
+
+def stats(a: np.ndarray):
+    """(count of non-finite elements, largest finite magnitude, sum of squares of finite elements)."""
+    _chk(a, a.dtype)
+    bad, mx, ss = ctypes.c_uint64(0), ctypes.c_float(0), ctypes.c_double(0)
+    rc = lib().oracle_stats(a.ctypes.data, _dtype_of(a), a.size, ctypes.byref(bad), ctypes.byref(mx),
+                            ctypes.byref(ss))
+    if rc:
+        raise ValueError("oracle_stats rejected its arguments")
+    return int(bad.value), float(mx.value), float(ss.value)
+
+
+def stats_tensors(ts):
+    """The same over a tensor list: counts and squares add up in tensor order, the maximum is the maximum."""
+    bad, mx, ss = 0, 0.0, 0.0
+    for t in ts:
+        b, m, s2 = stats(t)
+        bad, mx, ss = bad + b, max(mx, m), ss + s2
+    return bad, mx, ss
 
 
 # -- tensor lists: a plain loop over tensors ---------------------------------------

@@ -197,3 +197,34 @@ int oracle_easgd(float *x, float *c, float alpha, int64_t n)
     }
     return 0;
 }
+
+/*
+ * Diagnostics of one exchanged buffer, for watching the reduced-precision
+ * transfer (Section 4 reports an accuracy cost of the half-precision exchange):
+ * how many elements are not finite (an overflow in the pack shows up as an
+ * infinity), the largest finite magnitude, and the sum of squares of the finite
+ * elements accumulated in binary64 in index order (its square root is the
+ * L2 norm).  Elements are binary32, or binary16 widened exactly.
+ */
+int oracle_stats(const void *a, int dtype, int64_t n, uint64_t *nonfinite, float *max_abs, double *sum_sq)
+{
+    if (!a || n < 0 || !nonfinite || !max_abs || !sum_sq) return 1;
+    if (dtype != ORACLE_F32 && dtype != ORACLE_F16) return 1;
+    uint64_t bad = 0;
+    float mx = 0.0f;
+    double ss = 0.0;
+    for (int64_t j = 0; j < n; ++j) {
+        float x = (dtype == ORACLE_F32) ? ((const float *)a)[j] : widen(((const uint16_t *)a)[j]);
+        if ((bits_of(x) & 0x7f800000u) == 0x7f800000u) {   /* infinity or NaN */
+            ++bad;
+            continue;
+        }
+        float ax = x < 0.0f ? -x : x;
+        if (ax > mx) mx = ax;
+        ss = ss + (double)x * (double)x;
+    }
+    *nonfinite = bad;
+    *max_abs = mx;
+    *sum_sq = ss;
+    return 0;
+}

@@ -42,7 +42,14 @@ SIGNATURES = {
     "pxchg_easgd": (_int, [_vp, _vp, _vp, _f, _vp]),
     "pxchg_easgd_round": (_int, [_vp, _int, _pp, _vp, _f, _vp]),
     "pxchg_reduce_avg_sgd_momentum": (_int, [_vp, _int, _pp, _int, _int, _vp, _vp, _f, _f, _f, _vp]),
+    "pxchg_buffer_stats": (_int, [_vp, _vp, _vp, _vp]),
 }
+
+
+class Stats(ctypes.Structure):
+    """Host mirror of pxchg_stats (24 bytes)."""
+    _fields_ = [("nonfinite", ctypes.c_uint64), ("sum_sq", ctypes.c_double), ("max_abs", ctypes.c_float),
+                ("reserved", ctypes.c_uint32)]
 
 
 class PxchgError(RuntimeError):
@@ -260,3 +267,19 @@ def reduce_avg_sgd_momentum(table: Table, contrib: Sequence[BufSet], param: BufS
     _check(load().pxchg_reduce_avg_sgd_momentum(table.handle, len(contrib), _handles(contrib), mode, wire_dtype,
                                                 param.handle, vel.handle, lr, mu, wd, _stream_ptr(stream)),
            "pxchg_reduce_avg_sgd_momentum")
+
+
+def buffer_stats(table: Table, bufset: BufSet, out, stream=None) -> None:
+    """`out`: a CUDA tensor of at least 24 bytes (e.g. 3 int64), or a raw device address.  Read it back with
+    read_stats() after synchronising."""
+    addr = out if isinstance(out, int) else out.data_ptr()
+    if not isinstance(out, int) and out.numel() * out.element_size() < ctypes.sizeof(Stats):
+        raise ValueError("the output needs 24 bytes")
+    _check(load().pxchg_buffer_stats(table.handle, bufset.handle, addr, _stream_ptr(stream)), "pxchg_buffer_stats")
+
+
+def read_stats(out) -> Tuple[int, float, float]:
+    """(nonfinite, max_abs, sum_sq) from the tensor buffer_stats() wrote; copies 24 bytes to the host."""
+    raw = out.view(-1).cpu().numpy().tobytes()[:ctypes.sizeof(Stats)]
+    st = Stats.from_buffer_copy(raw)
+    return int(st.nonfinite), float(st.max_abs), float(st.sum_sq)

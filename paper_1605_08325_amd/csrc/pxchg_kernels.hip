@@ -146,7 +146,10 @@ __device__ __forceinline__ void store1(_Float16 *p, float x) { *(PX_GLOBAL _Floa
 
 // Number of leading elements after which `a` is 16-byte aligned.
 __device__ __forceinline__ int head_of(uintptr_t a, int es) { return (int)(((16u - (unsigned)(a & 15u)) & 15u) / (unsigned)es); }
-__device__ __forceinline__ bool aligned_after(uintptr_t a, int es, int head) { return ((a + (uintptr_t)head * es) & 15u) == 0; }
+// Low four address bits of `a` after skipping `head` elements; zero means 16-byte aligned.  The kernels OR these
+// together for all operands AFTER all table pointers have been loaded, so that the scalar pointer loads of a chunk
+// are issued back to back instead of each waiting for the one before.
+__device__ __forceinline__ unsigned misalign_after(uintptr_t a, int es, int head) { return (unsigned)(a + (uintptr_t)head * es) & 15u; }
 
 // One vector step of a lane: every load is issued before the first use, then the
 // arithmetic, then the stores.
@@ -167,6 +170,11 @@ __device__ __forceinline__ void vector_step(const Op &op, int i0, int i1) {
 template <bool SPLIT, class Op>
 __device__ __forceinline__ void run_chunk(const Op &op, int len, int head) {
     const int tid = threadIdx.x;
+    if (BLOCK == 64 && len == 64 * UNIT && head == 0) {  // the common case: one full, aligned tile
+        const int lane_off = SPLIT ? tid * 4 : tid * UNIT;
+        vector_step<SPLIT>(op, lane_off, lane_off + (SPLIT ? 64 * 4 : 4));
+        return;
+    }
     if (head < 0 || head > len) {
         for (int i = tid; i < len; i += BLOCK) op.scalar(i);
         return;
@@ -268,7 +276,7 @@ __global__ __launch_bounds__(BLOCK) void pxchg_convert_kernel(const PxChunk *__r
         op.src = table_ptr<const TI>(args.src[w], ch.tensor) + ch.start;
         op.dst = table_ptr<TO>(args.dst[w], ch.tensor) + ch.start;
         int head = head_of((uintptr_t)op.dst, sizeof(TO));
-        if (!aligned_after((uintptr_t)op.src, sizeof(TI), head)) head = -1;
+        if (misalign_after((uintptr_t)op.src, sizeof(TI), head)) head = -1;
         run_chunk<use_split<TI, TO>()>(op, ch.len, head);
     }
 }
@@ -368,12 +376,13 @@ __global__ __launch_bounds__(BLOCK) void pxchg_reduce_avg_kernel(const PxChunk *
         op.use_div = args.use_div;
         op.kf = args.kf;
         op.scale = args.scale;
-        int head = head_of((uintptr_t)op.dst, sizeof(TO));
 #pragma unroll
-        for (int w = 0; w < K; ++w) {
-            op.src[w] = table_ptr<const TI>(args.contrib[w], ch.tensor) + ch.start;
-            if (!aligned_after((uintptr_t)op.src[w], sizeof(TI), head)) head = -1;
-        }
+        for (int w = 0; w < K; ++w) op.src[w] = table_ptr<const TI>(args.contrib[w], ch.tensor) + ch.start;
+        int head = head_of((uintptr_t)op.dst, sizeof(TO));
+        unsigned bad = 0;
+#pragma unroll
+        for (int w = 0; w < K; ++w) bad |= misalign_after((uintptr_t)op.src[w], sizeof(TI), head);
+        if (bad) head = -1;
         run_chunk<use_split<TI, TO>()>(op, ch.len, head);
     }
 }
@@ -398,7 +407,7 @@ __global__ __launch_bounds__(BLOCK) void pxchg_reduce_avg_anyk_kernel(const PxCh
         if ((int)threadIdx.x < args.k) {
             const TI *p = table_ptr<const TI>(args.contrib[threadIdx.x], ch.tensor) + ch.start;
             sp[threadIdx.x] = p;
-            if (!aligned_after((uintptr_t)p, sizeof(TI), head0)) s_head = -1;  // benign race: all write -1
+            if (misalign_after((uintptr_t)p, sizeof(TI), head0)) s_head = -1;  // benign race: all write -1
         }
         __syncthreads();
         op.src = sp;
@@ -459,7 +468,7 @@ __global__ __launch_bounds__(BLOCK) void pxchg_sgd_momentum_kernel(const PxChunk
         op.mu = args.mu;
         op.wd = args.wd;
         int head = head_of((uintptr_t)op.g, sizeof(TG));
-        if (!aligned_after((uintptr_t)op.w, 4, head) || !aligned_after((uintptr_t)op.v, 4, head)) head = -1;
+        if (misalign_after((uintptr_t)op.w, 4, head) | misalign_after((uintptr_t)op.v, 4, head)) head = -1;
         run_chunk<use_split<float>()>(op, ch.len, head);
     }
 }
@@ -537,14 +546,13 @@ __global__ __launch_bounds__(BLOCK) void pxchg_reduce_avg_sgd_momentum_kernel(co
         op.lr = args.lr;
         op.mu = args.mu;
         op.wd = args.wd;
-        op.src[0] = table_ptr<const TI>(args.contrib[0], ch.tensor) + ch.start;
-        int head = head_of((uintptr_t)op.src[0], sizeof(TI));
 #pragma unroll
-        for (int q = 1; q < K; ++q) {
-            op.src[q] = table_ptr<const TI>(args.contrib[q], ch.tensor) + ch.start;
-            if (!aligned_after((uintptr_t)op.src[q], sizeof(TI), head)) head = -1;
-        }
-        if (!aligned_after((uintptr_t)op.w, 4, head) || !aligned_after((uintptr_t)op.v, 4, head)) head = -1;
+        for (int q = 0; q < K; ++q) op.src[q] = table_ptr<const TI>(args.contrib[q], ch.tensor) + ch.start;
+        int head = head_of((uintptr_t)op.src[0], sizeof(TI));
+        unsigned bad = misalign_after((uintptr_t)op.w, 4, head) | misalign_after((uintptr_t)op.v, 4, head);
+#pragma unroll
+        for (int q = 1; q < K; ++q) bad |= misalign_after((uintptr_t)op.src[q], sizeof(TI), head);
+        if (bad) head = -1;
         run_chunk<use_split<float>()>(op, ch.len, head);
     }
 }
@@ -604,13 +612,84 @@ __global__ __launch_bounds__(BLOCK) void pxchg_easgd_kernel(const PxChunk *__res
         ElasticOp<K, NT> op;
         op.c = table_ptr<float>(args.c, ch.tensor) + ch.start;
         op.alpha = args.alpha;
-        int head = head_of((uintptr_t)op.c, 4);
 #pragma unroll
-        for (int q = 0; q < K; ++q) {
-            op.x[q] = table_ptr<float>(args.x[q], ch.tensor) + ch.start;
-            if (!aligned_after((uintptr_t)op.x[q], 4, head)) head = -1;
-        }
+        for (int q = 0; q < K; ++q) op.x[q] = table_ptr<float>(args.x[q], ch.tensor) + ch.start;
+        int head = head_of((uintptr_t)op.c, 4);
+        unsigned bad = 0;
+#pragma unroll
+        for (int q = 0; q < K; ++q) bad |= misalign_after((uintptr_t)op.x[q], 4, head);
+        if (bad) head = -1;
         run_chunk<use_split<float>()>(op, ch.len, head);
+    }
+}
+
+// ---------------------------------------------------------------- diagnostics
+
+struct StatsAcc {
+    unsigned long long bad;
+    float mx;
+    double ss;
+};
+
+__device__ __forceinline__ void stats_take(StatsAcc &a, float x) {
+    if ((__float_as_uint(x) & 0x7f800000u) == 0x7f800000u) {  // infinity or NaN
+        a.bad += 1;
+    } else {
+        a.mx = fmaxf(a.mx, fabsf(x));
+        a.ss = a.ss + (double)x * (double)x;
+    }
+}
+
+template <typename T, int NT>
+struct StatsOp {
+    const T *src;
+    StatsAcc *acc;  // this lane's running result
+    struct State {
+        F8 x;
+    };
+    __device__ __forceinline__ void scalar(int i) const { stats_take(*acc, load1(src + i)); }
+    template <bool SP>
+    __device__ __forceinline__ void load(State &st, int i0, int i1) const { st.x = load8<NT, SP>(src, i0, i1); }
+    __device__ __forceinline__ void compute(State &st) const {
+#pragma unroll
+        for (int e = 0; e < UNIT; ++e) stats_take(*acc, st.x.v[e]);
+    }
+    template <bool SP>
+    __device__ __forceinline__ void store(const State &, int, int) const {}
+};
+
+__global__ void pxchg_stats_clear_kernel(pxchg_stats *out) {
+    out->nonfinite = 0;
+    out->sum_sq = 0.0;
+    out->max_abs = 0.0f;
+    out->reserved = 0;
+}
+
+// A grid-stride walk over the chunks; every lane keeps its own count, maximum
+// and binary64 sum of squares, the 64 lanes of a wavefront are combined with
+// cross-lane exchanges, and lane 0 of each wavefront issues three atomics.
+template <typename T, int NT>
+__global__ __launch_bounds__(BLOCK) void pxchg_stats_kernel(const PxChunk *__restrict__ chunks, int n_chunks,
+                                                            const void *const *set, pxchg_stats *out) {
+    StatsAcc acc = {0ull, 0.0f, 0.0};
+    for (int c = blockIdx.x; c < n_chunks; c += gridDim.x) {
+        const PxChunk ch = chunks[c];
+        StatsOp<T, NT> op;
+        op.src = table_ptr<const T>(set, ch.tensor) + ch.start;
+        op.acc = &acc;
+        run_chunk<false>(op, ch.len, head_of((uintptr_t)op.src, sizeof(T)));
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        acc.bad += __shfl_xor(acc.bad, off);
+        acc.mx = fmaxf(acc.mx, __shfl_xor(acc.mx, off));
+        acc.ss += __shfl_xor(acc.ss, off);
+    }
+    if ((threadIdx.x & 63) == 0) {
+        if (acc.bad) atomicAdd((unsigned long long *)&out->nonfinite, acc.bad);
+        // magnitudes are non-negative, so their bit patterns order like the values
+        atomicMax((unsigned *)&out->max_abs, __float_as_uint(acc.mx));
+        atomicAdd(&out->sum_sq, acc.ss);
     }
 }
 
@@ -938,6 +1017,28 @@ int pxchg_easgd_round(const pxchg_table *table, int k, pxchg_bufset *const *x, p
         if ((rc = after_launch())) return rc;
     }
     return PXCHG_OK;
+}
+
+int pxchg_buffer_stats(const pxchg_table *table, const pxchg_bufset *set, pxchg_stats *out, void *stream) {
+    int rc = check_table(table);
+    if (rc) return rc;
+    if ((rc = check_set(table, set, -1))) return rc;
+    if (!out || ((uintptr_t)out & 7u)) return PXCHG_ERR_INVALID_ARG;
+    hipStream_t s = (hipStream_t)stream;
+    hipLaunchKernelGGL(pxchg_stats_clear_kernel, dim3(1), dim3(1), 0, s, out);
+    if ((rc = after_launch())) return rc;
+    if (table->n_chunks == 0) return PXCHG_OK;
+    // a few resident wavefronts per compute unit, each looping: few atomics, plenty of loads in flight
+    const int64_t cap = (int64_t)px_cu_count(table->device) * 32;
+    const dim3 grid((unsigned)std::min<int64_t>(table->n_chunks, cap));
+    const void *const *ptrs = (const void *const *)set->d_ptrs;
+    if (set->dtype == PXCHG_F32)
+        hipLaunchKernelGGL((pxchg_stats_kernel<float, 1>), grid, dim3(BLOCK), 0, s, table->d_chunks,
+                           (int)table->n_chunks, ptrs, out);
+    else
+        hipLaunchKernelGGL((pxchg_stats_kernel<_Float16, 1>), grid, dim3(BLOCK), 0, s, table->d_chunks,
+                           (int)table->n_chunks, ptrs, out);
+    return after_launch();
 }
 
 int pxchg_easgd(const pxchg_table *table, pxchg_bufset *x, pxchg_bufset *c, float alpha, void *stream) {

@@ -149,3 +149,48 @@ def test_config5_easgd_100_rounds_sampled(px, oracle_mod):
         assert_close_params(got, xs[i], f"worker {i}")
         assert_bits_equal(got, xs[i], f"worker {i}")
     assert_bits_equal(gather_device(d_c, idx), c, "center")
+
+
+# ------------------------------------------------------------------ the paper's other two model sizes (Table 2)
+
+def test_vggnet_shaped_k8_f16_one_step_sampled(px, oracle_mod):
+    """138,357,544 parameters in 32 tensors (Table 2's VGGNet count), same exchange as configuration 3."""
+    base = wl.config(3)
+    cfg = wl.Config("vggnet_sync_k8_f16", tuple(wl.vggnet_counts()), 8, "f16", seed=base.seed + 100)
+    sync_exchange(px, oracle_mod, cfg, steps=1, full=False)
+
+
+def test_googlenet_count_many_small_tensors_k8_f16(px, oracle_mod):
+    """13,378,280 parameters (Table 2's GoogLeNet count) spread over 128 ragged tensors."""
+    base = wl.config(4)
+    cfg = wl.Config("googlenet_sync_k8_f16", tuple(wl.googlenet_scale_counts(base.seed)), 8, "f16",
+                    seed=base.seed + 100)
+    sync_exchange(px, oracle_mod, cfg, steps=1, full=True)
+
+
+def test_weight_averaging_mode_on_alexnet_shapes(px, oracle_mod):
+    """Section 4's other scheme: every worker descends on its own (learning rate scaled by k), then weights
+    and momentum are averaged (binary32 transfer, k = 8).  Same kernels, no update after the average."""
+    import torch
+    cfg = wl.config(2)
+    counts, k = list(cfg.counts), 8
+    table = px.Table(counts)
+    idx = sample_indices(counts, 20_000, cfg.seed, px.get_option(px.OPT_CHUNK_ELEMS))
+    w0 = wl.gaussian_tensors(counts, cfg.param_sigma, cfg.seed, "param")
+    grads = wl.gaussian_workers(counts, cfg.grad_sigma, cfg.seed, "grad", k)
+    d_ws = [to_device(w0) for _ in range(k)]
+    d_vs = [to_device(wl.zeros_tensors(counts)) for _ in range(k)]
+    s_ws, s_vs = [table.bufset(w) for w in d_ws], [table.bufset(v) for v in d_vs]
+    for i in range(k):
+        px.sgd_momentum(table, table.bufset(to_device(grads[i])), s_ws[i], s_vs[i], k * cfg.lr, cfg.mu, cfg.wd)
+    px.reduce_avg(table, s_ws, s_ws[0])        # in place into worker 0's copy
+    px.reduce_avg(table, s_vs, s_vs[0])
+    torch.cuda.synchronize()
+    ws, vs = [], []
+    for i in range(k):
+        wi, vi = gather(w0, idx), gather(wl.zeros_tensors(counts), idx)
+        oracle_mod.sgd_momentum_tensors(gather(grads[i], idx), wi, vi, np.float32(k * cfg.lr), cfg.mu, cfg.wd)
+        ws.append(wi)
+        vs.append(vi)
+    assert_bits_equal(gather_device(d_ws[0], idx), oracle_mod.reduce_avg_tensors(ws), "averaged weights")
+    assert_bits_equal(gather_device(d_vs[0], idx), oracle_mod.reduce_avg_tensors(vs), "averaged momentum")

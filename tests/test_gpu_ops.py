@@ -409,3 +409,104 @@ def test_argument_errors(px):
     with pytest.raises(px.PxchgError) as e:
         px.BufSet(table, [a[0].data_ptr() + 2, a[1].data_ptr()], px.F32)
     assert e.value.status == 1
+
+
+# ------------------------------------------------------------------ diagnostics
+
+@pytest.mark.parametrize("dt", [np.float32, np.float16])
+@pytest.mark.parametrize("offset", [0, 1])
+def test_buffer_stats(px, oracle_mod, dt, offset):
+    import torch
+    table = px.Table(RAGGED)
+    a = [t.astype(dt) for t in _gauss(RAGGED, 970)]
+    a[7][[3, 500, 19_999]] = [np.inf, np.nan, -np.inf]
+    a[11][70_000] = -7.25
+    a[0][0] = np.nan
+    d_a = to_device(a, offset)
+    out = torch.full((4,), -1, dtype=torch.int64, device="cuda")     # garbage in: the call clears it
+    for _ in range(2):                                               # and a second call starts from zero again
+        px.buffer_stats(table, table.bufset(d_a), out)
+        torch.cuda.synchronize()
+        bad, mx, ss = px.read_stats(out)
+        wbad, wmx, wss = oracle_mod.stats_tensors(a)
+        assert bad == wbad == 4 and mx == wmx == 7.25
+        assert abs(ss - wss) <= 1e-11 * wss
+    assert int(out[3].item()) == -1                                  # nothing past the 24 bytes was touched
+
+
+def test_buffer_stats_sees_overflow_of_the_pack(px, oracle_mod):
+    import torch
+    counts = [5000, 8192 * 2 + 1]
+    table = px.Table(counts)
+    g = _gauss(counts, 971)
+    g[1][[10, 9000]] = [7.0e4, -1.0e5]                               # beyond the binary16 range
+    d_g = to_device(g)
+    d_h = empty_like_device(counts, np.float16)
+    s_g, s_h = table.bufset(d_g), table.bufset(d_h)
+    px.pack_fp16(table, [s_g], [s_h])
+    out = torch.zeros(3, dtype=torch.int64, device="cuda")
+    px.buffer_stats(table, s_g, out)
+    torch.cuda.synchronize()
+    assert px.read_stats(out)[0] == 0
+    px.buffer_stats(table, s_h, out)
+    torch.cuda.synchronize()
+    bad, mx, ss = px.read_stats(out)
+    assert (bad, mx) == oracle_mod.stats_tensors(oracle_mod.pack_fp16_tensors(g))[:2] and bad == 2
+
+
+def test_buffer_stats_full_size(px, oracle_mod):
+    """AlexNet-shaped averaged gradient: every element read once, grid-stride walk with partial last pass."""
+    import torch
+    counts = wl.alexnet_counts()
+    table = px.Table(counts)
+    a = [t.astype(np.float16) for t in wl.gaussian_tensors(counts, 0.01, 972, "grad")]
+    d_a = to_device(a)
+    out = torch.zeros(3, dtype=torch.int64, device="cuda")
+    px.buffer_stats(table, table.bufset(d_a), out)
+    torch.cuda.synchronize()
+    bad, mx, ss = px.read_stats(out)
+    wbad, wmx, wss = oracle_mod.stats_tensors(a)
+    # both are sums of n non-negative binary64 terms in some order: each is within (n-1) * 2^-53 of the exact
+    # sum (the oracle adds in index order, the GPU per lane, then across lanes, then across wavefronts)
+    n = sum(counts)
+    assert bad == wbad == 0 and mx == wmx and abs(ss - wss) <= 2 * n * 2.0 ** -53 * wss
+    # against numpy's pairwise binary64 sum, which is accurate to a few ulp
+    exact = float(sum(np.sum(t.astype(np.float64) ** 2) for t in a))
+    assert abs(ss - exact) <= 1e-12 * exact
+    with pytest.raises(px.PxchgError):
+        px.buffer_stats(table, table.bufset(d_a), out.data_ptr() + 4)   # misaligned output
+
+
+# ------------------------------------------------------------------ layer by layer, on two streams
+
+def test_per_layer_exchange_on_two_streams_equals_whole_set(px, oracle_mod):
+    """The exchange of one layer does not depend on the others, so layers can be exchanged as their
+    gradients become ready, on different streams (the overlap the paper names as future work).  One
+    table per layer, alternating streams; results equal the oracle on the whole set."""
+    import torch
+    counts = [34_848, 96, 307_200, 256, 100_003, 1000]
+    k = 4
+    grads = [_gauss(counts, 980, w) for w in range(k)]
+    w = _gauss(counts, 981, role="param")
+    v = wl.zeros_tensors(counts)
+    d_g = [to_device(g) for g in grads]
+    d_w, d_v = to_device(w), to_device(v)
+    d_avg = empty_like_device(counts, np.float32)
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    torch.cuda.synchronize()
+    keep = []
+    for layer in reversed(range(len(counts) // 2)):          # last layer's gradients are ready first
+        sl = slice(2 * layer, 2 * layer + 2)                  # weight and bias of this layer
+        table = px.Table(counts[sl])
+        sets = [table.bufset(d_g[i][sl]) for i in range(k)]
+        s_avg, s_w, s_v = table.bufset(d_avg[sl]), table.bufset(d_w[sl]), table.bufset(d_v[sl])
+        st = streams[layer % 2]
+        px.reduce_avg(table, sets, s_avg, px.AVG, stream=st)
+        px.sgd_momentum(table, s_avg, s_w, s_v, 0.01, 0.9, 5e-4, stream=st)
+        keep.append((table, sets, s_avg, s_w, s_v))
+    for st in streams:
+        st.synchronize()
+    avg = oracle_mod.reduce_avg_tensors(grads)
+    oracle_mod.sgd_momentum_tensors(avg, w, v, 0.01, 0.9, 5e-4)
+    assert_bits_equal(to_host(d_w), w, "w")
+    assert_bits_equal(to_host(d_v), v, "v")

@@ -168,3 +168,34 @@ def test_easgd_zero_rate_is_identity(oracle_mod):
     oracle_mod.easgd(x, c, 0.0)
     assert np.array_equal(x.view(np.uint32), x0.view(np.uint32))
     assert np.array_equal(c.view(np.uint32), c0.view(np.uint32))
+
+
+# ---------------------------------------------------------------- diagnostics
+
+def test_stats_against_numpy_and_exact_sum(oracle_mod):
+    import math
+    rng = np.random.default_rng(11)
+    a = (rng.standard_normal(200_001) * 0.01).astype(np.float32)
+    a[[5, 77, 1000]] = [np.inf, -np.inf, np.nan]
+    a[123] = -3.5
+    bad, mx, ss = oracle_mod.stats(a)
+    fin = a[np.isfinite(a)].astype(np.float64)
+    assert bad == 3 and mx == 3.5
+    exact = math.fsum((fin * fin).tolist())        # squares of binary32 values are exact in binary64
+    assert abs(ss - exact) <= 1e-12 * exact
+    h = a.astype(np.float16)
+    badh, mxh, ssh = oracle_mod.stats(h)
+    finh = h[np.isfinite(h)].astype(np.float64)
+    assert badh == 3 and mxh == 3.5
+    assert abs(ssh - math.fsum((finh * finh).tolist())) <= 1e-12 * ssh
+
+
+def test_stats_special_cases(oracle_mod):
+    assert oracle_mod.stats(np.zeros(0, np.float32)) == (0, 0.0, 0.0)
+    assert oracle_mod.stats(np.array([np.nan, np.inf], np.float32)) == (2, 0.0, 0.0)
+    assert oracle_mod.stats(np.array([-0.0, 1e-45], np.float32)) == (0, float(np.float32(1e-45)), float(np.float32(1e-45)) ** 2)
+    # an overflow in the pack shows up as one non-finite element
+    g = np.array([1.0, 70000.0, -2.0], np.float32)
+    assert oracle_mod.stats(oracle_mod.pack_fp16(g)) == (1, 2.0, 5.0)
+    parts = [np.array([3.0, 4.0], np.float32), np.array([np.inf, -12.0], np.float32)]
+    assert oracle_mod.stats_tensors(parts) == (1, 12.0, 169.0)
