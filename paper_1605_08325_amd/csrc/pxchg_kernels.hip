@@ -167,14 +167,10 @@ __device__ __forceinline__ void vector_step(const Op &op, int i0, int i1) {
 // The vector part is cut into 512-element tiles (one vector step of a whole
 // wavefront); with SPLIT, tiles use the split lane layout.  What is left after
 // the last full tile goes in the contiguous layout.
-template <bool SPLIT, class Op>
-__device__ __forceinline__ void run_chunk(const Op &op, int len, int head) {
-    const int tid = threadIdx.x;
-    if (BLOCK == 64 && len == 64 * UNIT && head == 0) {  // the common case: one full, aligned tile
-        const int lane_off = SPLIT ? tid * 4 : tid * UNIT;
-        vector_step<SPLIT>(op, lane_off, lane_off + (SPLIT ? 64 * 4 : 4));
-        return;
-    }
+// NTH lanes (whole wavefronts) work on the chunk together; `tid` is the lane's index among them.
+template <bool SPLIT, class Op, int NTH = BLOCK>
+__device__ __forceinline__ void run_chunk(const Op &op, int len, int head, int tid = threadIdx.x) {
+    constexpr int BLOCK = NTH;  // shadows the workgroup size: the strides below are those of the cooperating lanes
     if (head < 0 || head > len) {
         for (int i = tid; i < len; i += BLOCK) op.scalar(i);
         return;
@@ -665,19 +661,27 @@ __global__ void pxchg_stats_clear_kernel(pxchg_stats *out) {
     out->reserved = 0;
 }
 
-// A grid-stride walk over the chunks; every lane keeps its own count, maximum
-// and binary64 sum of squares, the 64 lanes of a wavefront are combined with
-// cross-lane exchanges, and lane 0 of each wavefront issues three atomics.
+// Every wavefront walks its own chunks (wavefront-stride over the chunk list); every lane keeps its own
+// count, maximum and binary64 sum of squares.  The 64 lanes of a wavefront are combined with cross-lane
+// exchanges, the wavefronts of a workgroup through LDS, and one lane per workgroup issues the three atomics
+// (atomics on one address serialise, so there must be few of them).
+constexpr int STATS_BLOCK = 1024;
 template <typename T, int NT>
-__global__ __launch_bounds__(BLOCK) void pxchg_stats_kernel(const PxChunk *__restrict__ chunks, int n_chunks,
-                                                            const void *const *set, pxchg_stats *out) {
+__global__ __launch_bounds__(STATS_BLOCK) void pxchg_stats_kernel(const PxChunk *__restrict__ chunks, int n_chunks,
+                                                                  const void *const *set, pxchg_stats *out) {
+    constexpr int WAVES = STATS_BLOCK / 64;
+    __shared__ unsigned long long s_bad[WAVES];
+    __shared__ float s_mx[WAVES];
+    __shared__ double s_ss[WAVES];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // the same in all 64 lanes: keep it scalar
     StatsAcc acc = {0ull, 0.0f, 0.0};
-    for (int c = blockIdx.x; c < n_chunks; c += gridDim.x) {
+    for (int c = blockIdx.x * WAVES + wave; c < n_chunks; c += gridDim.x * WAVES) {
         const PxChunk ch = chunks[c];
         StatsOp<T, NT> op;
         op.src = table_ptr<const T>(set, ch.tensor) + ch.start;
         op.acc = &acc;
-        run_chunk<false>(op, ch.len, head_of((uintptr_t)op.src, sizeof(T)));
+        run_chunk<false, StatsOp<T, NT>, 64>(op, ch.len, head_of((uintptr_t)op.src, sizeof(T)), lane);
     }
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) {
@@ -685,7 +689,18 @@ __global__ __launch_bounds__(BLOCK) void pxchg_stats_kernel(const PxChunk *__res
         acc.mx = fmaxf(acc.mx, __shfl_xor(acc.mx, off));
         acc.ss += __shfl_xor(acc.ss, off);
     }
-    if ((threadIdx.x & 63) == 0) {
+    if (lane == 0) {
+        s_bad[wave] = acc.bad;
+        s_mx[wave] = acc.mx;
+        s_ss[wave] = acc.ss;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int w = 1; w < WAVES; ++w) {
+            acc.bad += s_bad[w];
+            acc.mx = fmaxf(acc.mx, s_mx[w]);
+            acc.ss += s_ss[w];
+        }
         if (acc.bad) atomicAdd((unsigned long long *)&out->nonfinite, acc.bad);
         // magnitudes are non-negative, so their bit patterns order like the values
         atomicMax((unsigned *)&out->max_abs, __float_as_uint(acc.mx));
@@ -1028,15 +1043,17 @@ int pxchg_buffer_stats(const pxchg_table *table, const pxchg_bufset *set, pxchg_
     hipLaunchKernelGGL(pxchg_stats_clear_kernel, dim3(1), dim3(1), 0, s, out);
     if ((rc = after_launch())) return rc;
     if (table->n_chunks == 0) return PXCHG_OK;
-    // a few resident wavefronts per compute unit, each looping: few atomics, plenty of loads in flight
-    const int64_t cap = (int64_t)px_cu_count(table->device) * 32;
-    const dim3 grid((unsigned)std::min<int64_t>(table->n_chunks, cap));
+    // two 16-wavefront workgroups per compute unit, each wavefront looping over chunks: the card is full,
+    // and only three atomics per workgroup reach `out`
+    constexpr int waves = STATS_BLOCK / 64;
+    const int64_t need = (table->n_chunks + waves - 1) / waves;
+    const dim3 grid((unsigned)std::min<int64_t>(need, (int64_t)px_cu_count(table->device) * 2));
     const void *const *ptrs = (const void *const *)set->d_ptrs;
     if (set->dtype == PXCHG_F32)
-        hipLaunchKernelGGL((pxchg_stats_kernel<float, 1>), grid, dim3(BLOCK), 0, s, table->d_chunks,
+        hipLaunchKernelGGL((pxchg_stats_kernel<float, 1>), grid, dim3(STATS_BLOCK), 0, s, table->d_chunks,
                            (int)table->n_chunks, ptrs, out);
     else
-        hipLaunchKernelGGL((pxchg_stats_kernel<_Float16, 1>), grid, dim3(BLOCK), 0, s, table->d_chunks,
+        hipLaunchKernelGGL((pxchg_stats_kernel<_Float16, 1>), grid, dim3(STATS_BLOCK), 0, s, table->d_chunks,
                            (int)table->n_chunks, ptrs, out);
     return after_launch();
 }
