@@ -65,7 +65,8 @@ enum pxchg_option {
     PXCHG_OPT_CHECK_RANGES = 2,  /* 1 (default): pxchg_bufset_create verifies that each tensor lies
                                     inside one device allocation */
     PXCHG_OPT_NONTEMPORAL = 3    /* -1 (default): each kernel's own measured-best policy; 0..3: bit 0
-                                    puts the non-temporal hint on vector loads, bit 1 on vector stores */
+                                    puts the non-temporal hint on vector loads, bit 1 on vector stores;
+                                    4: non-temporal loads, and stores that are streaming with agent scope */
 };
 
 typedef struct pxchg_table pxchg_table;

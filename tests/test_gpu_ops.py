@@ -354,10 +354,13 @@ def test_results_do_not_depend_on_launch_shape(px, oracle_mod, chunk, bpc):
         px.set_option(px.OPT_BLOCKS_PER_CU, old[1])
 
 
-def test_nontemporal_off_gives_same_bits(px, oracle_mod):
+@pytest.mark.parametrize("policy", [0, 1, 2, 3, 4])
+def test_every_cache_policy_gives_the_same_bits(px, oracle_mod, policy):
+    """The cache hints on loads and stores (none, non-temporal loads, non-temporal stores, both, and
+    non-temporal loads with agent-scope streaming stores) never change a result."""
     old = px.get_option(px.OPT_NONTEMPORAL)
     try:
-        px.set_option(px.OPT_NONTEMPORAL, 0)
+        px.set_option(px.OPT_NONTEMPORAL, policy)
         table = px.Table(RAGGED)
         x = _gauss(RAGGED, 960, role="worker")
         c = _gauss(RAGGED, 961, role="center")
@@ -366,6 +369,29 @@ def test_nontemporal_off_gives_same_bits(px, oracle_mod):
         oracle_mod.easgd_tensors(x, c, 0.0625)
         assert_bits_equal(to_host(d_x), x, "x")
         assert_bits_equal(to_host(d_c), c, "c")
+        k = 3
+        g = [_gauss(RAGGED, 962, w) for w in range(k)]
+        s_g = [table.bufset(to_device(t)) for t in g]
+        d_h = [empty_like_device(RAGGED, np.float16) for _ in range(k)]
+        s_h = [table.bufset(t) for t in d_h]
+        px.pack_fp16(table, s_g, s_h)
+        packed = [oracle_mod.pack_fp16_tensors(t) for t in g]
+        for w in range(k):
+            assert_bits_equal(to_host(d_h[w]), packed[w], "pack")
+        d_avg = empty_like_device(RAGGED, np.float16)
+        s_avg = table.bufset(d_avg)
+        px.reduce_avg(table, s_h, s_avg)
+        avg = oracle_mod.reduce_avg_tensors(packed, np.float16)
+        assert_bits_equal(to_host(d_avg), avg, "reduce")
+        d_back = empty_like_device(RAGGED, np.float32)
+        px.unpack_fp16(table, [s_avg], [table.bufset(d_back)])
+        assert_bits_equal(to_host(d_back), oracle_mod.unpack_fp16_tensors(avg), "unpack")
+        w_, v_ = _gauss(RAGGED, 963, role="param"), _gauss(RAGGED, 964, role="velocity")
+        d_w, d_v = to_device(w_), to_device(v_)
+        px.sgd_momentum(table, s_avg, table.bufset(d_w), table.bufset(d_v), 0.01, 0.9, 5e-4)
+        oracle_mod.sgd_momentum_tensors(avg, w_, v_, 0.01, 0.9, 5e-4)
+        assert_bits_equal(to_host(d_w), w_, "w")
+        assert_bits_equal(to_host(d_v), v_, "v")
     finally:
         px.set_option(px.OPT_NONTEMPORAL, old)
 
