@@ -328,9 +328,9 @@ def main() -> int:
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "f32 sums and updates, f16 transfer",
+        "dtype": "f32",
         "data": "synthetic",
-        "config": {"workload": workload_name, "n_params": n, "n_tensors": len(counts), "k": k,
+        "config": {"workload": workload_name, "transfer_dtype": "f16", "n_params": n, "n_tensors": len(counts), "k": k,
                    "step": "pack x8 -> reduce_avg f16->f16 -> sgd_momentum (f16 grad) -> 8 easgd meetings",
                    "gradient_sets": len(grad_sets), "chunk_elems": px.get_option(px.OPT_CHUNK_ELEMS),
                    "blocks_per_cu": px.get_option(px.OPT_BLOCKS_PER_CU),
