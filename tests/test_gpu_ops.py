@@ -536,3 +536,127 @@ def test_per_layer_exchange_on_two_streams_equals_whole_set(px, oracle_mod):
     oracle_mod.sgd_momentum_tensors(avg, w, v, 0.01, 0.9, 5e-4)
     assert_bits_equal(to_host(d_w), w, "w")
     assert_bits_equal(to_host(d_v), v, "v")
+
+
+# ------------------------------------------------------------------ degenerate and maximum sizes
+
+def test_table_of_empty_tensors_is_a_no_op(px):
+    import torch
+    table = px.Table([0, 0, 0])
+    assert table.total == 0 and table.n_chunks == 0
+    s32 = px.BufSet(table, [0, 0, 0], px.F32)
+    s32b = px.BufSet(table, [0, 0, 0], px.F32)
+    s32c = px.BufSet(table, [0, 0, 0], px.F32)
+    s16 = px.BufSet(table, [0, 0, 0], px.F16)
+    px.pack_fp16(table, [s32], [s16])
+    px.unpack_fp16(table, [s16], [s32])
+    px.reduce_avg(table, [s32, s32b], s32c)
+    px.sgd_momentum(table, s16, s32, s32b, 0.1, 0.9, 0.0)
+    px.easgd(table, s32, s32b, 0.5)
+    px.easgd_round(table, [s32, s32b], s32c, 0.5)
+    px.reduce_avg_sgd_momentum(table, [s16], s32, s32b, 0.1, 0.9)
+    out = torch.full((3,), 5, dtype=torch.int64, device="cuda")
+    px.buffer_stats(table, s16, out)
+    torch.cuda.synchronize()
+    assert px.read_stats(out) == (0, 0.0, 0.0)
+
+
+def test_one_tensor_longer_than_2_to_the_31_elements(px, oracle_mod):
+    """64-bit element offsets: a single binary16 tensor of 2^31 + 1,029 elements is widened on the GPU and
+    compared with the oracle on windows at the start, around the 2^31 boundary, at the end and in between."""
+    import torch
+    n = (1 << 31) + 1029
+    rng = np.random.default_rng(99)
+    block = rng.integers(0, 1 << 16, 1 << 22, dtype=np.uint16)          # all kinds of halves, NaN included
+    table = px.Table([n])
+    d_h = torch.empty(n, dtype=torch.float16, device="cuda")
+    d_blk = torch.from_numpy(block.view(np.float16)).cuda()
+    reps = n // block.size
+    d_h[:reps * block.size].view(reps, block.size).copy_(d_blk.expand(reps, block.size))
+    d_h[reps * block.size:].copy_(d_blk[:n - reps * block.size])
+    d_f = torch.empty(n, dtype=torch.float32, device="cuda")
+    px.unpack_fp16(table, [table.bufset([d_h])], [table.bufset([d_f])])
+    out = torch.zeros(3, dtype=torch.int64, device="cuda")
+    px.buffer_stats(table, table.bufset([d_h]), out)
+    torch.cuda.synchronize()
+    windows = [0, 12_345_678, (1 << 31) - 2048, (1 << 31) - 5, n - 4099, n - 1029]
+    for s in windows:
+        e = min(n, s + 4099)
+        idx = np.arange(s, e) % block.size
+        want = oracle_mod.unpack_fp16(np.ascontiguousarray(block[idx]).view(np.float16))
+        got = d_f[s:e].cpu().numpy()
+        assert_bits_equal([got], [want], f"window at {s}", nan_as_class=True)
+    # the count of non-finite halves over all n elements follows from the block
+    exp = (block >> 10) & 0x1F
+    per_block = int(np.count_nonzero(exp == 0x1F))
+    tail = int(np.count_nonzero(exp[:n - reps * block.size] == 0x1F))
+    assert px.read_stats(out)[0] == reps * per_block + tail
+    del d_f, d_h
+    torch.cuda.empty_cache()
+
+
+# ------------------------------------------------------------------ a whole step captured in a HIP graph
+
+def test_exchange_step_replayed_from_a_hip_graph(px, oracle_mod):
+    """The calls allocate nothing, copy nothing from the host and record no memset, so a step can be captured
+    once and replayed.  Three replays with fresh gradients written between them (eager work and
+    synchronisations in between), each checked against the oracle."""
+    import torch
+    counts = [34_848, 96, 20_001, 3, 8192 * 2 + 5, 1000]
+    k = 4
+    table = px.Table(counts)
+    w = _gauss(counts, 990, role="param")
+    v = wl.zeros_tensors(counts)
+    xs = [_gauss(counts, 991, i, role="worker") for i in range(k)]
+    c = _gauss(counts, 992, role="center")
+    d_g = [to_device(_gauss(counts, 993, i)) for i in range(k)]
+    d_h = [empty_like_device(counts, np.float16) for _ in range(k)]
+    d_avg = empty_like_device(counts, np.float16)
+    d_w, d_v = to_device(w), to_device(v)
+    d_xs, d_c = [to_device(x) for x in xs], to_device(c)
+    d_stats = torch.zeros(3, dtype=torch.int64, device="cuda")
+    s_g, s_h = [table.bufset(t) for t in d_g], [table.bufset(t) for t in d_h]
+    s_avg, s_w, s_v = table.bufset(d_avg), table.bufset(d_w), table.bufset(d_v)
+    s_xs, s_c = [table.bufset(t) for t in d_xs], table.bufset(d_c)
+
+    def step():
+        px.pack_fp16(table, s_g, s_h)
+        px.reduce_avg(table, s_h, s_avg)
+        px.buffer_stats(table, s_avg, d_stats)
+        px.sgd_momentum(table, s_avg, s_w, s_v, 0.01, 0.9, 5e-4)
+        for i in range(k):
+            px.easgd(table, s_xs[i], s_c, 0.125)
+
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        snapshot = [t.clone() for t in d_w + d_v + d_c] + [t.clone() for x in d_xs for t in x]
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    # capture does not execute: state is unchanged
+    for a, b in zip(d_w + d_v + d_c + [t for x in d_xs for t in x], snapshot):
+        assert torch.equal(a, b)
+    for r in range(3):
+        grads = [_gauss(counts, 994 + r, i) for i in range(k)]
+        for i in range(k):
+            for dst, src in zip(d_g[i], grads[i]):
+                dst.copy_(torch.from_numpy(src))                 # eager work between replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        packed = [oracle_mod.pack_fp16_tensors(g) for g in grads]
+        avg = oracle_mod.reduce_avg_tensors(packed, np.float16)
+        oracle_mod.sgd_momentum_tensors(avg, w, v, 0.01, 0.9, 5e-4)
+        for i in range(k):
+            oracle_mod.easgd_tensors(xs[i], c, 0.125)
+        assert_bits_equal(to_host(d_avg), avg, f"replay {r} average")
+        assert_bits_equal(to_host(d_w), w, f"replay {r} w")
+        assert_bits_equal(to_host(d_v), v, f"replay {r} v")
+        assert_bits_equal(to_host(d_c), c, f"replay {r} center")
+        assert_bits_equal(to_host(d_xs[k - 1]), xs[k - 1], f"replay {r} worker")
+        bad, mx, ss = px.read_stats(d_stats)
+        wbad, wmx, wss = oracle_mod.stats_tensors(avg)
+        assert bad == wbad and mx == wmx and abs(ss - wss) <= 1e-12 * wss
