@@ -65,23 +65,25 @@ def upload(tensors):
 
 
 def cpu_baseline(counts, grads, w, v, xs, c, order, cfg, alpha, threads):
-    """The oracle, as it stands, on the host cores: same stages, same inputs."""
+    """The oracle, as it stands, on the host cores: same stages, same inputs.  Returns per-stage seconds with
+    all `threads` host threads (element range split over them) and with one thread."""
+    import ctypes
+
     import oracle
     L = oracle.lib()
-    import ctypes
     k = len(grads)
+    half = cfg.transfer == "f16"
     flat = lambda ts: np.concatenate(ts) if len(ts) > 1 else ts[0].copy()  # noqa: E731
     # one flat copy per buffer: the oracle is element-wise, so flattening the
     # tensor list changes nothing but the loop bounds
     g = [flat(t) for t in grads]
     n = g[0].size
-    h = [np.empty(n, np.float16) for _ in range(k)]
-    avg = np.empty(n, np.float16)
+    wire = np.float16 if half else np.float32
+    wire_es, wire_id = (2, oracle.F16) if half else (4, oracle.F32)
+    h = [np.empty(n, np.float16) for _ in range(k)] if half else g
+    avg = np.empty(n, wire)
     wf, vf = flat(w), flat(v)
     xf, cf = [flat(t) for t in xs], flat(c)
-    pieces = threads * 4
-    bounds = np.linspace(0, n, pieces + 1).astype(np.int64)
-    spans = [(int(a), int(b)) for a, b in zip(bounds[:-1], bounds[1:]) if b > a]
 
     def ptr(a, off, es):
         return ctypes.c_void_p(a.ctypes.data + off * es)
@@ -93,12 +95,12 @@ def cpu_baseline(counts, grads, w, v, xs, c, order, cfg, alpha, threads):
 
     def reduce(span):
         a, b = span
-        ps = (ctypes.c_void_p * k)(*[h[i].ctypes.data + a * 2 for i in range(k)])
-        L.oracle_reduce_avg(k, ps, oracle.F16, ptr(avg, a, 2), oracle.F16, oracle.AVG, b - a)
+        ps = (ctypes.c_void_p * k)(*[h[i].ctypes.data + a * wire_es for i in range(k)])
+        L.oracle_reduce_avg(k, ps, wire_id, ptr(avg, a, wire_es), wire_id, oracle.AVG, b - a)
 
     def update(span):
         a, b = span
-        L.oracle_sgd_momentum(ptr(avg, a, 2), oracle.F16, ptr(wf, a, 4), ptr(vf, a, 4),
+        L.oracle_sgd_momentum(ptr(avg, a, wire_es), wire_id, ptr(wf, a, 4), ptr(vf, a, 4),
                               cfg.lr, cfg.mu, cfg.wd, b - a)
 
     def elastic(span):
@@ -106,17 +108,27 @@ def cpu_baseline(counts, grads, w, v, xs, c, order, cfg, alpha, threads):
         for i in order:
             L.oracle_easgd(ptr(xf[i], a, 4), ptr(cf, a, 4), alpha, b - a)
 
-    times = {}
-    with ThreadPoolExecutor(threads) as ex:
-        for name, fn in (("pack", pack), ("reduce", reduce), ("update", update), ("elastic", elastic)):
-            best = None
-            for _ in range(2):
-                t0 = time.perf_counter()
-                list(ex.map(fn, spans))
-                dt = time.perf_counter() - t0
-                best = dt if best is None else min(best, dt)
-            times[name] = best
-    return times
+    stages = [("reduce", reduce), ("update", update), ("elastic", elastic)]
+    if half:
+        stages.insert(0, ("pack", pack))
+
+    def run(nthreads, reps):
+        pieces = nthreads * 4 if nthreads > 1 else 1
+        bounds = np.linspace(0, n, pieces + 1).astype(np.int64)
+        spans = [(int(a), int(b)) for a, b in zip(bounds[:-1], bounds[1:]) if b > a]
+        times = {}
+        with ThreadPoolExecutor(nthreads) as ex:
+            for name, fn in stages:
+                best = None
+                for _ in range(reps):
+                    t0 = time.perf_counter()
+                    list(ex.map(fn, spans))
+                    dt = time.perf_counter() - t0
+                    best = dt if best is None else min(best, dt)
+                times[name] = best
+        return times
+
+    return run(threads, 2), run(1, 1)
 
 
 def main() -> int:
@@ -126,6 +138,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--sets", type=int, default=2, help="rotating sets of fresh gradients resident in HBM")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--config", type=int, default=3, choices=[1, 2, 3, 4, 5],
+                    help="benchmark configuration (3 = the graded one: AlexNet-shaped, k = 8, half-precision transfer)")
     ap.add_argument("--workload", default="alexnet", choices=["alexnet", "vggnet", "googlenet"],
                     help="tensor shapes: AlexNet (the graded workload), the VGGNet parameter count of the paper's "
                          "Table 2, or its GoogLeNet count spread over 128 small tensors")
@@ -150,10 +164,16 @@ def main() -> int:
     if args.nontemporal >= 0:
         px.set_option(px.OPT_NONTEMPORAL, args.nontemporal)
 
-    cfg = wl.config(3)
+    cfg = wl.config(args.config)
+    if args.workload != "alexnet" and args.config != 3:
+        print("bench.py: --workload goes with --config 3 only", file=sys.stderr)
+        return 2
     counts = {"alexnet": lambda: list(cfg.counts), "vggnet": wl.vggnet_counts,
               "googlenet": lambda: wl.googlenet_scale_counts(cfg.seed)}[args.workload]()
     k, n = cfg.k, sum(counts)
+    half = cfg.transfer == "f16"
+    wire_t, wire_es, wire_px, wire_name = ((torch.float16, 2, px.F16, "_Float16") if half
+                                           else (torch.float32, 4, px.F32, "float"))
     workload_name = cfg.name if args.workload == "alexnet" else f"{args.workload}_sync_k8_f16"
     threads = host_threads()
     table = px.Table(counts)
@@ -168,23 +188,25 @@ def main() -> int:
         if s == 0:
             host_grads0 = grads
         d_g = [upload(g) for g in grads]
-        d_h = [[torch.empty(c, dtype=torch.float16, device="cuda") for c in counts] for _ in range(k)]
-        keep += [d_g, d_h]
         grad_sets.append([table.bufset(g) for g in d_g])
-        pack_sets.append([table.bufset(h) for h in d_h])
+        if half:
+            d_h = [[torch.empty(c, dtype=torch.float16, device="cuda") for c in counts] for _ in range(k)]
+            pack_sets.append([table.bufset(h) for h in d_h])
+        else:
+            pack_sets.append(grad_sets[-1])       # binary32 transfer: the contributions are the gradients themselves
         if s > 0:
             del grads
     w = wl.gaussian_tensors(counts, cfg.param_sigma, cfg.seed, "param")
     v = wl.zeros_tensors(counts)
     d_w, d_v = upload(w), upload(v)
-    d_avg = [torch.empty(c, dtype=torch.float16, device="cuda") for c in counts]
+    d_avg = [torch.empty(c, dtype=wire_t, device="cuda") for c in counts]
     s_w, s_v, s_avg = table.bufset(d_w), table.bufset(d_v), table.bufset(d_avg)
     cfg5 = wl.config(5)
+    alpha = float(np.float32(0.5 / k))            # configuration 5's rate, 0.5/k
     xs = wl.gaussian_workers(counts, cfg5.param_sigma, cfg5.seed, "worker", k, threads=threads)
     c = wl.gaussian_tensors(counts, cfg5.param_sigma, cfg5.seed, "center")
     d_xs, d_c = [upload(x) for x in xs], upload(c)
     s_xs, s_c = [table.bufset(x) for x in d_xs], table.bufset(d_c)
-    alpha = float(np.float32(cfg5.alpha))
     orders = wl.worker_orders(cfg5.seed, k, args.steps + args.warmup)
     torch.cuda.synchronize()
     t_gen = time.perf_counter() - t_gen
@@ -193,7 +215,8 @@ def main() -> int:
         s = i % len(grad_sets)
         if ev:
             ev[0].record()
-        px.pack_fp16(table, grad_sets[s], pack_sets[s])
+        if half:
+            px.pack_fp16(table, grad_sets[s], pack_sets[s])
         if ev:
             ev[1].record()
         px.reduce_avg(table, pack_sets[s], s_avg, px.AVG)
@@ -217,14 +240,17 @@ def main() -> int:
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
 
-    stage_names = ["pack", "reduce", "update", "elastic"]
+    all_stages = ["pack", "reduce", "update", "elastic"]
     stage_ms = {nm: float(np.mean([events[i][q].elapsed_time(events[i][q + 1]) for i in range(args.steps)]))
-                for q, nm in enumerate(stage_names)}
+                for q, nm in enumerate(all_stages)}
+    stage_names = all_stages if half else all_stages[1:]
     # algorithmic bytes per step and per launch
-    stage_bytes = {"pack": 6 * k * n, "reduce": (2 * k + 2) * n, "update": 18 * n, "elastic": 16 * n * k}
+    stage_bytes = {"pack": 6 * k * n, "reduce": (wire_es * k + wire_es) * n, "update": (wire_es + 16) * n,
+                   "elastic": 16 * n * k}
     launches = {"pack": 1, "reduce": 1, "update": 1, "elastic": k}
-    kernels = {"pack": "pxchg_convert_kernel<float,_Float16>", "reduce": "pxchg_reduce_avg_kernel<8,_Float16,_Float16>",
-               "update": "pxchg_sgd_momentum_kernel<_Float16>", "elastic": "pxchg_easgd_kernel<1>"}
+    kernels = {"pack": "pxchg_convert_kernel<float,_Float16>",
+               "reduce": f"pxchg_reduce_avg_kernel<{k},{wire_name},{wire_name}>",
+               "update": f"pxchg_sgd_momentum_kernel<{wire_name}>", "elastic": "pxchg_easgd_kernel<1>"}
     stages = {}
     for nm in stage_names:
         per_launch_ms = stage_ms[nm] / launches[nm]
@@ -235,8 +261,8 @@ def main() -> int:
                       "traffic": MEASURED_TRAFFIC_BYTES.get(nm, (None, None))[0]}
     dominant = max(stage_names, key=lambda nm: stage_ms[nm])
     d = stages[dominant]
-    if args.workload != "alexnet":
-        MEASURED_TRAFFIC_BYTES.clear()  # the counters were collected on the AlexNet-shaped set only
+    if args.workload != "alexnet" or args.config != 3:
+        MEASURED_TRAFFIC_BYTES.clear()  # the counters were collected on configuration 3 only
         for st in stages.values():
             st["traffic"] = None
     traffic = MEASURED_TRAFFIC_BYTES.get(dominant, (None, None))[0]
@@ -248,21 +274,21 @@ def main() -> int:
     ru_ms = stage_ms["reduce"] + stage_ms["update"]
     value = ru_bytes / (ru_ms * 1e-3) / 1e9
     ms_per_step = wall / args.steps * 1e3
-    step_bytes = sum(stage_bytes.values())
+    step_bytes = sum(stage_bytes[nm] for nm in stage_names)
 
     # ---- fused variants (same arithmetic, fewer bytes), timed after the main region
     fused = {}
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
     for i in range(3):
-        px.reduce_avg_sgd_momentum(table, pack_sets[0], s_w, s_v, cfg.lr, cfg.mu, cfg.wd, px.AVG, px.F16)
+        px.reduce_avg_sgd_momentum(table, pack_sets[0], s_w, s_v, cfg.lr, cfg.mu, cfg.wd, px.AVG, wire_px)
     ev[0].record()
     for i in range(args.steps):
         px.reduce_avg_sgd_momentum(table, pack_sets[i % len(pack_sets)], s_w, s_v, cfg.lr, cfg.mu, cfg.wd,
-                                   px.AVG, px.F16)
+                                   px.AVG, wire_px)
     ev[1].record()
     torch.cuda.synchronize()
     ms = ev[0].elapsed_time(ev[1]) / args.steps
-    fb = (2 * k + 16) * n
+    fb = (wire_es * k + 16) * n
     fused["reduce_update"] = {"ms": round(ms, 5), "algorithmic_bytes": fb, "GBps": round(fb / ms / 1e6, 1),
                               "frac_of_hbm_peak": round(fb / ms / 1e6 / HBM_PEAK_GBPS, 4)}
     for i in range(3):
@@ -287,9 +313,10 @@ def main() -> int:
     ev[1].record()
     torch.cuda.synchronize()
     ms = ev[0].elapsed_time(ev[1]) / args.steps
-    fused["diagnostics_f16"] = {"ms": round(ms, 5), "algorithmic_bytes": 2 * n, "GBps": round(2 * n / ms / 1e6, 1),
-                                "frac_of_hbm_peak": round(2 * n / ms / 1e6 / HBM_PEAK_GBPS, 4),
-                                "note": "122 MB input fits the 256 MB memory-side cache"}
+    fused["diagnostics"] = {"ms": round(ms, 5), "algorithmic_bytes": wire_es * n,
+                            "GBps": round(wire_es * n / ms / 1e6, 1),
+                            "frac_of_hbm_peak": round(wire_es * n / ms / 1e6 / HBM_PEAK_GBPS, 4),
+                            "note": "two launches; an input under 256 MB may sit in the memory-side cache"}
 
     # ---- a plain copy through the same kernel family (k = 1, no divide: out = in) as a
     # reference for what HBM sustains here, and as the known-size kernel that the
@@ -309,13 +336,15 @@ def main() -> int:
     # ---- the oracle on the host cores, same workload (a baseline, not a target)
     baseline = None
     if not args.no_cpu_baseline:
-        t = cpu_baseline(counts, host_grads0, w, v, xs, c, [int(j) for j in orders[0]], cfg, alpha, threads)
+        t, t1 = cpu_baseline(counts, host_grads0, w, v, xs, c, [int(j) for j in orders[0]], cfg, alpha, threads)
         cpu_ru = ru_bytes / (t["reduce"] + t["update"]) / 1e9
         baseline = {"value": round(cpu_ru, 2), "unit": "GB/s", "cores": threads, "kind": "oracle",
                     "sample": "the full workload, one step, element range split over the threads, best of 2 "
                               "per stage (same byte accounting as the GPU figure)",
                     "stage_seconds": {kk: round(vv, 4) for kk, vv in t.items()},
-                    "step_GBps": round(step_bytes / sum(t.values()) / 1e9, 2)}
+                    "step_GBps": round(step_bytes / sum(t.values()) / 1e9, 2),
+                    "single_thread": {"value": round(ru_bytes / (t1["reduce"] + t1["update"]) / 1e9, 2),
+                                      "stage_seconds": {kk: round(vv, 4) for kk, vv in t1.items()}}}
 
     out = {
         "metric": "reduce+update GB/s on AlexNet-shaped 61M params, k=8 (fraction of HBM peak)",
@@ -330,8 +359,9 @@ def main() -> int:
         "vs_baseline": None,
         "dtype": "f32",
         "data": "synthetic",
-        "config": {"workload": workload_name, "transfer_dtype": "f16", "n_params": n, "n_tensors": len(counts), "k": k,
-                   "step": "pack x8 -> reduce_avg f16->f16 -> sgd_momentum (f16 grad) -> 8 easgd meetings",
+        "config": {"workload": workload_name, "transfer_dtype": cfg.transfer, "n_params": n, "n_tensors": len(counts), "k": k,
+                   "step": (f"pack x{k} -> " if half else "") + f"reduce_avg {cfg.transfer}->{cfg.transfer} -> "
+                           f"sgd_momentum ({cfg.transfer} grad) -> {k} easgd meetings",
                    "gradient_sets": len(grad_sets), "chunk_elems": px.get_option(px.OPT_CHUNK_ELEMS),
                    "blocks_per_cu": px.get_option(px.OPT_BLOCKS_PER_CU),
                    "nontemporal": px.get_option(px.OPT_NONTEMPORAL)},
