@@ -14,8 +14,9 @@
  *
  * Conventions
  *   - Plain C ABI.  Every function returns a PXCHG_* status (0 = success) unless
- *     stated otherwise; nothing throws or aborts, and only the two destroy calls
- *     synchronise the device.
+ *     stated otherwise; nothing throws or aborts, and only the set-up calls that
+ *     say so (the two destroy calls, pxchg_table_set_multipliers) synchronise the
+ *     device.
  *   - "host" / "device" says where a pointer must live.  Data buffers are device
  *     memory owned by the caller; the library owns only tables and buffer sets.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
@@ -102,10 +103,19 @@ int pxchg_plan_chunks(int n_tensors, const int64_t *counts /*host*/, int64_t chu
  * The table is bound to the device current at creation; the library keeps a
  * device copy of the chunk list.  Destroying a table or a buffer set waits for
  * the device to go idle first (launches may still be reading their device-side
- * lists); these are the only calls that synchronise.
+ * lists).
  */
 int pxchg_table_create(int n_tensors, const int64_t *counts /*host*/, pxchg_table **out);
 int pxchg_table_destroy(pxchg_table *table);
+/*
+ * Optional per-tensor multipliers for the update calls (the usual way to give biases another learning rate or
+ * no weight decay; the paper names weight decay and the learning-rate policy among the hyper-parameters,
+ * Section 4).  Host arrays of n_tensors floats, or NULL for "all ones"; both NULL removes the multipliers.
+ * pxchg_sgd_momentum and pxchg_reduce_avg_sgd_momentum then use, for tensor t, lr * lr_mult[t] and
+ * wd * wd_mult[t], each product rounded to binary32.  Synchronises the device (the values must not change
+ * under a running launch); not for the hot path.
+ */
+int pxchg_table_set_multipliers(pxchg_table *table, const float *lr_mult /*host*/, const float *wd_mult /*host*/);
 int64_t pxchg_table_total(const pxchg_table *table);   /* sum of counts; -1 if NULL */
 int pxchg_table_n_tensors(const pxchg_table *table);   /* -1 if NULL */
 int64_t pxchg_table_n_chunks(const pxchg_table *table); /* -1 if NULL */

@@ -30,6 +30,7 @@ SIGNATURES = {
                                  ctypes.POINTER(_i64), ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(_i64)]),
     "pxchg_table_create": (_int, [_int, ctypes.POINTER(_i64), _pp]),
     "pxchg_table_destroy": (_int, [_vp]),
+    "pxchg_table_set_multipliers": (_int, [_vp, ctypes.POINTER(_f), ctypes.POINTER(_f)]),
     "pxchg_table_total": (_i64, [_vp]),
     "pxchg_table_n_tensors": (_int, [_vp]),
     "pxchg_table_n_chunks": (_i64, [_vp]),
@@ -152,6 +153,17 @@ class Table:
     @property
     def n_chunks(self) -> int:
         return int(load().pxchg_table_n_chunks(self._h))
+
+    def set_multipliers(self, lr_mult: Optional[Sequence[float]] = None,
+                        wd_mult: Optional[Sequence[float]] = None) -> None:
+        """Per-tensor learning-rate and decay multipliers for the update calls (None = all ones)."""
+        def arr(x):
+            if x is None:
+                return None
+            if len(x) != len(self.counts):
+                raise ValueError("one multiplier per tensor expected")
+            return (_f * len(x))(*[float(v) for v in x])
+        _check(load().pxchg_table_set_multipliers(self._h, arr(lr_mult), arr(wd_mult)), "pxchg_table_set_multipliers")
 
     def bufset(self, tensors, dtype: Optional[int] = None) -> "BufSet":
         return BufSet(self, tensors, dtype)

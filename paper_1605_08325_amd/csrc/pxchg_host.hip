@@ -139,6 +139,7 @@ int pxchg_table_create(int n_tensors, const int64_t *counts, pxchg_table **out) 
     t->n_chunks = n_chunks;
     t->counts.assign(counts, counts + n_tensors);
     t->d_chunks = nullptr;
+    t->d_mult = nullptr;
 
     if (n_chunks > 0) {
         std::vector<PxChunk> h(n_chunks);
@@ -172,9 +173,47 @@ int pxchg_table_destroy(pxchg_table *table) {
         (void)hipGetLastError();
         rc = PXCHG_ERR_RUNTIME;
     }
+    if (table->d_mult && hipFree(table->d_mult) != hipSuccess) {
+        (void)hipGetLastError();
+        rc = PXCHG_ERR_RUNTIME;
+    }
     table->magic = 0;
     delete table;
     return rc;
+}
+
+int pxchg_table_set_multipliers(pxchg_table *table, const float *lr_mult, const float *wd_mult) {
+    if (!px_valid(table)) return PXCHG_ERR_INVALID_ARG;
+    int device = -1;
+    if (hipGetDevice(&device) != hipSuccess || device != table->device) {
+        (void)hipGetLastError();
+        return PXCHG_ERR_NO_DEVICE;
+    }
+    (void)hipDeviceSynchronize();  // no launch may be reading the old values while they change
+    if (!lr_mult && !wd_mult) {
+        if (table->d_mult && hipFree(table->d_mult) != hipSuccess) {
+            (void)hipGetLastError();
+            return PXCHG_ERR_RUNTIME;
+        }
+        table->d_mult = nullptr;
+        return PXCHG_OK;
+    }
+    std::vector<float> h(2 * (size_t)table->n_tensors);
+    for (int t = 0; t < table->n_tensors; ++t) {
+        h[2 * t] = lr_mult ? lr_mult[t] : 1.0f;
+        h[2 * t + 1] = wd_mult ? wd_mult[t] : 1.0f;
+    }
+    const size_t bytes = h.size() * sizeof(float);
+    if (!table->d_mult && hipMalloc((void **)&table->d_mult, bytes) != hipSuccess) {
+        (void)hipGetLastError();
+        table->d_mult = nullptr;
+        return PXCHG_ERR_RUNTIME;
+    }
+    if (hipMemcpy(table->d_mult, h.data(), bytes, hipMemcpyHostToDevice) != hipSuccess) {
+        (void)hipGetLastError();
+        return PXCHG_ERR_RUNTIME;
+    }
+    return PXCHG_OK;
 }
 
 int64_t pxchg_table_total(const pxchg_table *table) { return px_valid(table) ? table->total : -1; }

@@ -27,6 +27,7 @@ struct pxchg_table {
     int64_t n_chunks;
     std::vector<int64_t> counts;
     PxChunk *d_chunks;  // device copy of the chunk list
+    float *d_mult;      // optional: n_tensors pairs (lr multiplier, decay multiplier); null = all ones
 };
 
 struct pxchg_bufset {

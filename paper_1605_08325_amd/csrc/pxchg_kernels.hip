@@ -434,8 +434,19 @@ struct UpdateArgs {
     const void *const *grad;
     void *const *param;
     void *const *vel;
+    const float *mult;  // per tensor (lr multiplier, decay multiplier), or null
     float lr, mu, wd;
 };
+
+// The tensor's own learning rate and decay: the call's values times the table's per-tensor multipliers, each
+// product rounded to binary32 (uniform per chunk).
+__device__ __forceinline__ void tensor_rates(const float *mult, int tensor, float &lr, float &wd) {
+    if (mult) {
+        const float PX_CONST *m = (const float PX_CONST *)mult + 2 * tensor;
+        lr = lr * m[0];
+        wd = wd * m[1];
+    }
+}
 
 template <typename TG, int NT>
 struct UpdateOp {
@@ -480,6 +491,7 @@ __global__ __launch_bounds__(BLOCK) void pxchg_sgd_momentum_kernel(const PxChunk
         op.lr = args.lr;
         op.mu = args.mu;
         op.wd = args.wd;
+        tensor_rates(args.mult, ch.tensor, op.lr, op.wd);
         int head = head_of((uintptr_t)op.g, sizeof(TG));
         if (misalign_after((uintptr_t)op.w, 4, head) | misalign_after((uintptr_t)op.v, 4, head)) head = -1;
         run_chunk<use_split<float>()>(op, ch.len, head);
@@ -492,6 +504,7 @@ struct FusedArgs {
     const void *const *contrib[PXCHG_MAX_K];
     void *const *param;
     void *const *vel;
+    const float *mult;  // per tensor (lr multiplier, decay multiplier), or null
     int k;
     int use_div;
     float kf, scale;
@@ -559,6 +572,7 @@ __global__ __launch_bounds__(BLOCK) void pxchg_reduce_avg_sgd_momentum_kernel(co
         op.lr = args.lr;
         op.mu = args.mu;
         op.wd = args.wd;
+        tensor_rates(args.mult, ch.tensor, op.lr, op.wd);
 #pragma unroll
         for (int q = 0; q < K; ++q) op.src[q] = table_ptr<const TI>(args.contrib[q], ch.tensor) + ch.start;
         int head = head_of((uintptr_t)op.src[0], sizeof(TI));
@@ -959,6 +973,7 @@ int pxchg_sgd_momentum(const pxchg_table *table, const pxchg_bufset *grad, pxchg
     a.grad = (const void *const *)grad->d_ptrs;
     a.param = (void *const *)param->d_ptrs;
     a.vel = (void *const *)vel->d_ptrs;
+    a.mult = table->d_mult;
     a.lr = lr;
     a.mu = mu;
     a.wd = wd;
@@ -1004,6 +1019,7 @@ int pxchg_reduce_avg_sgd_momentum(const pxchg_table *table, int k, const pxchg_b
     }
     a.param = (void *const *)param->d_ptrs;
     a.vel = (void *const *)vel->d_ptrs;
+    a.mult = table->d_mult;
     a.k = k;
     fill_scale(k, mode, &a.use_div, &a.kf, &a.scale);
     a.lr = lr;

@@ -660,3 +660,46 @@ def test_exchange_step_replayed_from_a_hip_graph(px, oracle_mod):
         bad, mx, ss = px.read_stats(d_stats)
         wbad, wmx, wss = oracle_mod.stats_tensors(avg)
         assert bad == wbad and mx == wmx and abs(ss - wss) <= 1e-12 * wss
+
+
+# ------------------------------------------------------------------ per-tensor multipliers
+
+@pytest.mark.parametrize("fused", [False, True])
+def test_per_tensor_learning_rate_and_decay_multipliers(px, oracle_mod, fused):
+    """Biases with twice the learning rate and no weight decay, one frozen tensor: tensor t is updated with
+    lr * lr_mult[t] and wd * wd_mult[t] (products rounded to binary32), as a per-tensor oracle call."""
+    counts = [34_848, 96, 20_001, 3, 8192 * 2 + 5, 1000]
+    lr_mult = [1.0, 2.0, 1.0, 2.0, 0.0, 0.3]
+    wd_mult = [1.0, 0.0, 1.0, 0.0, 1.0, 2.5]
+    k, lr, mu, wd = 3, 0.01, 0.9, 5e-4
+    table = px.Table(counts)
+    table.set_multipliers(lr_mult, wd_mult)
+    grads = [_gauss(counts, 1000, i) for i in range(k)]
+    w, v = _gauss(counts, 1001, role="param"), _gauss(counts, 1002, sigma=1e-3, role="velocity")
+    w_before = [a.copy() for a in w]
+    d_w, d_v = to_device(w), to_device(v)
+    s_g = [table.bufset(to_device(g)) for g in grads]
+    s_w, s_v = table.bufset(d_w), table.bufset(d_v)
+    if fused:
+        px.reduce_avg_sgd_momentum(table, s_g, s_w, s_v, lr, mu, wd, px.AVG, px.F32)
+    else:
+        d_avg = empty_like_device(counts, np.float32)
+        s_avg = table.bufset(d_avg)
+        px.reduce_avg(table, s_g, s_avg)
+        px.sgd_momentum(table, s_avg, s_w, s_v, lr, mu, wd)
+    avg = oracle_mod.reduce_avg_tensors(grads)
+    for t in range(len(counts)):
+        lr_t = np.float32(lr) * np.float32(lr_mult[t])
+        wd_t = np.float32(wd) * np.float32(wd_mult[t])
+        oracle_mod.sgd_momentum(avg[t], w[t], v[t], lr_t, mu, wd_t)
+    assert_bits_equal(to_host(d_w), w, "w")
+    assert_bits_equal(to_host(d_v), v, "v")
+    assert np.any(w[0] != w_before[0])
+    # removing the multipliers restores the plain behaviour
+    table.set_multipliers(None, None)
+    w2, v2 = _gauss(counts, 1001, role="param"), _gauss(counts, 1002, sigma=1e-3, role="velocity")
+    d_w2, d_v2 = to_device(w2), to_device(v2)
+    d_avg = to_device(avg)
+    px.sgd_momentum(table, table.bufset(d_avg), table.bufset(d_w2), table.bufset(d_v2), lr, mu, wd)
+    oracle_mod.sgd_momentum_tensors(avg, w2, v2, lr, mu, wd)
+    assert_bits_equal(to_host(d_w2), w2, "w without multipliers")
