@@ -6,13 +6,15 @@
 // memory traffic only:
 //   * one launch per call: workgroups walk a device-resident list of chunks
 //     (tensor, start, length), so 16 tensors or 116 cost the same single launch;
-//   * each lane moves 16-byte vectors (8 halves or 4 floats per load/store) and
-//     issues all loads of a step before the first use, so a lane keeps up to
-//     k x 16 bytes in flight;
-//   * no LDS staging and no cross-lane traffic: lanes are independent, which
-//     also makes the fixed worker order of the sum trivially bit-exact;
-//   * streaming accesses may carry the non-temporal hint (nothing is reused
-//     inside one launch).
+//   * each lane handles 8 elements per step with 16-byte (or, for binary16 next
+//     to float32 operands, 8-byte) vector accesses laid out so that every memory
+//     instruction of a wavefront covers one contiguous stretch, and issues all
+//     loads of a step before the first use (k x 16 bytes in flight per lane);
+//   * no LDS staging and no cross-lane traffic in the exchange kernels: lanes are
+//     independent, which also makes the fixed worker order of the sum trivially
+//     bit-exact (only the diagnostics kernel reduces across lanes);
+//   * nothing is reused inside one launch, so loads carry the non-temporal hint
+//     and stores a per-kernel streaming policy, both chosen by measurement.
 // There is no matrix-core work here on purpose: there is no contraction.
 //
 // Floating point: compiled with -ffp-contract=off and `fp contract(off)` below,
@@ -41,6 +43,7 @@ constexpr int UNIT = 8;     // elements one lane handles per vector step
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
 
 // Data pointers come out of pointer tables in memory, so the compiler cannot
 // know they are global addresses; say so, to get global (not flat) memory
@@ -70,7 +73,7 @@ __device__ __forceinline__ V ldv(const PX_GLOBAL V *p) {
     else
         return *p;
 }
-// Streaming store with agent scope ("sc1 nt"): measured 4 % faster than the plain non-temporal store on the
+// Streaming store with agent scope ("sc1 nt"): measured 1-4 % faster than the plain non-temporal store on the
 // kernels that write half of their traffic.  The compiler has no builtin that sets both bits on a 16-byte
 // vector store, hence the instruction is written out; the trailing s_nop covers the one wait state the
 // hardware wants between a wide store and a later write of its data registers, which the compiler cannot
@@ -94,8 +97,6 @@ __device__ __forceinline__ void stv(PX_GLOBAL V *p, V x) {
     else
         *p = x;
 }
-
-typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
 
 // A lane's 8 elements are [i0, i0+4) and [i1, i1+4) of the chunk.  In the
 // contiguous layout (SPLIT = false) i1 == i0 + 4.  In the split layout the two
@@ -164,8 +165,7 @@ __device__ __forceinline__ void store1(_Float16 *p, float x) { *(PX_GLOBAL _Floa
 // Number of leading elements after which `a` is 16-byte aligned.
 __device__ __forceinline__ int head_of(uintptr_t a, int es) { return (int)(((16u - (unsigned)(a & 15u)) & 15u) / (unsigned)es); }
 // Low four address bits of `a` after skipping `head` elements; zero means 16-byte aligned.  The kernels OR these
-// together for all operands AFTER all table pointers have been loaded, so that the scalar pointer loads of a chunk
-// are issued back to back instead of each waiting for the one before.
+// together over all operands of a chunk.
 __device__ __forceinline__ unsigned misalign_after(uintptr_t a, int es, int head) { return (unsigned)(a + (uintptr_t)head * es) & 15u; }
 
 // One vector step of a lane: every load is issued before the first use, then the
@@ -221,7 +221,6 @@ constexpr bool use_split() {
     return PX_SPLIT && (std::is_same<T, float>::value || ...);
 }
 
-__device__ __forceinline__ void scale_sum8(F8 &s, int use_div, float kf, float scale);
 __device__ __forceinline__ float scale_sum(float s, int use_div, float kf, float scale) {
     // AVG with k a power of two and SUM multiply by an exactly representable
     // factor (1/k or 1), which gives the correctly rounded quotient; other k take
