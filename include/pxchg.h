@@ -67,7 +67,8 @@ enum pxchg_option {
                                     inside one device allocation */
     PXCHG_OPT_NONTEMPORAL = 3    /* -1 (default): each kernel's own measured-best policy; 0..3: bit 0
                                     puts the non-temporal hint on vector loads, bit 1 on vector stores;
-                                    4: non-temporal loads, and stores that are streaming with agent scope */
+                                    4: non-temporal loads, and stores that are streaming with agent scope;
+                                    5: non-temporal loads, and agent-scope stores without the streaming hint */
 };
 
 typedef struct pxchg_table pxchg_table;

@@ -66,7 +66,7 @@ int pxchg_set_option(int option, int64_t value) {
             o.check_ranges = value;
             return PXCHG_OK;
         case PXCHG_OPT_NONTEMPORAL:
-            if (value < -1 || value > 4) return PXCHG_ERR_INVALID_ARG;
+            if (value < -1 || value > 5) return PXCHG_ERR_INVALID_ARG;
             o.nontemporal = value;
             return PXCHG_OK;
         default:

@@ -68,7 +68,7 @@ struct F8 {
 
 template <int NT, typename V>
 __device__ __forceinline__ V ldv(const PX_GLOBAL V *p) {
-    if constexpr ((NT & 1) != 0 || NT == 4)
+    if constexpr (NT == 1 || NT == 3 || NT == 4 || NT == 5)
         return __builtin_nontemporal_load(p);
     else
         return *p;
@@ -86,13 +86,26 @@ __device__ __forceinline__ void store_sc1_nt(PX_GLOBAL V *p, V x) {
     else
         asm volatile("global_store_dwordx2 %0, %1, off sc1 nt\n\ts_nop 0" ::"v"(p), "v"(x) : "memory");
 }
+// Agent-scope store without the streaming hint ("sc1"): measured 3 % faster than a plain store on the reduce
+// kernel, whose writes are one byte in nine of its traffic.
+template <typename V>
+__device__ __forceinline__ void store_sc1(PX_GLOBAL V *p, V x) {
+    static_assert(sizeof(V) == 16 || sizeof(V) == 8, "dwordx4 or dwordx2");
+    if constexpr (sizeof(V) == 16)
+        asm volatile("global_store_dwordx4 %0, %1, off sc1\n\ts_nop 0" ::"v"(p), "v"(x) : "memory");
+    else
+        asm volatile("global_store_dwordx2 %0, %1, off sc1\n\ts_nop 0" ::"v"(p), "v"(x) : "memory");
+}
 
-// NT: 0 plain, bit 0 non-temporal loads, bit 1 non-temporal stores, 4 = non-temporal loads with "sc1 nt" stores.
+// NT: 0 plain, bit 0 non-temporal loads, bit 1 non-temporal stores, 4 = non-temporal loads with "sc1 nt" stores,
+// 5 = non-temporal loads with "sc1" stores.
 template <int NT, typename V>
 __device__ __forceinline__ void stv(PX_GLOBAL V *p, V x) {
     if constexpr (NT == 4)
         store_sc1_nt(p, x);
-    else if constexpr ((NT & 2) != 0)
+    else if constexpr (NT == 5)
+        store_sc1(p, x);
+    else if constexpr (NT == 2 || NT == 3)
         __builtin_nontemporal_store(x, p);
     else
         *p = x;
@@ -742,7 +755,7 @@ __global__ __launch_bounds__(STATS_BLOCK) void pxchg_stats_kernel(const PxChunk 
 
 struct Launch {
     dim3 grid;
-    int nt;  // 0..3: bit 0 non-temporal loads, bit 1 non-temporal stores; 4: nt loads, "sc1 nt" stores
+    int nt;  // 0..3: bit 0 non-temporal loads, bit 1 non-temporal stores; 4: nt loads, "sc1 nt" stores; 5: nt loads, "sc1" stores
 };
 
 // `nt_default` is the kernel's own measured-best policy, used unless the caller
@@ -757,22 +770,25 @@ Launch launch_shape(const pxchg_table *t, int64_t n_virtual, int nt_default) {
     return l;
 }
 
-// Measured on MI355X (AlexNet-shaped set, k = 8): the hint on loads helps every
-// kernel; on stores it helps the ones that write a large share of their traffic
-// and slightly hurts the reduce, which writes one byte in nine.
-// The agent-scope streaming store (policy 4) measured 1-2 % faster than the plain non-temporal store for the
-// update with a binary16 gradient and for the single elastic meeting, the same for pack and the fused elastic
-// round, and 5 % slower for the fused reduce+update; it is the default only where it won.
-constexpr int NT_LOADS = 1, NT_STORES = 2, NT_BOTH = 3, NT_LOADS_SC1_STORES = 4;
+// Measured on MI355X (AlexNet-shaped set, k = 8), A/B inside one run:
+//   * the non-temporal hint on loads helps every kernel (+10..17 %);
+//   * the reduce (one written byte in nine) and the widening unpack are fastest with agent-scope stores without
+//     the streaming hint (policy 5: +3..4 % over plain stores, +7 % over non-temporal stores);
+//   * pack, the update with a binary16 gradient and the single elastic meeting are fastest with agent-scope
+//     streaming stores (policy 4: +1..2 % over plain non-temporal stores);
+//   * the update with a binary32 gradient, the fused reduce+update and the fused elastic round are fastest with
+//     plain non-temporal stores (policy 3; policy 4 is 2..5 % slower there).
+constexpr int NT_BOTH = 3, NT_LOADS_SC1NT_STORES = 4, NT_LOADS_SC1_STORES = 5;
 
-// Expands CALL(n) for the run-time cache policy n = 0..4.
+// Expands CALL(n) for the run-time cache policy n = 0..5.
 #define PX_DISPATCH_NT(nt, CALL) \
     switch (nt) {                \
         case 0: CALL(0); break;  \
         case 1: CALL(1); break;  \
         case 2: CALL(2); break;  \
         case 3: CALL(3); break;  \
-        default: CALL(4); break; \
+        case 4: CALL(4); break;  \
+        default: CALL(5); break; \
     }
 
 int check_table(const pxchg_table *t) {
@@ -818,10 +834,7 @@ int launch_convert(const pxchg_table *t, int k, const pxchg_bufset *const *src, 
             if (dst[i] == dst[j]) return PXCHG_ERR_INVALID_ARG;
     if (t->n_chunks == 0) return PXCHG_OK;
     const int64_t n_virtual = t->n_chunks * k;
-    // narrowing (pack) reads two bytes for each one written and likes the hint on
-    // both sides; widening (unpack) writes twice what it reads and measured best
-    // with the hint on the stores only
-    const Launch l = launch_shape(t, n_virtual, sizeof(TO) < sizeof(TI) ? NT_BOTH : NT_STORES);
+    const Launch l = launch_shape(t, n_virtual, sizeof(TO) < sizeof(TI) ? NT_LOADS_SC1NT_STORES : NT_LOADS_SC1_STORES);
 #define PX_CALL(N)                                                                                            \
     hipLaunchKernelGGL((pxchg_convert_kernel<TI, TO, N>), l.grid, dim3(BLOCK), 0, stream, t->d_chunks,         \
                        (int)t->n_chunks, n_virtual, a)
@@ -841,7 +854,7 @@ void launch_reduce_k(const pxchg_table *t, const Launch &l, const ReduceArgs &a,
 
 template <typename TI, typename TO>
 void launch_reduce(const pxchg_table *t, int k, const ReduceArgs &a, hipStream_t stream) {
-    const Launch l = launch_shape(t, t->n_chunks, NT_LOADS);
+    const Launch l = launch_shape(t, t->n_chunks, NT_LOADS_SC1_STORES);
     switch (k) {
         case 1: launch_reduce_k<1, TI, TO>(t, l, a, stream); break;
         case 2: launch_reduce_k<2, TI, TO>(t, l, a, stream); break;
@@ -976,7 +989,7 @@ int pxchg_sgd_momentum(const pxchg_table *table, const pxchg_bufset *grad, pxchg
     a.lr = lr;
     a.mu = mu;
     a.wd = wd;
-    const Launch l = launch_shape(table, table->n_chunks, grad->dtype == PXCHG_F16 ? NT_LOADS_SC1_STORES : NT_BOTH);
+    const Launch l = launch_shape(table, table->n_chunks, grad->dtype == PXCHG_F16 ? NT_LOADS_SC1NT_STORES : NT_BOTH);
     hipStream_t s = (hipStream_t)stream;
 #define PX_CALL32(N)                                                                                      \
     hipLaunchKernelGGL((pxchg_sgd_momentum_kernel<float, N>), l.grid, dim3(BLOCK), 0, s, table->d_chunks,  \
@@ -1045,7 +1058,7 @@ int pxchg_easgd_round(const pxchg_table *table, int k, pxchg_bufset *const *x, p
     }
     if (table->n_chunks == 0) return PXCHG_OK;
     hipStream_t s = (hipStream_t)stream;
-    const Launch l = launch_shape(table, table->n_chunks, k == 1 ? NT_LOADS_SC1_STORES : NT_BOTH);
+    const Launch l = launch_shape(table, table->n_chunks, k == 1 ? NT_LOADS_SC1NT_STORES : NT_BOTH);
     // More than 8 workers: successive launches of up to 8, the center carried
     // through memory between them (same arithmetic, same order).
     for (int i0 = 0; i0 < k; i0 += 8) {

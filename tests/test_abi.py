@@ -83,7 +83,7 @@ def test_options_validate_their_values(px):
             with pytest.raises(px.PxchgError):
                 px.set_option(px.OPT_CHUNK_ELEMS, bad)
         for opt, bad in ((px.OPT_BLOCKS_PER_CU, -1), (px.OPT_BLOCKS_PER_CU, 65), (px.OPT_CHECK_RANGES, 2),
-                         (px.OPT_NONTEMPORAL, 5), (px.OPT_NONTEMPORAL, -2), (17, 0)):
+                         (px.OPT_NONTEMPORAL, 6), (px.OPT_NONTEMPORAL, -2), (17, 0)):
             with pytest.raises(px.PxchgError):
                 px.set_option(opt, bad)
         assert px.get_option(17) == -1

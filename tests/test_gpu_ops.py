@@ -354,7 +354,7 @@ def test_results_do_not_depend_on_launch_shape(px, oracle_mod, chunk, bpc):
         px.set_option(px.OPT_BLOCKS_PER_CU, old[1])
 
 
-@pytest.mark.parametrize("policy", [0, 1, 2, 3, 4])
+@pytest.mark.parametrize("policy", [0, 1, 2, 3, 4, 5])
 def test_every_cache_policy_gives_the_same_bits(px, oracle_mod, policy):
     """The cache hints on loads and stores (none, non-temporal loads, non-temporal stores, both, and
     non-temporal loads with agent-scope streaming stores) never change a result."""
