@@ -154,3 +154,15 @@ def test_table_create_without_a_gpu_reports_no_device(px):
     with pytest.raises(px.PxchgError) as e:
         px.Table([10, 20])
     assert e.value.status == 4
+
+
+def test_header_is_plain_c(tmp_path):
+    """The boundary must be usable from C: the header compiles as C99 and as C++ with no other include."""
+    import subprocess
+    src = tmp_path / "use_header.c"
+    src.write_text('#include "pxchg.h"\nint main(void) { pxchg_stats s; s.nonfinite = 0; return (int)s.nonfinite + PXCHG_OK; }\n')
+    inc = os.path.join(ROOT, "include")
+    for cc, std in (("gcc", "-std=c99"), ("g++", "-std=c++11")):
+        r = subprocess.run([cc, std, "-pedantic", "-Wall", "-Werror", "-fsyntax-only", "-x",
+                            "c" if cc == "gcc" else "c++", "-I", inc, str(src)], capture_output=True, text=True)
+        assert r.returncode == 0, r.stderr
