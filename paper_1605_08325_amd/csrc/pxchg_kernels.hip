@@ -6,10 +6,11 @@
 // memory traffic only:
 //   * one launch per call: workgroups walk a device-resident list of chunks
 //     (tensor, start, length), so 16 tensors or 116 cost the same single launch;
-//   * each lane handles 8 elements per step with 16-byte (or, for binary16 next
-//     to float32 operands, 8-byte) vector accesses laid out so that every memory
-//     instruction of a wavefront covers one contiguous stretch, and issues all
-//     loads of a step before the first use (k x 16 bytes in flight per lane);
+//   * each lane moves one 16-byte vector per operand and step (8 halves in a
+//     pure binary16 kernel; 4 floats, with binary16 operands as 8-byte pieces,
+//     in a kernel that touches float32), so every memory instruction of a
+//     wavefront covers one contiguous 1 KiB, and issues all loads of a step
+//     before the first use (k x 16 bytes in flight per lane);
 //   * no LDS staging and no cross-lane traffic in the exchange kernels: lanes are
 //     independent, which also makes the fixed worker order of the sum trivially
 //     bit-exact (only the diagnostics kernel reduces across lanes);
@@ -30,16 +31,26 @@
 
 namespace {
 
-// One wavefront per workgroup and one 512-element chunk per workgroup measured
-// best on MI355X (more, smaller workgroups keep the window of addresses that is
-// in flight narrow); larger workgroups and several vector steps per lane were
-// measured slower.
-#ifndef PX_BLOCK
-#define PX_BLOCK 64
-#endif
-constexpr int BLOCK = PX_BLOCK;  // lanes per workgroup (a multiple of the 64-lane wavefront)
-static_assert(BLOCK % 64 == 0 && BLOCK >= PXCHG_MAX_K, "whole wavefronts, and one lane per worker in the any-k kernel");
-constexpr int UNIT = 8;     // elements one lane handles per vector step
+// A workgroup takes one 512-element chunk, and every memory instruction of a
+// wavefront covers one contiguous stretch (1 KiB for 16-byte lanes).  Three lane
+// layouts do that, chosen per kernel by measurement on MI355X:
+//   * pure binary16 kernels: one wavefront, lane l owns elements 8l..8l+7 (one
+//     16-byte access per operand);
+//   * kernels that mix binary16 and float32 operands, and the many-operand float32
+//     kernels: one wavefront in the SPLIT layout, lane l owns 4l..4l+3 and
+//     256+4l..256+4l+3 (float32 as two 16-byte accesses 1 KiB apart, binary16 as
+//     two 8-byte accesses);
+//   * the in-place float32 kernels with few operands (momentum update, one
+//     elastic meeting): two wavefronts, lane l of the 128 owns 4l..4l+3 (+6 % on
+//     the elastic meeting, +1..2 % on the update; 10..20 % slower for pack/unpack).
+// As many small workgroups as there are chunks keep the window of addresses in
+// flight narrow; larger tiles, several steps per lane and persistent grids were
+// all measured slower.
+template <typename... T>
+constexpr bool touches_f32() {
+    return (std::is_same<T, float>::value || ...);
+}
+static_assert(PXCHG_MAX_K <= 64, "the any-k kernel uses one lane per worker to fetch pointers");
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
@@ -62,8 +73,9 @@ __device__ __forceinline__ T *table_ptr(void *const *table, int tensor) {
     return (T *)((void *const PX_CONST *)table)[tensor];
 }
 
-struct F8 {
-    float v[UNIT];
+template <int U>
+struct FV {
+    float v[U];
 };
 
 template <int NT, typename V>
@@ -111,63 +123,72 @@ __device__ __forceinline__ void stv(PX_GLOBAL V *p, V x) {
         *p = x;
 }
 
-// A lane's 8 elements are [i0, i0+4) and [i1, i1+4) of the chunk.  In the
-// contiguous layout (SPLIT = false) i1 == i0 + 4.  In the split layout the two
-// groups are 256 elements apart, so that each float32 memory instruction of a
-// wavefront covers one contiguous 1 KiB instead of every other 16 bytes of 2 KiB.
-// All group addresses are 16-byte aligned for float32 and 8-byte aligned for
-// binary16 (16-byte in the contiguous layout).
-template <int NT, bool SPLIT>
-__device__ __forceinline__ F8 load8(const float *p, int i0, int i1) {
-    const f32x4 a = ldv<NT>((const PX_GLOBAL f32x4 *)(p + i0));
-    const f32x4 b = ldv<NT>((const PX_GLOBAL f32x4 *)(p + i1));
-    F8 r;
+// A lane's U elements starting at p, as binary32: U consecutive elements, or (SPLIT, U = 8) elements
+// p[0..3] and p[256..259].  p is aligned to the access: 16 bytes, or 8 bytes for four halves.
+constexpr int SPLIT_GAP = 256;
+template <int NT, int U, bool SPLIT>
+__device__ __forceinline__ FV<U> loadv(const float *p) {
+    static_assert(U == 4 || U == 8, "one or two 16-byte vectors");
+    static_assert(!SPLIT || U == 8, "the split layout is two groups of four");
+    FV<U> r;
+    const f32x4 a = ldv<NT>((const PX_GLOBAL f32x4 *)p);
     r.v[0] = a.x; r.v[1] = a.y; r.v[2] = a.z; r.v[3] = a.w;
-    r.v[4] = b.x; r.v[5] = b.y; r.v[6] = b.z; r.v[7] = b.w;
-    return r;
-}
-template <int NT, bool SPLIT>
-__device__ __forceinline__ F8 load8(const _Float16 *p, int i0, int i1) {
-    F8 r;
-    if constexpr (SPLIT) {
-        const f16x4 a = ldv<NT>((const PX_GLOBAL f16x4 *)(p + i0));
-        const f16x4 b = ldv<NT>((const PX_GLOBAL f16x4 *)(p + i1));
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {  // exact widening
-            r.v[i] = (float)a[i];
-            r.v[4 + i] = (float)b[i];
-        }
-    } else {
-        const f16x8 h = ldv<NT>((const PX_GLOBAL f16x8 *)(p + i0));
-#pragma unroll
-        for (int i = 0; i < UNIT; ++i) r.v[i] = (float)h[i];  // exact widening
+    if constexpr (U == 8) {
+        const f32x4 b = ldv<NT>((const PX_GLOBAL f32x4 *)(p + (SPLIT ? SPLIT_GAP : 4)));
+        r.v[4] = b.x; r.v[5] = b.y; r.v[6] = b.z; r.v[7] = b.w;
     }
     return r;
 }
-template <int NT, bool SPLIT>
-__device__ __forceinline__ void store8(float *p, int i0, int i1, const F8 &x) {
-    f32x4 a, b;
-    a.x = x.v[0]; a.y = x.v[1]; a.z = x.v[2]; a.w = x.v[3];
-    b.x = x.v[4]; b.y = x.v[5]; b.z = x.v[6]; b.w = x.v[7];
-    stv<NT>((PX_GLOBAL f32x4 *)(p + i0), a);
-    stv<NT>((PX_GLOBAL f32x4 *)(p + i1), b);
-}
-template <int NT, bool SPLIT>
-__device__ __forceinline__ void store8(_Float16 *p, int i0, int i1, const F8 &x) {
-    if constexpr (SPLIT) {
-        f16x4 a, b;
+template <int NT, int U, bool SPLIT>
+__device__ __forceinline__ FV<U> loadv(const _Float16 *p) {
+    static_assert(U == 4 || U == 8, "8 or 16 bytes");
+    static_assert(!SPLIT || U == 8, "the split layout is two groups of four");
+    FV<U> r;
+    if constexpr (U == 4 || SPLIT) {
+        const f16x4 a = ldv<NT>((const PX_GLOBAL f16x4 *)p);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {  // round to nearest even
-            a[i] = (_Float16)x.v[i];
-            b[i] = (_Float16)x.v[4 + i];
+        for (int i = 0; i < 4; ++i) r.v[i] = (float)a[i];  // exact widening
+        if constexpr (SPLIT) {
+            const f16x4 b = ldv<NT>((const PX_GLOBAL f16x4 *)(p + SPLIT_GAP));
+#pragma unroll
+            for (int i = 0; i < 4; ++i) r.v[4 + i] = (float)b[i];
         }
-        stv<NT>((PX_GLOBAL f16x4 *)(p + i0), a);
-        stv<NT>((PX_GLOBAL f16x4 *)(p + i1), b);
+    } else {
+        const f16x8 h = ldv<NT>((const PX_GLOBAL f16x8 *)p);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) r.v[i] = (float)h[i];  // exact widening
+    }
+    return r;
+}
+template <int NT, int U, bool SPLIT>
+__device__ __forceinline__ void storev(float *p, const FV<U> &x) {
+    f32x4 a;
+    a.x = x.v[0]; a.y = x.v[1]; a.z = x.v[2]; a.w = x.v[3];
+    stv<NT>((PX_GLOBAL f32x4 *)p, a);
+    if constexpr (U == 8) {
+        f32x4 b;
+        b.x = x.v[4]; b.y = x.v[5]; b.z = x.v[6]; b.w = x.v[7];
+        stv<NT>((PX_GLOBAL f32x4 *)(p + (SPLIT ? SPLIT_GAP : 4)), b);
+    }
+}
+template <int NT, int U, bool SPLIT>
+__device__ __forceinline__ void storev(_Float16 *p, const FV<U> &x) {
+    if constexpr (U == 4 || SPLIT) {
+        f16x4 a;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) a[i] = (_Float16)x.v[i];  // round to nearest even
+        stv<NT>((PX_GLOBAL f16x4 *)p, a);
+        if constexpr (SPLIT) {
+            f16x4 b;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) b[i] = (_Float16)x.v[4 + i];
+            stv<NT>((PX_GLOBAL f16x4 *)(p + SPLIT_GAP), b);
+        }
     } else {
         f16x8 h;
 #pragma unroll
-        for (int i = 0; i < UNIT; ++i) h[i] = (_Float16)x.v[i];  // round to nearest even
-        stv<NT>((PX_GLOBAL f16x8 *)(p + i0), h);
+        for (int i = 0; i < 8; ++i) h[i] = (_Float16)x.v[i];  // round to nearest even
+        stv<NT>((PX_GLOBAL f16x8 *)p, h);
     }
 }
 __device__ __forceinline__ float load1(const float *p) { return *(const PX_GLOBAL float *)p; }
@@ -177,61 +198,48 @@ __device__ __forceinline__ void store1(_Float16 *p, float x) { *(PX_GLOBAL _Floa
 
 // Number of leading elements after which `a` is 16-byte aligned.
 __device__ __forceinline__ int head_of(uintptr_t a, int es) { return (int)(((16u - (unsigned)(a & 15u)) & 15u) / (unsigned)es); }
-// Low four address bits of `a` after skipping `head` elements; zero means 16-byte aligned.  The kernels OR these
-// together over all operands of a chunk.
-__device__ __forceinline__ unsigned misalign_after(uintptr_t a, int es, int head) { return (unsigned)(a + (uintptr_t)head * es) & 15u; }
+// Address bits of `a`, after skipping `head` elements, that spoil the alignment of a U-element vector access
+// (16 bytes, or 8 for four halves); zero means aligned.  The kernels OR these together over a chunk's operands.
+template <int U>
+__device__ __forceinline__ unsigned misalign_after(uintptr_t a, int es, int head) {
+    const unsigned mask = (unsigned)(U * es < 16 ? U * es : 16) - 1u;
+    return (unsigned)(a + (uintptr_t)head * es) & mask;
+}
+// (The split layout's 8-byte binary16 accesses would be content with 8-byte alignment, but the consecutive
+// 8-element steps that finish a chunk use 16-byte ones, so U = 8 always asks for 16.)
 
 // One vector step of a lane: every load is issued before the first use, then the
 // arithmetic, then the stores.
 template <bool SP, class Op>
-__device__ __forceinline__ void vector_step(const Op &op, int i0, int i1) {
+__device__ __forceinline__ void vector_step(const Op &op, int i) {
     typename Op::State st;
-    op.template load<SP>(st, i0, i1);
+    op.template load<SP>(st, i);
     op.compute(st);
-    op.template store<SP>(st, i0, i1);
+    op.template store<SP>(st, i);
 }
 
-// Walks one chunk: an element-wise head until every operand is 16-byte aligned,
-// 8-element vector steps, an element-wise tail.  `head` < 0 means the operands
-// cannot be aligned together and the whole chunk goes element by element.
-// The vector part is cut into 512-element tiles (one vector step of a whole
-// wavefront); with SPLIT, tiles use the split lane layout.  What is left after
-// the last full tile goes in the contiguous layout.
-// NTH lanes (whole wavefronts) work on the chunk together; `tid` is the lane's index among them.
-template <bool SPLIT, class Op, int NTH = BLOCK>
-__device__ __forceinline__ void run_chunk(const Op &op, int len, int head, int tid = threadIdx.x) {
-    constexpr int BLOCK = NTH;  // shadows the workgroup size: the strides below are those of the cooperating lanes
+// Walks one chunk with NTH cooperating lanes (`tid` is the lane's index among them): an element-wise head
+// until every operand is aligned, U-element vector steps, an element-wise tail.  `head` < 0 means the operands
+// cannot be aligned together and the whole chunk goes element by element.  With SPLIT (U = 8) the vector part
+// is cut into 512-element tiles, one split-layout step of a whole wavefront each, and what is left after the
+// last full tile goes in consecutive 8-element steps.
+template <int U, bool SPLIT, int NTH, class Op>
+__device__ __forceinline__ void run_chunk(const Op &op, int len, int head, int tid) {
     if (head < 0 || head > len) {
-        for (int i = tid; i < len; i += BLOCK) op.scalar(i);
+        for (int i = tid; i < len; i += NTH) op.scalar(i);
         return;
     }
-    for (int i = tid; i < head; i += BLOCK) op.scalar(i);
-    constexpr int TILE = 64 * UNIT;
-    constexpr int WAVES = BLOCK / 64;
-    const int nvec = (len - head) / UNIT;
-    const int ntile = nvec / 64;
-    const int lane = tid & 63, wave = tid >> 6;
-    const int lane_off = SPLIT ? lane * 4 : lane * UNIT;
-    constexpr int second = SPLIT ? 64 * 4 : 4;
-    for (int t = wave; t < ntile; t += WAVES) {
-        const int i0 = head + t * TILE + lane_off;
-        vector_step<SPLIT>(op, i0, i0 + second);
+    for (int i = tid; i < head; i += NTH) op.scalar(i);
+    const int nvec = (len - head) / U;
+    int done = 0;
+    if constexpr (SPLIT) {
+        static_assert(U == 8 && NTH % 64 == 0, "two groups of four per lane, whole wavefronts");
+        const int ntile = nvec / 64;
+        for (int t = tid >> 6; t < ntile; t += NTH / 64) vector_step<true>(op, head + t * (64 * U) + (tid & 63) * 4);
+        done = ntile * 64;
     }
-    for (int u = ntile * 64 + tid; u < nvec; u += BLOCK) {
-        const int i0 = head + u * UNIT;
-        vector_step<false>(op, i0, i0 + 4);
-    }
-    for (int i = head + nvec * UNIT + tid; i < len; i += BLOCK) op.scalar(i);
-}
-
-#ifndef PX_SPLIT
-#define PX_SPLIT 1
-#endif
-// Kernels that touch float32 arrays use the split layout; a pure binary16 kernel
-// already moves one contiguous 1 KiB per wavefront instruction.
-template <typename... T>
-constexpr bool use_split() {
-    return PX_SPLIT && (std::is_same<T, float>::value || ...);
+    for (int u = done + tid; u < nvec; u += NTH) vector_step<false>(op, head + u * U);
+    for (int i = head + nvec * U + tid; i < len; i += NTH) op.scalar(i);
 }
 
 __device__ __forceinline__ float scale_sum(float s, int use_div, float kf, float scale) {
@@ -241,13 +249,14 @@ __device__ __forceinline__ float scale_sum(float s, int use_div, float kf, float
     return use_div ? s / kf : s * scale;
 }
 
-__device__ __forceinline__ void scale_sum8(F8 &s, int use_div, float kf, float scale) {
+template <int U>
+__device__ __forceinline__ void scale_sumv(FV<U> &s, int use_div, float kf, float scale) {
     if (use_div) {  // uniform branch
 #pragma unroll
-        for (int e = 0; e < UNIT; ++e) s.v[e] = s.v[e] / kf;
+        for (int e = 0; e < U; ++e) s.v[e] = s.v[e] / kf;
     } else {
 #pragma unroll
-        for (int e = 0; e < UNIT; ++e) s.v[e] = s.v[e] * scale;
+        for (int e = 0; e < U; ++e) s.v[e] = s.v[e] * scale;
     }
 }
 
@@ -274,35 +283,38 @@ struct ConvertArgs {
     void *const *dst[PXCHG_MAX_K];
 };
 
-template <typename TI, typename TO, int NT>
+template <typename TI, typename TO, int NT, int U>
 struct ConvertOp {
     const TI *src;
     TO *dst;
     __device__ __forceinline__ void scalar(int i) const { store1(dst + i, load1(src + i)); }
     struct State {
-        F8 x;
+        FV<U> x;
     };
     template <bool SP>
-    __device__ __forceinline__ void load(State &st, int i0, int i1) const { st.x = load8<NT, SP>(src, i0, i1); }
+    __device__ __forceinline__ void load(State &st, int i) const { st.x = loadv<NT, U, SP>(src + i); }
     __device__ __forceinline__ void compute(State &) const {}
     template <bool SP>
-    __device__ __forceinline__ void store(const State &st, int i0, int i1) const { store8<NT, SP>(dst, i0, i1, st.x); }
+    __device__ __forceinline__ void store(const State &st, int i) const { storev<NT, U, SP>(dst + i, st.x); }
 };
 
 // Converts every tensor of every worker between binary32 and binary16.  The
 // grid covers k x n_chunks virtual chunks, worker-major.
 template <typename TI, typename TO, int NT>
-__global__ __launch_bounds__(BLOCK) void pxchg_convert_kernel(const PxChunk *__restrict__ chunks, int n_chunks,
-                                                              int64_t n_virtual, ConvertArgs args) {
+__global__ __launch_bounds__(64) void pxchg_convert_kernel(const PxChunk *__restrict__ chunks, int n_chunks,
+                                                           int64_t n_virtual, ConvertArgs args) {
+    constexpr int U = 8, NTH = 64;
+    constexpr bool SPLIT = true;  // float32 on one side
     for (int64_t vc = blockIdx.x; vc < n_virtual; vc += gridDim.x) {
         const int w = (int)(vc / n_chunks);
         const PxChunk ch = chunks[vc - (int64_t)w * n_chunks];
-        ConvertOp<TI, TO, NT> op;
+        ConvertOp<TI, TO, NT, U> op;
         op.src = table_ptr<const TI>(args.src[w], ch.tensor) + ch.start;
         op.dst = table_ptr<TO>(args.dst[w], ch.tensor) + ch.start;
         int head = head_of((uintptr_t)op.dst, sizeof(TO));
-        if (misalign_after((uintptr_t)op.src, sizeof(TI), head)) head = -1;
-        run_chunk<use_split<TI, TO>()>(op, ch.len, head);
+        if (misalign_after<U>((uintptr_t)op.src, sizeof(TI), head) | misalign_after<U>((uintptr_t)op.dst, sizeof(TO), head))
+            head = -1;
+        run_chunk<U, SPLIT, NTH>(op, ch.len, head, threadIdx.x);
     }
 }
 
@@ -317,7 +329,7 @@ struct ReduceArgs {
     float scale;
 };
 
-template <int K, typename TI, typename TO, int NT>
+template <int K, typename TI, typename TO, int NT, int U>
 struct ReduceOp {
     const TI *src[K];
     TO *dst;
@@ -330,28 +342,28 @@ struct ReduceOp {
         store1(dst + i, scale_sum(s, use_div, kf, scale));
     }
     struct State {
-        F8 c[K];
+        FV<U> c[K];
     };
     template <bool SP>
-    __device__ __forceinline__ void load(State &st, int i0, int i1) const {
+    __device__ __forceinline__ void load(State &st, int i) const {
 #pragma unroll
-        for (int w = 0; w < K; ++w) st.c[w] = load8<NT, SP>(src[w], i0, i1);
+        for (int w = 0; w < K; ++w) st.c[w] = loadv<NT, U, SP>(src[w] + i);
     }
     __device__ __forceinline__ void compute(State &st) const {
 #pragma unroll
         for (int w = 1; w < K; ++w)
 #pragma unroll
-            for (int e = 0; e < UNIT; ++e) st.c[0].v[e] = st.c[0].v[e] + st.c[w].v[e];  // worker order
-        scale_sum8(st.c[0], use_div, kf, scale);
+            for (int e = 0; e < U; ++e) st.c[0].v[e] = st.c[0].v[e] + st.c[w].v[e];  // worker order
+        scale_sumv(st.c[0], use_div, kf, scale);
     }
     template <bool SP>
-    __device__ __forceinline__ void store(const State &st, int i0, int i1) const {
-        store8<NT, SP>(dst, i0, i1, st.c[0]);
+    __device__ __forceinline__ void store(const State &st, int i) const {
+        storev<NT, U, SP>(dst + i, st.c[0]);
     }
 };
 
 // Any k up to PXCHG_MAX_K: the chunk's k source pointers sit in LDS.
-template <typename TI, typename TO, int NT>
+template <typename TI, typename TO, int NT, int U>
 struct ReduceOpAnyK {
     const TI *const *src;  // LDS
     TO *dst;
@@ -363,40 +375,42 @@ struct ReduceOpAnyK {
         store1(dst + i, scale_sum(s, use_div, kf, scale));
     }
     struct State {
-        F8 s;
+        FV<U> s;
     };
     // any k: the sum is formed while loading, four contributions at a time
     template <bool SP>
-    __device__ __forceinline__ void load(State &st, int i0, int i1) const {
-        F8 s = load8<NT, SP>(src[0], i0, i1);
+    __device__ __forceinline__ void load(State &st, int i) const {
+        FV<U> s = loadv<NT, U, SP>(src[0] + i);
         int w = 1;
         for (; w + 4 <= k; w += 4) {
-            F8 c[4];
+            FV<U> c[4];
 #pragma unroll
-            for (int q = 0; q < 4; ++q) c[q] = load8<NT, SP>(src[w + q], i0, i1);
+            for (int q = 0; q < 4; ++q) c[q] = loadv<NT, U, SP>(src[w + q] + i);
 #pragma unroll
             for (int q = 0; q < 4; ++q)
 #pragma unroll
-                for (int e = 0; e < UNIT; ++e) s.v[e] = s.v[e] + c[q].v[e];
+                for (int e = 0; e < U; ++e) s.v[e] = s.v[e] + c[q].v[e];
         }
         for (; w < k; ++w) {
-            const F8 c = load8<NT, SP>(src[w], i0, i1);
+            const FV<U> c = loadv<NT, U, SP>(src[w] + i);
 #pragma unroll
-            for (int e = 0; e < UNIT; ++e) s.v[e] = s.v[e] + c.v[e];
+            for (int e = 0; e < U; ++e) s.v[e] = s.v[e] + c.v[e];
         }
         st.s = s;
     }
-    __device__ __forceinline__ void compute(State &st) const { scale_sum8(st.s, use_div, kf, scale); }
+    __device__ __forceinline__ void compute(State &st) const { scale_sumv(st.s, use_div, kf, scale); }
     template <bool SP>
-    __device__ __forceinline__ void store(const State &st, int i0, int i1) const { store8<NT, SP>(dst, i0, i1, st.s); }
+    __device__ __forceinline__ void store(const State &st, int i) const { storev<NT, U, SP>(dst + i, st.s); }
 };
 
 template <int K, typename TI, typename TO, int NT>
-__global__ __launch_bounds__(BLOCK) void pxchg_reduce_avg_kernel(const PxChunk *__restrict__ chunks, int n_chunks,
-                                                                 ReduceArgs args) {
+__global__ __launch_bounds__(64) void pxchg_reduce_avg_kernel(const PxChunk *__restrict__ chunks, int n_chunks,
+                                                              ReduceArgs args) {
+    constexpr int U = 8, NTH = 64;
+    constexpr bool SPLIT = touches_f32<TI, TO>();
     for (int c = blockIdx.x; c < n_chunks; c += gridDim.x) {
         const PxChunk ch = chunks[c];
-        ReduceOp<K, TI, TO, NT> op;
+        ReduceOp<K, TI, TO, NT, U> op;
         op.dst = table_ptr<TO>(args.out, ch.tensor) + ch.start;
         op.use_div = args.use_div;
         op.kf = args.kf;
@@ -404,22 +418,24 @@ __global__ __launch_bounds__(BLOCK) void pxchg_reduce_avg_kernel(const PxChunk *
 #pragma unroll
         for (int w = 0; w < K; ++w) op.src[w] = table_ptr<const TI>(args.contrib[w], ch.tensor) + ch.start;
         int head = head_of((uintptr_t)op.dst, sizeof(TO));
-        unsigned bad = 0;
+        unsigned bad = misalign_after<U>((uintptr_t)op.dst, sizeof(TO), head);
 #pragma unroll
-        for (int w = 0; w < K; ++w) bad |= misalign_after((uintptr_t)op.src[w], sizeof(TI), head);
+        for (int w = 0; w < K; ++w) bad |= misalign_after<U>((uintptr_t)op.src[w], sizeof(TI), head);
         if (bad) head = -1;
-        run_chunk<use_split<TI, TO>()>(op, ch.len, head);
+        run_chunk<U, SPLIT, NTH>(op, ch.len, head, threadIdx.x);
     }
 }
 
 template <typename TI, typename TO, int NT>
-__global__ __launch_bounds__(BLOCK) void pxchg_reduce_avg_anyk_kernel(const PxChunk *__restrict__ chunks, int n_chunks,
-                                                                      ReduceArgs args) {
+__global__ __launch_bounds__(64) void pxchg_reduce_avg_anyk_kernel(const PxChunk *__restrict__ chunks, int n_chunks,
+                                                                   ReduceArgs args) {
+    constexpr int U = 8, NTH = 64;
+    constexpr bool SPLIT = touches_f32<TI, TO>();
     __shared__ const TI *sp[PXCHG_MAX_K];
     __shared__ int s_head;
     for (int c = blockIdx.x; c < n_chunks; c += gridDim.x) {
         const PxChunk ch = chunks[c];
-        ReduceOpAnyK<TI, TO, NT> op;
+        ReduceOpAnyK<TI, TO, NT, U> op;
         op.dst = table_ptr<TO>(args.out, ch.tensor) + ch.start;
         op.k = args.k;
         op.use_div = args.use_div;
@@ -427,16 +443,16 @@ __global__ __launch_bounds__(BLOCK) void pxchg_reduce_avg_anyk_kernel(const PxCh
         op.scale = args.scale;
         const int head0 = head_of((uintptr_t)op.dst, sizeof(TO));
         __syncthreads();  // previous chunk's readers are done with sp
-        if (threadIdx.x == 0) s_head = head0;
+        if (threadIdx.x == 0) s_head = misalign_after<U>((uintptr_t)op.dst, sizeof(TO), head0) ? -1 : head0;
         __syncthreads();
         if ((int)threadIdx.x < args.k) {
             const TI *p = table_ptr<const TI>(args.contrib[threadIdx.x], ch.tensor) + ch.start;
             sp[threadIdx.x] = p;
-            if (misalign_after((uintptr_t)p, sizeof(TI), head0)) s_head = -1;  // benign race: all write -1
+            if (misalign_after<U>((uintptr_t)p, sizeof(TI), head0)) s_head = -1;  // benign race: all write -1
         }
         __syncthreads();
         op.src = sp;
-        run_chunk<use_split<TI, TO>()>(op, ch.len, s_head);
+        run_chunk<U, SPLIT, NTH>(op, ch.len, s_head, threadIdx.x);
     }
 }
 
@@ -460,7 +476,7 @@ __device__ __forceinline__ void tensor_rates(const float *mult, int tensor, floa
     }
 }
 
-template <typename TG, int NT>
+template <typename TG, int NT, int U>
 struct UpdateOp {
     const TG *g;
     float *w, *v;
@@ -472,31 +488,33 @@ struct UpdateOp {
         store1(w + i, wi);
     }
     struct State {
-        F8 a, ww, vv;
+        FV<U> a, ww, vv;
     };
     template <bool SP>
-    __device__ __forceinline__ void load(State &st, int i0, int i1) const {
-        st.a = load8<NT, SP>(g, i0, i1);
-        st.ww = load8<NT, SP>(w, i0, i1);
-        st.vv = load8<NT, SP>(v, i0, i1);
+    __device__ __forceinline__ void load(State &st, int i) const {
+        st.a = loadv<NT, U, SP>(g + i);
+        st.ww = loadv<NT, U, SP>(w + i);
+        st.vv = loadv<NT, U, SP>(v + i);
     }
     __device__ __forceinline__ void compute(State &st) const {
 #pragma unroll
-        for (int e = 0; e < UNIT; ++e) momentum_step(st.a.v[e], st.ww.v[e], st.vv.v[e], lr, mu, wd);
+        for (int e = 0; e < U; ++e) momentum_step(st.a.v[e], st.ww.v[e], st.vv.v[e], lr, mu, wd);
     }
     template <bool SP>
-    __device__ __forceinline__ void store(const State &st, int i0, int i1) const {
-        store8<NT, SP>(v, i0, i1, st.vv);
-        store8<NT, SP>(w, i0, i1, st.ww);
+    __device__ __forceinline__ void store(const State &st, int i) const {
+        storev<NT, U, SP>(v + i, st.vv);
+        storev<NT, U, SP>(w + i, st.ww);
     }
 };
 
 template <typename TG, int NT>
-__global__ __launch_bounds__(BLOCK) void pxchg_sgd_momentum_kernel(const PxChunk *__restrict__ chunks, int n_chunks,
-                                                                   UpdateArgs args) {
+__global__ __launch_bounds__(128) void pxchg_sgd_momentum_kernel(const PxChunk *__restrict__ chunks, int n_chunks,
+                                                                 UpdateArgs args) {
+    constexpr int U = 4, NTH = 128;  // two wavefronts of 4-element lanes
+    constexpr bool SPLIT = false;
     for (int c = blockIdx.x; c < n_chunks; c += gridDim.x) {
         const PxChunk ch = chunks[c];
-        UpdateOp<TG, NT> op;
+        UpdateOp<TG, NT, U> op;
         op.g = table_ptr<const TG>(args.grad, ch.tensor) + ch.start;
         op.w = table_ptr<float>(args.param, ch.tensor) + ch.start;
         op.v = table_ptr<float>(args.vel, ch.tensor) + ch.start;
@@ -505,8 +523,10 @@ __global__ __launch_bounds__(BLOCK) void pxchg_sgd_momentum_kernel(const PxChunk
         op.wd = args.wd;
         tensor_rates(args.mult, ch.tensor, op.lr, op.wd);
         int head = head_of((uintptr_t)op.g, sizeof(TG));
-        if (misalign_after((uintptr_t)op.w, 4, head) | misalign_after((uintptr_t)op.v, 4, head)) head = -1;
-        run_chunk<use_split<float>()>(op, ch.len, head);
+        if (misalign_after<U>((uintptr_t)op.g, sizeof(TG), head) | misalign_after<U>((uintptr_t)op.w, 4, head) |
+            misalign_after<U>((uintptr_t)op.v, 4, head))
+            head = -1;
+        run_chunk<U, SPLIT, NTH>(op, ch.len, head, threadIdx.x);
     }
 }
 
@@ -523,7 +543,7 @@ struct FusedArgs {
     float lr, mu, wd;
 };
 
-template <int K, typename TI, bool WIRE16, int NT>
+template <int K, typename TI, bool WIRE16, int NT, int U>
 struct FusedOp {
     const TI *src[K];
     float *w, *v;
@@ -545,37 +565,39 @@ struct FusedOp {
         store1(w + i, wi);
     }
     struct State {
-        F8 c[K], ww, vv;
+        FV<U> c[K], ww, vv;
     };
     template <bool SP>
-    __device__ __forceinline__ void load(State &st, int i0, int i1) const {
+    __device__ __forceinline__ void load(State &st, int i) const {
 #pragma unroll
-        for (int q = 0; q < K; ++q) st.c[q] = load8<NT, SP>(src[q], i0, i1);
-        st.ww = load8<NT, SP>(w, i0, i1);
-        st.vv = load8<NT, SP>(v, i0, i1);
+        for (int q = 0; q < K; ++q) st.c[q] = loadv<NT, U, SP>(src[q] + i);
+        st.ww = loadv<NT, U, SP>(w + i);
+        st.vv = loadv<NT, U, SP>(v + i);
     }
     __device__ __forceinline__ void compute(State &st) const {
 #pragma unroll
         for (int q = 1; q < K; ++q)
 #pragma unroll
-            for (int e = 0; e < UNIT; ++e) st.c[0].v[e] = st.c[0].v[e] + st.c[q].v[e];  // worker order
-        scale_sum8(st.c[0], use_div, kf, scale);
+            for (int e = 0; e < U; ++e) st.c[0].v[e] = st.c[0].v[e] + st.c[q].v[e];  // worker order
+        scale_sumv(st.c[0], use_div, kf, scale);
 #pragma unroll
-        for (int e = 0; e < UNIT; ++e) momentum_step(wire(st.c[0].v[e]), st.ww.v[e], st.vv.v[e], lr, mu, wd);
+        for (int e = 0; e < U; ++e) momentum_step(wire(st.c[0].v[e]), st.ww.v[e], st.vv.v[e], lr, mu, wd);
     }
     template <bool SP>
-    __device__ __forceinline__ void store(const State &st, int i0, int i1) const {
-        store8<NT, SP>(v, i0, i1, st.vv);
-        store8<NT, SP>(w, i0, i1, st.ww);
+    __device__ __forceinline__ void store(const State &st, int i) const {
+        storev<NT, U, SP>(v + i, st.vv);
+        storev<NT, U, SP>(w + i, st.ww);
     }
 };
 
 template <int K, typename TI, bool WIRE16, int NT>
-__global__ __launch_bounds__(BLOCK) void pxchg_reduce_avg_sgd_momentum_kernel(const PxChunk *__restrict__ chunks,
-                                                                              int n_chunks, FusedArgs args) {
+__global__ __launch_bounds__(64) void pxchg_reduce_avg_sgd_momentum_kernel(const PxChunk *__restrict__ chunks,
+                                                                           int n_chunks, FusedArgs args) {
+    constexpr int U = 8, NTH = 64;
+    constexpr bool SPLIT = true;
     for (int c = blockIdx.x; c < n_chunks; c += gridDim.x) {
         const PxChunk ch = chunks[c];
-        FusedOp<K, TI, WIRE16, NT> op;
+        FusedOp<K, TI, WIRE16, NT, U> op;
         op.w = table_ptr<float>(args.param, ch.tensor) + ch.start;
         op.v = table_ptr<float>(args.vel, ch.tensor) + ch.start;
         op.use_div = args.use_div;
@@ -588,11 +610,11 @@ __global__ __launch_bounds__(BLOCK) void pxchg_reduce_avg_sgd_momentum_kernel(co
 #pragma unroll
         for (int q = 0; q < K; ++q) op.src[q] = table_ptr<const TI>(args.contrib[q], ch.tensor) + ch.start;
         int head = head_of((uintptr_t)op.src[0], sizeof(TI));
-        unsigned bad = misalign_after((uintptr_t)op.w, 4, head) | misalign_after((uintptr_t)op.v, 4, head);
+        unsigned bad = misalign_after<U>((uintptr_t)op.w, 4, head) | misalign_after<U>((uintptr_t)op.v, 4, head);
 #pragma unroll
-        for (int q = 1; q < K; ++q) bad |= misalign_after((uintptr_t)op.src[q], sizeof(TI), head);
+        for (int q = 0; q < K; ++q) bad |= misalign_after<U>((uintptr_t)op.src[q], sizeof(TI), head);
         if (bad) head = -1;
-        run_chunk<use_split<float>()>(op, ch.len, head);
+        run_chunk<U, SPLIT, NTH>(op, ch.len, head, threadIdx.x);
     }
 }
 
@@ -605,7 +627,7 @@ struct ElasticArgs {
     float alpha;
 };
 
-template <int K, int NT>
+template <int K, int NT, int U>
 struct ElasticOp {
     float *x[K];
     float *c;
@@ -621,44 +643,47 @@ struct ElasticOp {
         store1(c + i, ci);
     }
     struct State {
-        F8 xs[K], cc;
+        FV<U> xs[K], cc;
     };
     template <bool SP>
-    __device__ __forceinline__ void load(State &st, int i0, int i1) const {
+    __device__ __forceinline__ void load(State &st, int i) const {
 #pragma unroll
-        for (int q = 0; q < K; ++q) st.xs[q] = load8<NT, SP>(x[q], i0, i1);
-        st.cc = load8<NT, SP>(c, i0, i1);
+        for (int q = 0; q < K; ++q) st.xs[q] = loadv<NT, U, SP>(x[q] + i);
+        st.cc = loadv<NT, U, SP>(c + i);
     }
     __device__ __forceinline__ void compute(State &st) const {
 #pragma unroll
         for (int q = 0; q < K; ++q)  // arrival order: the center carries over
 #pragma unroll
-            for (int e = 0; e < UNIT; ++e) elastic_step(st.xs[q].v[e], st.cc.v[e], alpha);
+            for (int e = 0; e < U; ++e) elastic_step(st.xs[q].v[e], st.cc.v[e], alpha);
     }
     template <bool SP>
-    __device__ __forceinline__ void store(const State &st, int i0, int i1) const {
+    __device__ __forceinline__ void store(const State &st, int i) const {
 #pragma unroll
-        for (int q = 0; q < K; ++q) store8<NT, SP>(x[q], i0, i1, st.xs[q]);
-        store8<NT, SP>(c, i0, i1, st.cc);
+        for (int q = 0; q < K; ++q) storev<NT, U, SP>(x[q] + i, st.xs[q]);
+        storev<NT, U, SP>(c + i, st.cc);
     }
 };
 
 template <int K, int NT>
-__global__ __launch_bounds__(BLOCK) void pxchg_easgd_kernel(const PxChunk *__restrict__ chunks, int n_chunks,
-                                                            ElasticArgs args) {
+__global__ __launch_bounds__(K == 1 ? 128 : 64) void pxchg_easgd_kernel(const PxChunk *__restrict__ chunks,
+                                                                        int n_chunks, ElasticArgs args) {
+    // one meeting: two wavefronts of 4-element lanes; a fused round: one wavefront in the split layout
+    constexpr int U = K == 1 ? 4 : 8, NTH = K == 1 ? 128 : 64;
+    constexpr bool SPLIT = K != 1;
     for (int c = blockIdx.x; c < n_chunks; c += gridDim.x) {
         const PxChunk ch = chunks[c];
-        ElasticOp<K, NT> op;
+        ElasticOp<K, NT, U> op;
         op.c = table_ptr<float>(args.c, ch.tensor) + ch.start;
         op.alpha = args.alpha;
 #pragma unroll
         for (int q = 0; q < K; ++q) op.x[q] = table_ptr<float>(args.x[q], ch.tensor) + ch.start;
         int head = head_of((uintptr_t)op.c, 4);
-        unsigned bad = 0;
+        unsigned bad = misalign_after<U>((uintptr_t)op.c, 4, head);
 #pragma unroll
-        for (int q = 0; q < K; ++q) bad |= misalign_after((uintptr_t)op.x[q], 4, head);
+        for (int q = 0; q < K; ++q) bad |= misalign_after<U>((uintptr_t)op.x[q], 4, head);
         if (bad) head = -1;
-        run_chunk<use_split<float>()>(op, ch.len, head);
+        run_chunk<U, SPLIT, NTH>(op, ch.len, head, threadIdx.x);
     }
 }
 
@@ -679,22 +704,22 @@ __device__ __forceinline__ void stats_take(StatsAcc &a, float x) {
     }
 }
 
-template <typename T, int NT>
+template <typename T, int NT, int U>
 struct StatsOp {
     const T *src;
     StatsAcc *acc;  // this lane's running result
     struct State {
-        F8 x;
+        FV<U> x;
     };
     __device__ __forceinline__ void scalar(int i) const { stats_take(*acc, load1(src + i)); }
     template <bool SP>
-    __device__ __forceinline__ void load(State &st, int i0, int i1) const { st.x = load8<NT, SP>(src, i0, i1); }
+    __device__ __forceinline__ void load(State &st, int i) const { st.x = loadv<NT, U, SP>(src + i); }
     __device__ __forceinline__ void compute(State &st) const {
 #pragma unroll
-        for (int e = 0; e < UNIT; ++e) stats_take(*acc, st.x.v[e]);
+        for (int e = 0; e < U; ++e) stats_take(*acc, st.x.v[e]);
     }
     template <bool SP>
-    __device__ __forceinline__ void store(const State &, int, int) const {}
+    __device__ __forceinline__ void store(const State &, int) const {}
 };
 
 __global__ void pxchg_stats_clear_kernel(pxchg_stats *out) {
@@ -721,10 +746,11 @@ __global__ __launch_bounds__(STATS_BLOCK) void pxchg_stats_kernel(const PxChunk 
     StatsAcc acc = {0ull, 0.0f, 0.0};
     for (int c = blockIdx.x * WAVES + wave; c < n_chunks; c += gridDim.x * WAVES) {
         const PxChunk ch = chunks[c];
-        StatsOp<T, NT> op;
+        constexpr int U = std::is_same<T, float>::value ? 4 : 8;  // 16 bytes per lane
+        StatsOp<T, NT, U> op;
         op.src = table_ptr<const T>(set, ch.tensor) + ch.start;
         op.acc = &acc;
-        run_chunk<false, StatsOp<T, NT>, 64>(op, ch.len, head_of((uintptr_t)op.src, sizeof(T)), lane);
+        run_chunk<U, false, 64>(op, ch.len, head_of((uintptr_t)op.src, sizeof(T)), lane);
     }
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) {
@@ -836,7 +862,7 @@ int launch_convert(const pxchg_table *t, int k, const pxchg_bufset *const *src, 
     const int64_t n_virtual = t->n_chunks * k;
     const Launch l = launch_shape(t, n_virtual, sizeof(TO) < sizeof(TI) ? NT_LOADS_SC1NT_STORES : NT_LOADS_SC1_STORES);
 #define PX_CALL(N)                                                                                            \
-    hipLaunchKernelGGL((pxchg_convert_kernel<TI, TO, N>), l.grid, dim3(BLOCK), 0, stream, t->d_chunks,         \
+    hipLaunchKernelGGL((pxchg_convert_kernel<TI, TO, N>), l.grid, dim3(64), 0, stream, t->d_chunks, \
                        (int)t->n_chunks, n_virtual, a)
     PX_DISPATCH_NT(l.nt, PX_CALL)
 #undef PX_CALL
@@ -846,7 +872,7 @@ int launch_convert(const pxchg_table *t, int k, const pxchg_bufset *const *src, 
 template <int K, typename TI, typename TO>
 void launch_reduce_k(const pxchg_table *t, const Launch &l, const ReduceArgs &a, hipStream_t stream) {
 #define PX_CALL(N)                                                                                            \
-    hipLaunchKernelGGL((pxchg_reduce_avg_kernel<K, TI, TO, N>), l.grid, dim3(BLOCK), 0, stream, t->d_chunks,   \
+    hipLaunchKernelGGL((pxchg_reduce_avg_kernel<K, TI, TO, N>), l.grid, dim3(64), 0, stream, t->d_chunks, \
                        (int)t->n_chunks, a)
     PX_DISPATCH_NT(l.nt, PX_CALL)
 #undef PX_CALL
@@ -866,7 +892,7 @@ void launch_reduce(const pxchg_table *t, int k, const ReduceArgs &a, hipStream_t
         case 8: launch_reduce_k<8, TI, TO>(t, l, a, stream); break;
         default: {
 #define PX_CALL(N)                                                                                            \
-    hipLaunchKernelGGL((pxchg_reduce_avg_anyk_kernel<TI, TO, N>), l.grid, dim3(BLOCK), 0, stream, t->d_chunks, \
+    hipLaunchKernelGGL((pxchg_reduce_avg_anyk_kernel<TI, TO, N>), l.grid, dim3(64), 0, stream, t->d_chunks, \
                        (int)t->n_chunks, a)
             PX_DISPATCH_NT(l.nt, PX_CALL)
 #undef PX_CALL
@@ -877,10 +903,10 @@ void launch_reduce(const pxchg_table *t, int k, const ReduceArgs &a, hipStream_t
 template <int K, typename TI>
 void launch_fused_k(const pxchg_table *t, const Launch &l, const FusedArgs &a, bool wire16, hipStream_t stream) {
 #define PX_CALL16(N)                                                                                          \
-    hipLaunchKernelGGL((pxchg_reduce_avg_sgd_momentum_kernel<K, TI, true, N>), l.grid, dim3(BLOCK), 0, stream, \
+    hipLaunchKernelGGL((pxchg_reduce_avg_sgd_momentum_kernel<K, TI, true, N>), l.grid, dim3(64), 0, stream, \
                        t->d_chunks, (int)t->n_chunks, a)
 #define PX_CALL32(N)                                                                                           \
-    hipLaunchKernelGGL((pxchg_reduce_avg_sgd_momentum_kernel<K, TI, false, N>), l.grid, dim3(BLOCK), 0, stream, \
+    hipLaunchKernelGGL((pxchg_reduce_avg_sgd_momentum_kernel<K, TI, false, N>), l.grid, dim3(64), 0, stream, \
                        t->d_chunks, (int)t->n_chunks, a)
     if (wire16) {
         PX_DISPATCH_NT(l.nt, PX_CALL16)
@@ -911,7 +937,7 @@ int launch_fused(const pxchg_table *t, int k, const FusedArgs &a, bool wire16, h
 template <int K>
 void launch_elastic_k(const pxchg_table *t, const Launch &l, const ElasticArgs &a, hipStream_t stream) {
 #define PX_CALL(N) \
-    hipLaunchKernelGGL((pxchg_easgd_kernel<K, N>), l.grid, dim3(BLOCK), 0, stream, t->d_chunks, (int)t->n_chunks, a)
+    hipLaunchKernelGGL((pxchg_easgd_kernel<K, N>), l.grid, dim3(K == 1 ? 128 : 64), 0, stream, t->d_chunks, (int)t->n_chunks, a)
     PX_DISPATCH_NT(l.nt, PX_CALL)
 #undef PX_CALL
 }
@@ -992,10 +1018,10 @@ int pxchg_sgd_momentum(const pxchg_table *table, const pxchg_bufset *grad, pxchg
     const Launch l = launch_shape(table, table->n_chunks, grad->dtype == PXCHG_F16 ? NT_LOADS_SC1NT_STORES : NT_BOTH);
     hipStream_t s = (hipStream_t)stream;
 #define PX_CALL32(N)                                                                                      \
-    hipLaunchKernelGGL((pxchg_sgd_momentum_kernel<float, N>), l.grid, dim3(BLOCK), 0, s, table->d_chunks,  \
+    hipLaunchKernelGGL((pxchg_sgd_momentum_kernel<float, N>), l.grid, dim3(128), 0, s, table->d_chunks,  \
                        (int)table->n_chunks, a)
 #define PX_CALL16(N)                                                                                        \
-    hipLaunchKernelGGL((pxchg_sgd_momentum_kernel<_Float16, N>), l.grid, dim3(BLOCK), 0, s, table->d_chunks, \
+    hipLaunchKernelGGL((pxchg_sgd_momentum_kernel<_Float16, N>), l.grid, dim3(128), 0, s, table->d_chunks, \
                        (int)table->n_chunks, a)
     if (grad->dtype == PXCHG_F32) {
         PX_DISPATCH_NT(l.nt, PX_CALL32)
