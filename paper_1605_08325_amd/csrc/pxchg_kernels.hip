@@ -6,11 +6,10 @@
 // memory traffic only:
 //   * one launch per call: workgroups walk a device-resident list of chunks
 //     (tensor, start, length), so 16 tensors or 116 cost the same single launch;
-//   * each lane moves one 16-byte vector per operand and step (8 halves in a
-//     pure binary16 kernel; 4 floats, with binary16 operands as 8-byte pieces,
-//     in a kernel that touches float32), so every memory instruction of a
-//     wavefront covers one contiguous 1 KiB, and issues all loads of a step
-//     before the first use (k x 16 bytes in flight per lane);
+//   * lanes move 16-byte vectors (8-byte ones for binary16 next to float32
+//     operands) in one of three lane layouts, all of which make every memory
+//     instruction of a wavefront cover one contiguous stretch, and issue all
+//     loads of a step before the first use (k x 16 bytes in flight per lane);
 //   * no LDS staging and no cross-lane traffic in the exchange kernels: lanes are
 //     independent, which also makes the fixed worker order of the sum trivially
 //     bit-exact (only the diagnostics kernel reduces across lanes);
@@ -42,7 +41,8 @@ namespace {
 //     two 8-byte accesses);
 //   * the in-place float32 kernels with few operands (momentum update, one
 //     elastic meeting): two wavefronts, lane l of the 128 owns 4l..4l+3 (+6 % on
-//     the elastic meeting, +1..2 % on the update; 10..20 % slower for pack/unpack).
+//     the elastic meeting and +3.5 % on the update against the split layout in
+//     the benchmark step; 10..20 % slower for pack/unpack).
 // As many small workgroups as there are chunks keep the window of addresses in
 // flight narrow; larger tiles, several steps per lane and persistent grids were
 // all measured slower.
