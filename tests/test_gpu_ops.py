@@ -331,7 +331,7 @@ def test_easgd_round_equals_k_pairs_in_order(px, oracle_mod, k):
 
 # ------------------------------------------------------------------ launch shapes
 
-@pytest.mark.parametrize("chunk,bpc", [(2048, 0), (32768, 0), (8192, 2), (4096, 8)])
+@pytest.mark.parametrize("chunk,bpc", [(512, 1), (1024, 0), (2048, 0), (32768, 0), (8192, 2), (4096, 8)])
 def test_results_do_not_depend_on_launch_shape(px, oracle_mod, chunk, bpc):
     old = (px.get_option(px.OPT_CHUNK_ELEMS), px.get_option(px.OPT_BLOCKS_PER_CU))
     try:
@@ -349,6 +349,24 @@ def test_results_do_not_depend_on_launch_shape(px, oracle_mod, chunk, bpc):
         px.pack_fp16(table, [table.bufset(to_device(s)) for s in src], [table.bufset(d) for d in d_dst])
         for w in range(3):
             assert_bits_equal(to_host(d_dst[w]), oracle_mod.pack_fp16_tensors(src[w]), "pack launch shape")
+        # the in-place float32 kernels (two wavefronts of 4-element lanes) under the same launch shapes
+        avg = oracle_mod.reduce_avg_tensors(contrib, np.float16)
+        w_, v_ = _gauss(RAGGED, 952, role="param"), _gauss(RAGGED, 953, sigma=1e-3, role="velocity")
+        d_w, d_v = to_device(w_), to_device(v_)
+        px.sgd_momentum(table, table.bufset(d_out), table.bufset(d_w), table.bufset(d_v), 0.01, 0.9, 5e-4)
+        oracle_mod.sgd_momentum_tensors(avg, w_, v_, 0.01, 0.9, 5e-4)
+        assert_bits_equal(to_host(d_w), w_, "update launch shape")
+        assert_bits_equal(to_host(d_v), v_, "update launch shape")
+        x_, c_ = _gauss(RAGGED, 954, role="worker"), _gauss(RAGGED, 955, role="center")
+        d_x, d_c = to_device(x_), to_device(c_)
+        px.easgd(table, table.bufset(d_x), table.bufset(d_c), 0.0625)
+        px.easgd_round(table, [table.bufset(d_w), table.bufset(d_v)], table.bufset(d_c), 0.0625)
+        oracle_mod.easgd_tensors(x_, c_, 0.0625)
+        oracle_mod.easgd_tensors(w_, c_, 0.0625)
+        oracle_mod.easgd_tensors(v_, c_, 0.0625)
+        assert_bits_equal(to_host(d_x), x_, "elastic launch shape")
+        assert_bits_equal(to_host(d_c), c_, "elastic launch shape")
+        assert_bits_equal(to_host(d_w), w_, "elastic round launch shape")
     finally:
         px.set_option(px.OPT_CHUNK_ELEMS, old[0])
         px.set_option(px.OPT_BLOCKS_PER_CU, old[1])
