@@ -33,16 +33,17 @@ namespace {
 // A workgroup takes one 512-element chunk, and every memory instruction of a
 // wavefront covers one contiguous stretch (1 KiB for 16-byte lanes).  Three lane
 // layouts do that, chosen per kernel by measurement on MI355X:
-//   * pure binary16 kernels: one wavefront, lane l owns elements 8l..8l+7 (one
-//     16-byte access per operand);
+//   * the any-k binary16 reduce and the diagnostics: one wavefront, lane l owns
+//     elements 8l..8l+7 (one 16-byte access per operand);
 //   * kernels that mix binary16 and float32 operands, and the many-operand float32
 //     kernels: one wavefront in the SPLIT layout, lane l owns 4l..4l+3 and
 //     256+4l..256+4l+3 (float32 as two 16-byte accesses 1 KiB apart, binary16 as
 //     two 8-byte accesses);
 //   * the in-place float32 kernels with few operands (momentum update, one
-//     elastic meeting): two wavefronts, lane l of the 128 owns 4l..4l+3 (+6 % on
-//     the elastic meeting and +3.5 % on the update against the split layout in
-//     the benchmark step; 10..20 % slower for pack/unpack).
+//     elastic meeting) and the k = 1..8 binary16 reduce: two wavefronts, lane l of
+//     the 128 owns 4l..4l+3 (+6 % on the elastic meeting, +3.5 % on the update
+//     and +5 % on the reduce against the layouts above; 10..20 % slower for
+//     pack/unpack and a few percent slower for the fused kernels).
 // As many small workgroups as there are chunks keep the window of addresses in
 // flight narrow; larger tiles, several steps per lane and persistent grids were
 // all measured slower.
@@ -320,6 +321,14 @@ __global__ __launch_bounds__(64) void pxchg_convert_kernel(const PxChunk *__rest
 
 // ---------------------------------------------------------------- reduce + average
 
+// Lanes per 512-element chunk in the k = 1..8 reduce: binary16 in and out runs as two wavefronts of 4-element
+// (8-byte) lanes, measured 5 % faster than one wavefront of 8-element lanes; with float32 on either side the
+// split layout of one wavefront measured best.
+template <typename TI, typename TO>
+constexpr int reduce_lanes() {
+    return touches_f32<TI, TO>() ? 64 : 128;
+}
+
 struct ReduceArgs {
     const void *const *contrib[PXCHG_MAX_K];
     void *const *out;
@@ -404,10 +413,10 @@ struct ReduceOpAnyK {
 };
 
 template <int K, typename TI, typename TO, int NT>
-__global__ __launch_bounds__(64) void pxchg_reduce_avg_kernel(const PxChunk *__restrict__ chunks, int n_chunks,
-                                                              ReduceArgs args) {
-    constexpr int U = 8, NTH = 64;
+__global__ __launch_bounds__((reduce_lanes<TI, TO>())) void pxchg_reduce_avg_kernel(const PxChunk *__restrict__ chunks,
+                                                                                    int n_chunks, ReduceArgs args) {
     constexpr bool SPLIT = touches_f32<TI, TO>();
+    constexpr int NTH = reduce_lanes<TI, TO>(), U = SPLIT ? 8 : 4;
     for (int c = blockIdx.x; c < n_chunks; c += gridDim.x) {
         const PxChunk ch = chunks[c];
         ReduceOp<K, TI, TO, NT, U> op;
@@ -872,7 +881,7 @@ int launch_convert(const pxchg_table *t, int k, const pxchg_bufset *const *src, 
 template <int K, typename TI, typename TO>
 void launch_reduce_k(const pxchg_table *t, const Launch &l, const ReduceArgs &a, hipStream_t stream) {
 #define PX_CALL(N)                                                                                            \
-    hipLaunchKernelGGL((pxchg_reduce_avg_kernel<K, TI, TO, N>), l.grid, dim3(64), 0, stream, t->d_chunks, \
+    hipLaunchKernelGGL((pxchg_reduce_avg_kernel<K, TI, TO, N>), l.grid, dim3(reduce_lanes<TI, TO>()), 0, stream, t->d_chunks, \
                        (int)t->n_chunks, a)
     PX_DISPATCH_NT(l.nt, PX_CALL)
 #undef PX_CALL
