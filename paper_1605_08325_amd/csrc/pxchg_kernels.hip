@@ -33,14 +33,15 @@ namespace {
 // A workgroup takes one 512-element chunk, and every memory instruction of a
 // wavefront covers one contiguous stretch (1 KiB for 16-byte lanes).  Three lane
 // layouts do that, chosen per kernel by measurement on MI355X:
-//   * the any-k binary16 reduce and the diagnostics: one wavefront, lane l owns
-//     elements 8l..8l+7 (one 16-byte access per operand);
+//   * the binary16 reduce of one to three workers and the diagnostics of a
+//     binary16 buffer: lane l of a wavefront owns elements 8l..8l+7 (one 16-byte
+//     access per operand);
 //   * kernels that mix binary16 and float32 operands, and the many-operand float32
 //     kernels: one wavefront in the SPLIT layout, lane l owns 4l..4l+3 and
 //     256+4l..256+4l+3 (float32 as two 16-byte accesses 1 KiB apart, binary16 as
 //     two 8-byte accesses);
 //   * the in-place float32 kernels with few operands (momentum update, one
-//     elastic meeting) and the k = 1..8 binary16 reduce: two wavefronts, lane l of
+//     elastic meeting) and the binary16 reduce of four or more workers: two wavefronts, lane l of
 //     the 128 owns 4l..4l+3 (+6 % on the elastic meeting, +3.5 % on the update
 //     and +5 % on the reduce against the layouts above; 10..20 % slower for
 //     pack/unpack and a few percent slower for the fused kernels).
@@ -321,12 +322,14 @@ __global__ __launch_bounds__(64) void pxchg_convert_kernel(const PxChunk *__rest
 
 // ---------------------------------------------------------------- reduce + average
 
-// Lanes per 512-element chunk in the k = 1..8 reduce: binary16 in and out runs as two wavefronts of 4-element
-// (8-byte) lanes, measured 5 % faster than one wavefront of 8-element lanes; with float32 on either side the
-// split layout of one wavefront measured best.
-template <typename TI, typename TO>
+// Lanes per 512-element chunk in the reduce kernels.  Binary16 in and out with four or more workers runs as
+// two wavefronts of 4-element (8-byte) lanes, measured 5..8 % faster than one wavefront of 8-element lanes;
+// with fewer workers a wavefront would have too little in flight that way (k = 1: 30 % slower), so those keep
+// one wavefront of 8-element lanes; with float32 on either side the split layout of one wavefront measured
+// best.  K = 0 stands for the any-k kernel (more than 8 workers).
+template <int K, typename TI, typename TO>
 constexpr int reduce_lanes() {
-    return touches_f32<TI, TO>() ? 64 : 128;
+    return (touches_f32<TI, TO>() || (K >= 1 && K <= 3)) ? 64 : 128;
 }
 
 struct ReduceArgs {
@@ -413,10 +416,10 @@ struct ReduceOpAnyK {
 };
 
 template <int K, typename TI, typename TO, int NT>
-__global__ __launch_bounds__((reduce_lanes<TI, TO>())) void pxchg_reduce_avg_kernel(const PxChunk *__restrict__ chunks,
-                                                                                    int n_chunks, ReduceArgs args) {
+__global__ __launch_bounds__((reduce_lanes<K, TI, TO>())) void pxchg_reduce_avg_kernel(
+    const PxChunk *__restrict__ chunks, int n_chunks, ReduceArgs args) {
     constexpr bool SPLIT = touches_f32<TI, TO>();
-    constexpr int NTH = reduce_lanes<TI, TO>(), U = SPLIT ? 8 : 4;
+    constexpr int NTH = reduce_lanes<K, TI, TO>(), U = NTH == 64 ? 8 : 4;
     for (int c = blockIdx.x; c < n_chunks; c += gridDim.x) {
         const PxChunk ch = chunks[c];
         ReduceOp<K, TI, TO, NT, U> op;
@@ -436,10 +439,10 @@ __global__ __launch_bounds__((reduce_lanes<TI, TO>())) void pxchg_reduce_avg_ker
 }
 
 template <typename TI, typename TO, int NT>
-__global__ __launch_bounds__(64) void pxchg_reduce_avg_anyk_kernel(const PxChunk *__restrict__ chunks, int n_chunks,
-                                                                   ReduceArgs args) {
-    constexpr int U = 8, NTH = 64;
+__global__ __launch_bounds__((reduce_lanes<0, TI, TO>())) void pxchg_reduce_avg_anyk_kernel(
+    const PxChunk *__restrict__ chunks, int n_chunks, ReduceArgs args) {
     constexpr bool SPLIT = touches_f32<TI, TO>();
+    constexpr int NTH = reduce_lanes<0, TI, TO>(), U = NTH == 64 ? 8 : 4;
     __shared__ const TI *sp[PXCHG_MAX_K];
     __shared__ int s_head;
     for (int c = blockIdx.x; c < n_chunks; c += gridDim.x) {
@@ -881,7 +884,7 @@ int launch_convert(const pxchg_table *t, int k, const pxchg_bufset *const *src, 
 template <int K, typename TI, typename TO>
 void launch_reduce_k(const pxchg_table *t, const Launch &l, const ReduceArgs &a, hipStream_t stream) {
 #define PX_CALL(N)                                                                                            \
-    hipLaunchKernelGGL((pxchg_reduce_avg_kernel<K, TI, TO, N>), l.grid, dim3(reduce_lanes<TI, TO>()), 0, stream, t->d_chunks, \
+    hipLaunchKernelGGL((pxchg_reduce_avg_kernel<K, TI, TO, N>), l.grid, dim3(reduce_lanes<K, TI, TO>()), 0, stream, t->d_chunks, \
                        (int)t->n_chunks, a)
     PX_DISPATCH_NT(l.nt, PX_CALL)
 #undef PX_CALL
@@ -901,7 +904,7 @@ void launch_reduce(const pxchg_table *t, int k, const ReduceArgs &a, hipStream_t
         case 8: launch_reduce_k<8, TI, TO>(t, l, a, stream); break;
         default: {
 #define PX_CALL(N)                                                                                            \
-    hipLaunchKernelGGL((pxchg_reduce_avg_anyk_kernel<TI, TO, N>), l.grid, dim3(64), 0, stream, t->d_chunks, \
+    hipLaunchKernelGGL((pxchg_reduce_avg_anyk_kernel<TI, TO, N>), l.grid, dim3(reduce_lanes<0, TI, TO>()), 0, stream, t->d_chunks, \
                        (int)t->n_chunks, a)
             PX_DISPATCH_NT(l.nt, PX_CALL)
 #undef PX_CALL
