@@ -134,8 +134,8 @@ def cpu_baseline(counts, grads, w, v, xs, c, order, cfg, alpha, threads):
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--sets", type=int, default=2, help="rotating sets of fresh gradients resident in HBM")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--config", type=int, default=3, choices=[1, 2, 3, 4, 5],
