@@ -57,6 +57,7 @@ static_assert(PXCHG_MAX_K <= 64, "the any-k kernel uses one lane per worker to f
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
 
 // Data pointers come out of pointer tables in memory, so the compiler cannot
 // know they are global addresses; say so, to get global (not flat) memory
@@ -94,21 +95,25 @@ __device__ __forceinline__ V ldv(const PX_GLOBAL V *p) {
 // see through inline assembly.
 template <typename V>
 __device__ __forceinline__ void store_sc1_nt(PX_GLOBAL V *p, V x) {
-    static_assert(sizeof(V) == 16 || sizeof(V) == 8, "dwordx4 or dwordx2");
+    static_assert(sizeof(V) == 16 || sizeof(V) == 8 || sizeof(V) == 4, "dwordx4, dwordx2 or dword");
     if constexpr (sizeof(V) == 16)
         asm volatile("global_store_dwordx4 %0, %1, off sc1 nt\n\ts_nop 0" ::"v"(p), "v"(x) : "memory");
-    else
+    else if constexpr (sizeof(V) == 8)
         asm volatile("global_store_dwordx2 %0, %1, off sc1 nt\n\ts_nop 0" ::"v"(p), "v"(x) : "memory");
+    else
+        asm volatile("global_store_dword %0, %1, off sc1 nt" ::"v"(p), "v"(x) : "memory");
 }
 // Agent-scope store without the streaming hint ("sc1"): measured 3 % faster than a plain store on the reduce
 // kernel, whose writes are one byte in nine of its traffic.
 template <typename V>
 __device__ __forceinline__ void store_sc1(PX_GLOBAL V *p, V x) {
-    static_assert(sizeof(V) == 16 || sizeof(V) == 8, "dwordx4 or dwordx2");
+    static_assert(sizeof(V) == 16 || sizeof(V) == 8 || sizeof(V) == 4, "dwordx4, dwordx2 or dword");
     if constexpr (sizeof(V) == 16)
         asm volatile("global_store_dwordx4 %0, %1, off sc1\n\ts_nop 0" ::"v"(p), "v"(x) : "memory");
-    else
+    else if constexpr (sizeof(V) == 8)
         asm volatile("global_store_dwordx2 %0, %1, off sc1\n\ts_nop 0" ::"v"(p), "v"(x) : "memory");
+    else
+        asm volatile("global_store_dword %0, %1, off sc1" ::"v"(p), "v"(x) : "memory");
 }
 
 // NT: 0 plain, bit 0 non-temporal loads, bit 1 non-temporal stores, 4 = non-temporal loads with "sc1 nt" stores,
@@ -130,9 +135,17 @@ __device__ __forceinline__ void stv(PX_GLOBAL V *p, V x) {
 constexpr int SPLIT_GAP = 256;
 template <int NT, int U, bool SPLIT>
 __device__ __forceinline__ FV<U> loadv(const float *p) {
-    static_assert(U == 4 || U == 8, "one or two 16-byte vectors");
+    static_assert(U == 1 || U == 2 || U == 4 || U == 8, "4 or 8 bytes, or one or two 16-byte vectors");
     static_assert(!SPLIT || U == 8, "the split layout is two groups of four");
     FV<U> r;
+    if constexpr (U == 1) {
+        r.v[0] = ldv<NT>((const PX_GLOBAL float *)p);
+        return r;
+    } else if constexpr (U == 2) {
+        const f32x2 a = ldv<NT>((const PX_GLOBAL f32x2 *)p);
+        r.v[0] = a.x; r.v[1] = a.y;
+        return r;
+    }
     const f32x4 a = ldv<NT>((const PX_GLOBAL f32x4 *)p);
     r.v[0] = a.x; r.v[1] = a.y; r.v[2] = a.z; r.v[3] = a.w;
     if constexpr (U == 8) {
@@ -164,6 +177,15 @@ __device__ __forceinline__ FV<U> loadv(const _Float16 *p) {
 }
 template <int NT, int U, bool SPLIT>
 __device__ __forceinline__ void storev(float *p, const FV<U> &x) {
+    if constexpr (U == 1) {
+        stv<NT>((PX_GLOBAL float *)p, x.v[0]);
+        return;
+    } else if constexpr (U == 2) {
+        f32x2 a2;
+        a2.x = x.v[0]; a2.y = x.v[1];
+        stv<NT>((PX_GLOBAL f32x2 *)p, a2);
+        return;
+    }
     f32x4 a;
     a.x = x.v[0]; a.y = x.v[1]; a.z = x.v[2]; a.w = x.v[3];
     stv<NT>((PX_GLOBAL f32x4 *)p, a);
@@ -632,6 +654,14 @@ __global__ __launch_bounds__(64) void pxchg_reduce_avg_sgd_momentum_kernel(const
 
 // ---------------------------------------------------------------- elastic averaging
 
+// Lanes per 512-element chunk in the elastic kernels: a wavefront should load 2..4 KiB in all, so the more
+// workers a fused round has, the narrower its lanes (a round of 8 with 4-byte lanes measured 7 % faster than
+// with the split layout of one wavefront).
+template <int K>
+constexpr int elastic_lanes() {
+    return K <= 2 ? 128 : K <= 4 ? 256 : 512;
+}
+
 struct ElasticArgs {
     void *const *x[PXCHG_MAX_K];
     void *const *c;
@@ -678,11 +708,10 @@ struct ElasticOp {
 };
 
 template <int K, int NT>
-__global__ __launch_bounds__(K == 1 ? 128 : 64) void pxchg_easgd_kernel(const PxChunk *__restrict__ chunks,
+__global__ __launch_bounds__((elastic_lanes<K>())) void pxchg_easgd_kernel(const PxChunk *__restrict__ chunks,
                                                                         int n_chunks, ElasticArgs args) {
-    // one meeting: two wavefronts of 4-element lanes; a fused round: one wavefront in the split layout
-    constexpr int U = K == 1 ? 4 : 8, NTH = K == 1 ? 128 : 64;
-    constexpr bool SPLIT = K != 1;
+    constexpr int NTH = elastic_lanes<K>(), U = 512 / NTH;
+    constexpr bool SPLIT = false;
     for (int c = blockIdx.x; c < n_chunks; c += gridDim.x) {
         const PxChunk ch = chunks[c];
         ElasticOp<K, NT, U> op;
@@ -949,7 +978,7 @@ int launch_fused(const pxchg_table *t, int k, const FusedArgs &a, bool wire16, h
 template <int K>
 void launch_elastic_k(const pxchg_table *t, const Launch &l, const ElasticArgs &a, hipStream_t stream) {
 #define PX_CALL(N) \
-    hipLaunchKernelGGL((pxchg_easgd_kernel<K, N>), l.grid, dim3(K == 1 ? 128 : 64), 0, stream, t->d_chunks, (int)t->n_chunks, a)
+    hipLaunchKernelGGL((pxchg_easgd_kernel<K, N>), l.grid, dim3(elastic_lanes<K>()), 0, stream, t->d_chunks, (int)t->n_chunks, a)
     PX_DISPATCH_NT(l.nt, PX_CALL)
 #undef PX_CALL
 }
