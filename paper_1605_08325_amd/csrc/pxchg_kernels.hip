@@ -32,19 +32,23 @@ namespace {
 
 // A workgroup takes one 512-element chunk, and every memory instruction of a
 // wavefront covers one contiguous stretch (1 KiB for 16-byte lanes).  Three lane
-// layouts do that, chosen per kernel by measurement on MI355X:
+// layouts do that, chosen per kernel by measurement on MI355X (the rule of thumb
+// behind the choices: a wavefront should have 2..4 KiB of loads in flight, and
+// binary16 accesses of at least 8 bytes where binary16 is all the traffic):
 //   * the binary16 reduce of one to three workers and the diagnostics of a
 //     binary16 buffer: lane l of a wavefront owns elements 8l..8l+7 (one 16-byte
 //     access per operand);
-//   * kernels that mix binary16 and float32 operands, and the many-operand float32
-//     kernels: one wavefront in the SPLIT layout, lane l owns 4l..4l+3 and
-//     256+4l..256+4l+3 (float32 as two 16-byte accesses 1 KiB apart, binary16 as
-//     two 8-byte accesses);
-//   * the in-place float32 kernels with few operands (momentum update, one
-//     elastic meeting) and the binary16 reduce of four or more workers: two wavefronts, lane l of
-//     the 128 owns 4l..4l+3 (+6 % on the elastic meeting, +3.5 % on the update
-//     and +5 % on the reduce against the layouts above; 10..20 % slower for
-//     pack/unpack and a few percent slower for the fused kernels).
+//   * pack, unpack, the reduces with float32 on one side and the float32 reduce
+//     of up to three workers: one wavefront in the SPLIT layout, lane l owns
+//     4l..4l+3 and 256+4l..256+4l+3 (float32 as two 16-byte accesses 1 KiB
+//     apart, binary16 as two 8-byte accesses);
+//   * everything else: 128, 256 or 512 lanes per chunk, lane l owning 4, 2 or 1
+//     consecutive elements.  Four elements for the in-place float32 kernels with
+//     few operands (momentum update, one elastic meeting: +3.5 % and +6 % against
+//     the split layout) and the binary16 reduce of four or more workers (+5 %);
+//     narrower lanes the more operands a step has (fused reduce+update, fused
+//     elastic round, float32 reduce of four or more workers: see reduce_lanes,
+//     fused_lanes and elastic_lanes below).
 // As many small workgroups as there are chunks keep the window of addresses in
 // flight narrow; larger tiles, several steps per lane and persistent grids were
 // all measured slower.
@@ -57,6 +61,7 @@ static_assert(PXCHG_MAX_K <= 64, "the any-k kernel uses one lane per worker to f
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 
 // Data pointers come out of pointer tables in memory, so the compiler cannot
@@ -156,10 +161,13 @@ __device__ __forceinline__ FV<U> loadv(const float *p) {
 }
 template <int NT, int U, bool SPLIT>
 __device__ __forceinline__ FV<U> loadv(const _Float16 *p) {
-    static_assert(U == 4 || U == 8, "8 or 16 bytes");
+    static_assert(U == 2 || U == 4 || U == 8, "4, 8 or 16 bytes");
     static_assert(!SPLIT || U == 8, "the split layout is two groups of four");
     FV<U> r;
-    if constexpr (U == 4 || SPLIT) {
+    if constexpr (U == 2) {
+        const f16x2 a = ldv<NT>((const PX_GLOBAL f16x2 *)p);
+        r.v[0] = (float)a[0]; r.v[1] = (float)a[1];
+    } else if constexpr (U == 4 || SPLIT) {
         const f16x4 a = ldv<NT>((const PX_GLOBAL f16x4 *)p);
 #pragma unroll
         for (int i = 0; i < 4; ++i) r.v[i] = (float)a[i];  // exact widening
@@ -347,10 +355,12 @@ __global__ __launch_bounds__(64) void pxchg_convert_kernel(const PxChunk *__rest
 // Lanes per 512-element chunk in the reduce kernels.  Binary16 in and out with four or more workers runs as
 // two wavefronts of 4-element (8-byte) lanes, measured 5..8 % faster than one wavefront of 8-element lanes;
 // with fewer workers a wavefront would have too little in flight that way (k = 1: 30 % slower), so those keep
-// one wavefront of 8-element lanes; with float32 on either side the split layout of one wavefront measured
-// best.  K = 0 stands for the any-k kernel (more than 8 workers).
+// one wavefront of 8-element lanes.  Float32 in and out with four or more workers: 2-element (8-byte) lanes,
+// +1..3 % over the split layout of one wavefront, which every other combination with float32 on either side
+// keeps.  K = 0 stands for the any-k kernel (more than 8 workers).
 template <int K, typename TI, typename TO>
 constexpr int reduce_lanes() {
+    if (std::is_same<TI, float>::value && std::is_same<TO, float>::value && K >= 4) return 256;
     return (touches_f32<TI, TO>() || (K >= 1 && K <= 3)) ? 64 : 128;
 }
 
@@ -440,8 +450,8 @@ struct ReduceOpAnyK {
 template <int K, typename TI, typename TO, int NT>
 __global__ __launch_bounds__((reduce_lanes<K, TI, TO>())) void pxchg_reduce_avg_kernel(
     const PxChunk *__restrict__ chunks, int n_chunks, ReduceArgs args) {
-    constexpr bool SPLIT = touches_f32<TI, TO>();
-    constexpr int NTH = reduce_lanes<K, TI, TO>(), U = NTH == 64 ? 8 : 4;
+    constexpr int NTH = reduce_lanes<K, TI, TO>(), U = 512 / NTH;
+    constexpr bool SPLIT = touches_f32<TI, TO>() && U == 8;
     for (int c = blockIdx.x; c < n_chunks; c += gridDim.x) {
         const PxChunk ch = chunks[c];
         ReduceOp<K, TI, TO, NT, U> op;
@@ -624,11 +634,21 @@ struct FusedOp {
     }
 };
 
+// Lanes per 512-element chunk in the fused kernel.  Float32 contributions: 2-element (8-byte) lanes measured
+// 3..6 % faster than the split layout of one wavefront for every k.  Binary16 contributions: the same 256
+// lanes (8-byte accesses to w and v, 4-byte ones to the contributions) from k = 3 on (+1..5 %); k = 2 keeps
+// the split layout and k = 1 runs as two wavefronts of 4-element lanes (+4 %).
+template <int K, typename TI>
+constexpr int fused_lanes() {
+    if (std::is_same<TI, float>::value) return 256;
+    return K == 1 ? 128 : K == 2 ? 64 : 256;
+}
+
 template <int K, typename TI, bool WIRE16, int NT>
-__global__ __launch_bounds__(64) void pxchg_reduce_avg_sgd_momentum_kernel(const PxChunk *__restrict__ chunks,
-                                                                           int n_chunks, FusedArgs args) {
-    constexpr int U = 8, NTH = 64;
-    constexpr bool SPLIT = true;
+__global__ __launch_bounds__((fused_lanes<K, TI>())) void pxchg_reduce_avg_sgd_momentum_kernel(
+    const PxChunk *__restrict__ chunks, int n_chunks, FusedArgs args) {
+    constexpr int NTH = fused_lanes<K, TI>(), U = 512 / NTH;
+    constexpr bool SPLIT = U == 8;
     for (int c = blockIdx.x; c < n_chunks; c += gridDim.x) {
         const PxChunk ch = chunks[c];
         FusedOp<K, TI, WIRE16, NT, U> op;
@@ -944,10 +964,10 @@ void launch_reduce(const pxchg_table *t, int k, const ReduceArgs &a, hipStream_t
 template <int K, typename TI>
 void launch_fused_k(const pxchg_table *t, const Launch &l, const FusedArgs &a, bool wire16, hipStream_t stream) {
 #define PX_CALL16(N)                                                                                          \
-    hipLaunchKernelGGL((pxchg_reduce_avg_sgd_momentum_kernel<K, TI, true, N>), l.grid, dim3(64), 0, stream, \
+    hipLaunchKernelGGL((pxchg_reduce_avg_sgd_momentum_kernel<K, TI, true, N>), l.grid, dim3(fused_lanes<K, TI>()), 0, stream, \
                        t->d_chunks, (int)t->n_chunks, a)
 #define PX_CALL32(N)                                                                                           \
-    hipLaunchKernelGGL((pxchg_reduce_avg_sgd_momentum_kernel<K, TI, false, N>), l.grid, dim3(64), 0, stream, \
+    hipLaunchKernelGGL((pxchg_reduce_avg_sgd_momentum_kernel<K, TI, false, N>), l.grid, dim3(fused_lanes<K, TI>()), 0, stream, \
                        t->d_chunks, (int)t->n_chunks, a)
     if (wire16) {
         PX_DISPATCH_NT(l.nt, PX_CALL16)
