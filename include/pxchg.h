@@ -68,7 +68,10 @@ enum pxchg_option {
     PXCHG_OPT_NONTEMPORAL = 3    /* -1 (default): each kernel's own measured-best policy; 0..3: bit 0
                                     puts the non-temporal hint on vector loads, bit 1 on vector stores;
                                     4: non-temporal loads, and stores that are streaming with agent scope;
-                                    5: non-temporal loads, and agent-scope stores without the streaming hint */
+                                    5: non-temporal loads, and agent-scope stores without the streaming hint.
+                                    Results never depend on it.  One operand is exempt: a binary16 gradient
+                                    of pxchg_sgd_momentum is always read with plain loads (it is usually the
+                                    mean just written by pxchg_reduce_avg and may still be cached) */
 };
 
 typedef struct pxchg_table pxchg_table;
