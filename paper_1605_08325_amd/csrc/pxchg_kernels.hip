@@ -755,18 +755,21 @@ __global__ __launch_bounds__((elastic_lanes<K>())) void pxchg_easgd_kernel(const
 // ---------------------------------------------------------------- diagnostics
 
 struct StatsAcc {
-    unsigned long long bad;
+    unsigned bad;  // one lane's share of the count: far below 2^32 for any set that fits the device
     float mx;
     double ss;
 };
 
+// Branch-free: a non-finite element counts and then takes part as +0, which changes neither the maximum of
+// magnitudes nor the sum.  The square of a binary32 value is exact in binary64, so the fused multiply-add
+// gives the same bits as a product and a sum rounded one after the other.
 __device__ __forceinline__ void stats_take(StatsAcc &a, float x) {
-    if ((__float_as_uint(x) & 0x7f800000u) == 0x7f800000u) {  // infinity or NaN
-        a.bad += 1;
-    } else {
-        a.mx = fmaxf(a.mx, fabsf(x));
-        a.ss = a.ss + (double)x * (double)x;
-    }
+    const bool nonfinite = (__float_as_uint(x) & 0x7f800000u) == 0x7f800000u;  // infinity or NaN
+    const float xf = nonfinite ? 0.0f : x;
+    a.bad += nonfinite ? 1u : 0u;
+    a.mx = fmaxf(a.mx, fabsf(xf));
+    const double d = (double)xf;
+    a.ss = __builtin_fma(d, d, a.ss);
 }
 
 template <typename T, int NT, int U>
@@ -808,7 +811,7 @@ __global__ __launch_bounds__(STATS_BLOCK) void pxchg_stats_kernel(const PxChunk 
     __shared__ double s_ss[WAVES];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // the same in all 64 lanes: keep it scalar
-    StatsAcc acc = {0ull, 0.0f, 0.0};
+    StatsAcc acc = {0u, 0.0f, 0.0};
     for (int c = blockIdx.x * WAVES + wave; c < n_chunks; c += gridDim.x * WAVES) {
         const PxChunk ch = chunks[c];
         constexpr int U = std::is_same<T, float>::value ? 4 : 8;  // 16 bytes per lane
@@ -817,25 +820,26 @@ __global__ __launch_bounds__(STATS_BLOCK) void pxchg_stats_kernel(const PxChunk 
         op.acc = &acc;
         run_chunk<U, false, 64>(op, ch.len, head_of((uintptr_t)op.src, sizeof(T)), lane);
     }
+    unsigned long long bad = acc.bad;
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) {
-        acc.bad += __shfl_xor(acc.bad, off);
+        bad += __shfl_xor(bad, off);
         acc.mx = fmaxf(acc.mx, __shfl_xor(acc.mx, off));
         acc.ss += __shfl_xor(acc.ss, off);
     }
     if (lane == 0) {
-        s_bad[wave] = acc.bad;
+        s_bad[wave] = bad;
         s_mx[wave] = acc.mx;
         s_ss[wave] = acc.ss;
     }
     __syncthreads();
     if (threadIdx.x == 0) {
         for (int w = 1; w < WAVES; ++w) {
-            acc.bad += s_bad[w];
+            bad += s_bad[w];
             acc.mx = fmaxf(acc.mx, s_mx[w]);
             acc.ss += s_ss[w];
         }
-        if (acc.bad) atomicAdd((unsigned long long *)&out->nonfinite, acc.bad);
+        if (bad) atomicAdd((unsigned long long *)&out->nonfinite, bad);
         // magnitudes are non-negative, so their bit patterns order like the values
         atomicMax((unsigned *)&out->max_abs, __float_as_uint(acc.mx));
         atomicAdd(&out->sum_sq, acc.ss);
