@@ -364,7 +364,8 @@ def main() -> int:
                            f"sgd_momentum ({cfg.transfer} grad) -> {k} easgd meetings",
                    "gradient_sets": len(grad_sets), "chunk_elems": px.get_option(px.OPT_CHUNK_ELEMS),
                    "blocks_per_cu": px.get_option(px.OPT_BLOCKS_PER_CU),
-                   "nontemporal": px.get_option(px.OPT_NONTEMPORAL)},
+                   "nontemporal": px.get_option(px.OPT_NONTEMPORAL),
+                   "seed": cfg.seed, "numpy": np.__version__},
         "value_frac_of_hbm_peak": round(value / HBM_PEAK_GBPS, 4),
         "reduce_update_ms": round(ru_ms, 5),
         "step_GBps": round(step_bytes / (ms_per_step * 1e-3) / 1e9, 1),
