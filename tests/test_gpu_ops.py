@@ -301,6 +301,42 @@ def test_easgd_pair(px, oracle_mod, offset):
     assert_bits_equal(to_host(d_c), c, "c")
 
 
+@pytest.mark.parametrize("k", [1, 2, 3, 4, 8])
+@pytest.mark.parametrize("in_dt", [np.float32, np.float16])
+@pytest.mark.parametrize("offsets", [(1, 1, 1), (2, 2, 2), (2, 1, 1), (0, 1, 0)])
+def test_fused_reduce_update_misaligned(px, oracle_mod, k, in_dt, offsets):
+    """Every lane width of the fused kernel (by k and contribution type) with operands that are off 16-byte
+    alignment by the same number of elements (head, vector body, tail), by the same number of bytes, or
+    without a common alignment (element-wise path)."""
+    oc, ow, ov = offsets
+    table = px.Table(RAGGED)
+    contrib = [[a.astype(in_dt) for a in _gauss(RAGGED, 820 + k, w)] for w in range(k)]
+    w_o = _gauss(RAGGED, 821, role="param")
+    v_o = _gauss(RAGGED, 822, sigma=1e-3, role="velocity")
+    d_w, d_v = to_device(w_o, ow), to_device(v_o, ov)
+    sets = [table.bufset(to_device(c, oc)) for c in contrib]
+    px.reduce_avg_sgd_momentum(table, sets, table.bufset(d_w), table.bufset(d_v), 0.01, 0.9, 5e-4, px.AVG, px.F16)
+    avg = oracle_mod.reduce_avg_tensors(contrib, np.float16)
+    oracle_mod.sgd_momentum_tensors(avg, w_o, v_o, 0.01, 0.9, 5e-4)
+    assert_bits_equal(to_host(d_w), w_o, "w")
+    assert_bits_equal(to_host(d_v), v_o, "v")
+
+
+@pytest.mark.parametrize("k,offset", [(2, 1), (3, 1), (4, 3), (8, 1), (8, 2)])
+def test_easgd_round_misaligned(px, oracle_mod, k, offset):
+    table = px.Table(RAGGED)
+    xs = [_gauss(RAGGED, 930, w, role="worker") for w in range(k)]
+    c = _gauss(RAGGED, 931, role="center")
+    d_xs = [to_device(x, offset) for x in xs]
+    d_c = to_device(c, offset if k != 3 else 0)      # k = 3: no common alignment
+    px.easgd_round(table, [table.bufset(x) for x in d_xs], table.bufset(d_c), 0.0625)
+    for i in range(k):
+        oracle_mod.easgd_tensors(xs[i], c, np.float32(0.0625))
+    for i in range(k):
+        assert_bits_equal(to_host(d_xs[i]), xs[i], f"x[{i}]")
+    assert_bits_equal(to_host(d_c), c, "center")
+
+
 @pytest.mark.parametrize("k", [1, 2, 5, 8, 11])
 def test_easgd_round_equals_k_pairs_in_order(px, oracle_mod, k):
     counts = RAGGED
