@@ -211,22 +211,26 @@ def main() -> int:
     torch.cuda.synchronize()
     t_gen = time.perf_counter() - t_gen
 
+    # the launch stream, looked up once (the binding's default looks it up on every call: 3 us of host time,
+    # which shows in the configurations whose kernels take 10..25 us)
+    stream = torch.cuda.current_stream().cuda_stream
+
     def step(i, ev=None):
         s = i % len(grad_sets)
         if ev:
             ev[0].record()
         if half:
-            px.pack_fp16(table, grad_sets[s], pack_sets[s])
+            px.pack_fp16(table, grad_sets[s], pack_sets[s], stream=stream)
         if ev:
             ev[1].record()
-        px.reduce_avg(table, pack_sets[s], s_avg, px.AVG)
+        px.reduce_avg(table, pack_sets[s], s_avg, px.AVG, stream=stream)
         if ev:
             ev[2].record()
-        px.sgd_momentum(table, s_avg, s_w, s_v, cfg.lr, cfg.mu, cfg.wd)
+        px.sgd_momentum(table, s_avg, s_w, s_v, cfg.lr, cfg.mu, cfg.wd, stream=stream)
         if ev:
             ev[3].record()
         for j in orders[i]:
-            px.easgd(table, s_xs[int(j)], s_c, alpha)
+            px.easgd(table, s_xs[int(j)], s_c, alpha, stream=stream)
         if ev:
             ev[4].record()
 
@@ -280,11 +284,12 @@ def main() -> int:
     fused = {}
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
     for i in range(3):
-        px.reduce_avg_sgd_momentum(table, pack_sets[0], s_w, s_v, cfg.lr, cfg.mu, cfg.wd, px.AVG, wire_px)
+        px.reduce_avg_sgd_momentum(table, pack_sets[0], s_w, s_v, cfg.lr, cfg.mu, cfg.wd, px.AVG, wire_px,
+                                   stream=stream)
     ev[0].record()
     for i in range(args.steps):
         px.reduce_avg_sgd_momentum(table, pack_sets[i % len(pack_sets)], s_w, s_v, cfg.lr, cfg.mu, cfg.wd,
-                                   px.AVG, wire_px)
+                                   px.AVG, wire_px, stream=stream)
     ev[1].record()
     torch.cuda.synchronize()
     ms = ev[0].elapsed_time(ev[1]) / args.steps
@@ -292,10 +297,10 @@ def main() -> int:
     fused["reduce_update"] = {"ms": round(ms, 5), "algorithmic_bytes": fb, "GBps": round(fb / ms / 1e6, 1),
                               "frac_of_hbm_peak": round(fb / ms / 1e6 / HBM_PEAK_GBPS, 4)}
     for i in range(3):
-        px.easgd_round(table, [s_xs[int(j)] for j in orders[i]], s_c, alpha)
+        px.easgd_round(table, [s_xs[int(j)] for j in orders[i]], s_c, alpha, stream=stream)
     ev[0].record()
     for i in range(args.steps):
-        px.easgd_round(table, [s_xs[int(j)] for j in orders[i]], s_c, alpha)
+        px.easgd_round(table, [s_xs[int(j)] for j in orders[i]], s_c, alpha, stream=stream)
     ev[1].record()
     torch.cuda.synchronize()
     ms = ev[0].elapsed_time(ev[1]) / args.steps
@@ -306,10 +311,10 @@ def main() -> int:
     # ---- diagnostics pass over the averaged gradient (read-only: 2 bytes per element)
     d_stats = torch.zeros(3, dtype=torch.int64, device="cuda")
     for i in range(3):
-        px.buffer_stats(table, s_avg, d_stats)
+        px.buffer_stats(table, s_avg, d_stats, stream=stream)
     ev[0].record()
     for i in range(args.steps):
-        px.buffer_stats(table, s_avg, d_stats)
+        px.buffer_stats(table, s_avg, d_stats, stream=stream)
     ev[1].record()
     torch.cuda.synchronize()
     ms = ev[0].elapsed_time(ev[1]) / args.steps
@@ -324,10 +329,10 @@ def main() -> int:
     d_copy = [torch.empty(c_, dtype=torch.float32, device="cuda") for c_ in counts]
     s_copy = table.bufset(d_copy)
     for i in range(3):
-        px.reduce_avg(table, [grad_sets[0][i % k]], s_copy, px.SUM)
+        px.reduce_avg(table, [grad_sets[0][i % k]], s_copy, px.SUM, stream=stream)
     ev[0].record()
     for i in range(args.steps):
-        px.reduce_avg(table, [grad_sets[i % len(grad_sets)][i % k]], s_copy, px.SUM)
+        px.reduce_avg(table, [grad_sets[i % len(grad_sets)][i % k]], s_copy, px.SUM, stream=stream)
     ev[1].record()
     torch.cuda.synchronize()
     copy_ms = ev[0].elapsed_time(ev[1]) / args.steps
