@@ -194,6 +194,8 @@ def main() -> int:
             pack_sets.append([table.bufset(h) for h in d_h])
         else:
             pack_sets.append(grad_sets[-1])       # binary32 transfer: the contributions are the gradients themselves
+        if s == 0:
+            contrib_tensors0 = d_h if half else d_g
         if s > 0:
             del grads
     w = wl.gaussian_tensors(counts, cfg.param_sigma, cfg.seed, "param")
@@ -322,6 +324,43 @@ def main() -> int:
                             "GBps": round(wire_es * n / ms / 1e6, 1),
                             "frac_of_hbm_peak": round(wire_es * n / ms / 1e6 / HBM_PEAK_GBPS, 4),
                             "note": "two launches; an input under 256 MB may sit in the memory-side cache"}
+
+    # ---- the same reduce -> update issued layer by layer (weight and bias of a layer together, last layer
+    # first, as back-propagation would hand the gradients over) on two alternating side streams
+    layer_slices = [slice(i, min(i + 2, len(counts))) for i in range(0, len(counts), 2)]
+    per_layer = []
+    for sl in reversed(layer_slices):
+        tb = px.Table(counts[sl])
+        per_layer.append((tb, [tb.bufset(contrib_tensors0[i][sl]) for i in range(k)], tb.bufset(d_avg[sl]),
+                          tb.bufset(d_w[sl]), tb.bufset(d_v[sl])))
+    main_stream = torch.cuda.current_stream()
+    side = [torch.cuda.Stream(), torch.cuda.Stream()]
+    go, done = torch.cuda.Event(), [torch.cuda.Event(), torch.cuda.Event()]
+
+    def per_layer_step():
+        go.record(main_stream)
+        for st in side:
+            st.wait_event(go)
+        for li, (tb, sh, sa, sw, sv) in enumerate(per_layer):
+            sp = side[li % 2].cuda_stream
+            px.reduce_avg(tb, sh, sa, px.AVG, stream=sp)
+            px.sgd_momentum(tb, sa, sw, sv, cfg.lr, cfg.mu, cfg.wd, stream=sp)
+        for st, d in zip(side, done):
+            d.record(st)
+            main_stream.wait_event(d)
+
+    for i in range(3):
+        per_layer_step()
+    ev[0].record()
+    for i in range(args.steps):
+        per_layer_step()
+    ev[1].record()
+    torch.cuda.synchronize()
+    ms = ev[0].elapsed_time(ev[1]) / args.steps
+    fused["per_layer_two_streams"] = {"ms": round(ms, 5), "algorithmic_bytes": ru_bytes, "layers": len(per_layer),
+                                      "launches": 2 * len(per_layer), "GBps": round(ru_bytes / ms / 1e6, 1),
+                                      "frac_of_hbm_peak": round(ru_bytes / ms / 1e6 / HBM_PEAK_GBPS, 4),
+                                      "note": "reduce+update of the whole set, one table per layer"}
 
     # ---- a plain copy through the same kernel family (k = 1, no divide: out = in) as a
     # reference for what HBM sustains here, and as the known-size kernel that the
