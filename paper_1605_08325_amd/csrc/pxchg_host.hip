@@ -15,7 +15,7 @@ constexpr int64_t kMaxChunk = 1 << 20;
 }  // namespace
 
 PxOptions &px_options() {
-    static PxOptions o = {/*chunk_elems=*/512, /*blocks_per_cu=*/0, /*check_ranges=*/1, /*nontemporal=*/-1};
+    static PxOptions o{{/*chunk_elems=*/512}, {/*blocks_per_cu=*/0}, {/*check_ranges=*/1}, {/*nontemporal=*/-1}};
     return o;
 }
 

@@ -5,6 +5,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
 #include <vector>
 
 #include "pxchg.h"
@@ -41,11 +42,13 @@ struct pxchg_bufset {
 constexpr uint32_t PX_TABLE_MAGIC = 0x70784354u;
 constexpr uint32_t PX_BUFSET_MAGIC = 0x70784253u;
 
+// Process-wide settings.  Each is one atomic word, so a thread that changes one while another thread is in a
+// call is not a data race: that call sees the old or the new value of each option it reads.
 struct PxOptions {
-    int64_t chunk_elems;
-    int64_t blocks_per_cu;
-    int64_t check_ranges;
-    int64_t nontemporal;
+    std::atomic<int64_t> chunk_elems;
+    std::atomic<int64_t> blocks_per_cu;
+    std::atomic<int64_t> check_ranges;
+    std::atomic<int64_t> nontemporal;
 };
 PxOptions &px_options();
 

@@ -145,17 +145,16 @@ __device__ __forceinline__ FV<U> loadv(const float *p) {
     FV<U> r;
     if constexpr (U == 1) {
         r.v[0] = ldv<NT>((const PX_GLOBAL float *)p);
-        return r;
     } else if constexpr (U == 2) {
         const f32x2 a = ldv<NT>((const PX_GLOBAL f32x2 *)p);
         r.v[0] = a.x; r.v[1] = a.y;
-        return r;
-    }
-    const f32x4 a = ldv<NT>((const PX_GLOBAL f32x4 *)p);
-    r.v[0] = a.x; r.v[1] = a.y; r.v[2] = a.z; r.v[3] = a.w;
-    if constexpr (U == 8) {
-        const f32x4 b = ldv<NT>((const PX_GLOBAL f32x4 *)(p + (SPLIT ? SPLIT_GAP : 4)));
-        r.v[4] = b.x; r.v[5] = b.y; r.v[6] = b.z; r.v[7] = b.w;
+    } else {
+        const f32x4 a = ldv<NT>((const PX_GLOBAL f32x4 *)p);
+        r.v[0] = a.x; r.v[1] = a.y; r.v[2] = a.z; r.v[3] = a.w;
+        if constexpr (U == 8) {
+            const f32x4 b = ldv<NT>((const PX_GLOBAL f32x4 *)(p + (SPLIT ? SPLIT_GAP : 4)));
+            r.v[4] = b.x; r.v[5] = b.y; r.v[6] = b.z; r.v[7] = b.w;
+        }
     }
     return r;
 }
@@ -187,20 +186,19 @@ template <int NT, int U, bool SPLIT>
 __device__ __forceinline__ void storev(float *p, const FV<U> &x) {
     if constexpr (U == 1) {
         stv<NT>((PX_GLOBAL float *)p, x.v[0]);
-        return;
     } else if constexpr (U == 2) {
         f32x2 a2;
         a2.x = x.v[0]; a2.y = x.v[1];
         stv<NT>((PX_GLOBAL f32x2 *)p, a2);
-        return;
-    }
-    f32x4 a;
-    a.x = x.v[0]; a.y = x.v[1]; a.z = x.v[2]; a.w = x.v[3];
-    stv<NT>((PX_GLOBAL f32x4 *)p, a);
-    if constexpr (U == 8) {
-        f32x4 b;
-        b.x = x.v[4]; b.y = x.v[5]; b.z = x.v[6]; b.w = x.v[7];
-        stv<NT>((PX_GLOBAL f32x4 *)(p + (SPLIT ? SPLIT_GAP : 4)), b);
+    } else {
+        f32x4 a;
+        a.x = x.v[0]; a.y = x.v[1]; a.z = x.v[2]; a.w = x.v[3];
+        stv<NT>((PX_GLOBAL f32x4 *)p, a);
+        if constexpr (U == 8) {
+            f32x4 b;
+            b.x = x.v[4]; b.y = x.v[5]; b.z = x.v[6]; b.w = x.v[7];
+            stv<NT>((PX_GLOBAL f32x4 *)(p + (SPLIT ? SPLIT_GAP : 4)), b);
+        }
     }
 }
 template <int NT, int U, bool SPLIT>
@@ -888,14 +886,15 @@ struct Launch {
 };
 
 // `nt_default` is the kernel's own measured-best policy, used unless the caller
-// set PXCHG_OPT_NONTEMPORAL to 0..3.
+// set PXCHG_OPT_NONTEMPORAL to 0..5.
 Launch launch_shape(const pxchg_table *t, int64_t n_virtual, int nt_default) {
     const PxOptions &o = px_options();
+    const int64_t bpc = o.blocks_per_cu, nt = o.nontemporal;
     int64_t g = std::min<int64_t>(n_virtual, (int64_t)1 << 24);  // the kernels loop over what is left
-    if (o.blocks_per_cu > 0) g = std::min<int64_t>(g, (int64_t)px_cu_count(t->device) * o.blocks_per_cu);
+    if (bpc > 0) g = std::min<int64_t>(g, (int64_t)px_cu_count(t->device) * bpc);
     Launch l;
     l.grid = dim3((unsigned)g, 1, 1);
-    l.nt = o.nontemporal < 0 ? nt_default : (int)o.nontemporal;
+    l.nt = nt < 0 ? nt_default : (int)nt;
     return l;
 }
 
