@@ -83,9 +83,11 @@ const char *pxchg_status_string(int status);
 /* Library version as major*10000 + minor*100 + patch. */
 int pxchg_version(void);
 
-/* Set / read a launch-shape control.  Process-wide, not thread-safe against
- * concurrent calls into the library.  pxchg_get_option returns -1 for an
- * unknown option. */
+/* Set / read a launch-shape control.  Process-wide; each option is one atomic
+ * word, so a call running in another thread sees the old or the new value.
+ * pxchg_set_option returns PXCHG_ERR_INVALID_ARG for an unknown option or a
+ * value outside the stated range; pxchg_get_option returns -1 for an unknown
+ * option. */
 int pxchg_set_option(int option, int64_t value);
 int64_t pxchg_get_option(int option);
 
