@@ -217,22 +217,22 @@ def main() -> int:
     # which shows in the configurations whose kernels take 10..25 us)
     stream = torch.cuda.current_stream().cuda_stream
 
-    def step(i, ev=None):
+    def step(i, ev=None, st=stream):
         s = i % len(grad_sets)
         if ev:
             ev[0].record()
         if half:
-            px.pack_fp16(table, grad_sets[s], pack_sets[s], stream=stream)
+            px.pack_fp16(table, grad_sets[s], pack_sets[s], stream=st)
         if ev:
             ev[1].record()
-        px.reduce_avg(table, pack_sets[s], s_avg, px.AVG, stream=stream)
+        px.reduce_avg(table, pack_sets[s], s_avg, px.AVG, stream=st)
         if ev:
             ev[2].record()
-        px.sgd_momentum(table, s_avg, s_w, s_v, cfg.lr, cfg.mu, cfg.wd, stream=stream)
+        px.sgd_momentum(table, s_avg, s_w, s_v, cfg.lr, cfg.mu, cfg.wd, stream=st)
         if ev:
             ev[3].record()
         for j in orders[i]:
-            px.easgd(table, s_xs[int(j)], s_c, alpha, stream=stream)
+            px.easgd(table, s_xs[int(j)], s_c, alpha, stream=st)
         if ev:
             ev[4].record()
 
@@ -361,6 +361,28 @@ def main() -> int:
                                       "launches": 2 * len(per_layer), "GBps": round(ru_bytes / ms / 1e6, 1),
                                       "frac_of_hbm_peak": round(ru_bytes / ms / 1e6 / HBM_PEAK_GBPS, 4),
                                       "note": "reduce+update of the whole set, one table per layer"}
+
+    # ---- the whole step captured once into a HIP graph and replayed (the calls allocate nothing and record
+    # no memset): what is left of a step when the host's per-call cost is gone
+    graph = torch.cuda.CUDAGraph()
+    cap = torch.cuda.Stream()
+    cap.wait_stream(main_stream)
+    with torch.cuda.stream(cap):
+        with torch.cuda.graph(graph, stream=cap):
+            step(0, st=cap.cuda_stream)
+    main_stream.wait_stream(cap)
+    torch.cuda.synchronize()
+    for i in range(3):
+        graph.replay()
+    ev[0].record()
+    for i in range(args.steps):
+        graph.replay()
+    ev[1].record()
+    torch.cuda.synchronize()
+    ms = ev[0].elapsed_time(ev[1]) / args.steps
+    fused["step_from_hip_graph"] = {"ms": round(ms, 5), "algorithmic_bytes": step_bytes,
+                                    "GBps": round(step_bytes / ms / 1e6, 1),
+                                    "eager_ms": round(ms_per_step, 5)}
 
     # ---- a plain copy through the same kernel family (k = 1, no divide: out = in) as a
     # reference for what HBM sustains here, and as the known-size kernel that the
