@@ -46,7 +46,9 @@ _lib = None
 def lib() -> ctypes.CDLL:
     global _lib
     if _lib is None:
-        L = ctypes.CDLL(build())
+        # PXCHG_ORACLE_LIB: a prebuilt oracle to load instead (the mutation test points it at deliberately
+        # broken builds to show that the pins notice)
+        L = ctypes.CDLL(os.environ.get("PXCHG_ORACLE_LIB") or build())
         i64, vp, f = ctypes.c_int64, ctypes.c_void_p, ctypes.c_float
         L.oracle_f32_to_f16_bits.argtypes = [ctypes.c_uint32]
         L.oracle_f32_to_f16_bits.restype = ctypes.c_uint16

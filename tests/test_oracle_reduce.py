@@ -7,28 +7,11 @@ import numpy as np
 import pytest
 
 import workloads as wl
+from exact_arith import exact_round_f32
 
 
 def f32(x):
     return np.asarray(x, dtype=np.float32)
-
-
-def exact_round_f32(q: Fraction) -> np.float32:
-    """Correctly rounded binary32 of a rational, by exact neighbour comparison
-    (no double rounding): start from the double-rounded guess and move to
-    whichever neighbour is strictly closer; break ties to even."""
-    g = np.float32(float(q))
-    while True:
-        lo = np.nextafter(g, np.float32(-np.inf))
-        hi = np.nextafter(g, np.float32(np.inf))
-        dg, dl, dh = (abs(Fraction(float(t)) - q) for t in (g, lo, hi))
-        even_g = (int(np.array([g]).view(np.uint32)[0]) & 1) == 0
-        if dl < dg or (dl == dg and not even_g):
-            g = lo
-        elif dh < dg or (dh == dg and not even_g):
-            g = hi
-        else:
-            return g
 
 
 def test_two_identical_buffers_give_exactly_twice(oracle_mod):
@@ -76,6 +59,27 @@ def test_order_sensitive_hand_cases(oracle_mod):
     c = [f32([3.0])] * 3 + [f32([1e8]), f32([-1e8])]
     # 9 + 1e8 -> 1e8 + 8, minus 1e8 = 8
     assert oracle_mod.reduce_avg(c, mode=oracle_mod.SUM)[0] == 8.0
+
+
+def test_order_sensitive_hand_cases_with_half_contributions(oracle_mod):
+    """The same for binary16 contributions, which are widened exactly and summed in binary32: 65504 (the largest
+    half) has ulp 2^-8 in binary32, so adding 2^-10 to it is lost, while 2^-10 survives next to zero."""
+    big, small = np.float16(65504.0), np.float16(2.0 ** -10)
+    h = lambda x: np.array([x], np.float16)
+    r = oracle_mod.reduce_avg([h(big), h(-big), h(small)], mode=oracle_mod.SUM)
+    assert r[0] == np.float32(2.0 ** -10)
+    r = oracle_mod.reduce_avg([h(big), h(small), h(-big)], mode=oracle_mod.SUM)
+    assert r[0] == 0.0
+    r = oracle_mod.reduce_avg([h(small), h(big), h(-big)], mode=oracle_mod.SUM)
+    assert r[0] == 0.0
+    # three quarters of an ulp, added one at a time: each 3 * 2^-10 alone rounds away, together they would not
+    c = [h(big)] + [h(np.float16(3 * 2.0 ** -10))] * 3 + [h(-big)]
+    assert oracle_mod.reduce_avg(c, mode=oracle_mod.SUM)[0] == 2.0 ** -8 * 3   # each step rounds up one ulp
+    c = [h(np.float16(3 * 2.0 ** -10))] * 3 + [h(big), h(-big)]
+    assert oracle_mod.reduce_avg(c, mode=oracle_mod.SUM)[0] == 2.0 ** -8 * 2   # 9 * 2^-10 rounds to two ulps
+    # the result as binary16, and the average, go through the same fold
+    r = oracle_mod.reduce_avg([h(big), h(-big), h(small), h(small)], np.float16, oracle_mod.AVG)
+    assert r.dtype == np.float16 and r[0] == np.float16(2.0 ** -11)
 
 
 def test_running_sum_starts_from_first_contribution(oracle_mod):

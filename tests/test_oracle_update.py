@@ -1,8 +1,12 @@
 """Pins for the oracle's momentum-SGD step and elastic-averaging step (Section 4:
 momentum SGD as the optimiser; EASGD with moving rate alpha)."""
+from fractions import Fraction
+
 import numpy as np
 import pytest
 import torch
+
+from exact_arith import exact_round_f32 as rn, fr
 
 
 # ---------------------------------------------------------------- momentum SGD
@@ -90,18 +94,64 @@ def test_half_gradient_is_widened_exactly(oracle_mod):
     assert np.array_equal(v1.view(np.uint32), v2.view(np.uint32))
 
 
-def test_each_operation_is_rounded_separately(oracle_mod):
-    """A fused multiply-add would keep the low bits of lr*gg; separate rounding
-    loses them.  Choose values where the two differ in v'."""
-    mu, lr = np.float32(0.9), np.float32(0.01)
-    v0 = np.array([1.0], np.float32)
+def test_each_operation_is_rounded_separately_hand_cases(oracle_mod):
+    """A fused multiply-add keeps the low bits of a product that separate rounding drops.  Two cancellations make
+    those bits the whole result: (a) mu*v equal to the rounded lr*g, (b) g equal to minus the rounded wd*w."""
+    lr, wd = np.float32(0.01), np.float32(5e-4)
     g = np.array([1.0 / 3.0], np.float32)
-    w, v = np.zeros(1, np.float32), v0.copy()
-    oracle_mod.sgd_momentum(g, w, v, float(lr), float(mu), 0.0)
-    mv = np.float32(mu * v0[0])
-    lg = np.float32(lr * g[0])
-    assert v[0] == np.float32(mv - lg)
-    assert w[0] == v[0]
+    lg = rn(fr(lr) * fr(g[0]))
+    assert fr(lg) != fr(lr) * fr(g[0])                       # the product is inexact: the case discriminates
+    w, v = np.zeros(1, np.float32), np.array([lg], np.float32)
+    oracle_mod.sgd_momentum(g, w, v, float(lr), 1.0, 0.0)     # mv = lg exactly, so v' = lg - lg
+    assert v[0] == 0.0 and w[0] == 0.0
+    w0 = np.array([0.7], np.float32)
+    dw = rn(fr(wd) * fr(w0[0]))
+    assert fr(dw) != fr(wd) * fr(w0[0])
+    w, v = w0.copy(), np.zeros(1, np.float32)
+    oracle_mod.sgd_momentum(np.array([-dw], np.float32), w, v, float(lr), 0.0, float(wd))   # gg = -dw + dw
+    assert v[0] == 0.0 and w[0] == w0[0]
+
+
+def test_update_equals_exact_arithmetic_rounded_after_every_operation(oracle_mod):
+    """Brute force: every product, sum and difference formed exactly (rationals) and rounded correctly to
+    binary32 on its own, on values spread over many binades.  The same with any one product fused into the
+    following sum must differ somewhere, or the inputs would not tell the two apart."""
+    rng = np.random.default_rng(12)
+    n = 400
+    spread = lambda lo, hi: (np.exp2(rng.uniform(lo, hi, n)) * rng.choice([-1, 1], n)).astype(np.float32)
+    g, w0, v0 = spread(-12, 2), spread(-8, 3), spread(-14, 0)
+    lr, mu, wd = np.float32(0.01), np.float32(0.9), np.float32(5e-4)
+    w, v = w0.copy(), v0.copy()
+    oracle_mod.sgd_momentum(g, w, v, float(lr), float(mu), float(wd))
+    fused_differs = [0, 0]
+    for j in range(n):
+        dw = rn(fr(wd) * fr(w0[j]))
+        gg = rn(fr(g[j]) + fr(dw))
+        mv = rn(fr(mu) * fr(v0[j]))
+        lg = rn(fr(lr) * fr(gg))
+        vn = rn(fr(mv) - fr(lg))
+        wn = rn(fr(w0[j]) + fr(vn))
+        assert v[j] == vn and w[j] == wn, j
+        fused_differs[0] += rn(fr(mv) - fr(lr) * fr(gg)) != vn
+        fused_differs[1] += rn(fr(g[j]) + fr(wd) * fr(w0[j])) != gg
+    assert min(fused_differs) > 0, fused_differs
+
+
+def test_easgd_equals_exact_arithmetic_rounded_after_every_operation(oracle_mod):
+    rng = np.random.default_rng(13)
+    n = 400
+    spread = lambda lo, hi: (np.exp2(rng.uniform(lo, hi, n)) * rng.choice([-1, 1], n)).astype(np.float32)
+    x0, c0 = spread(-8, 3), spread(-8, 3)
+    alpha = np.float32(0.0625 * 1.7)                            # not a power of two: alpha * diff is inexact
+    x, c = x0.copy(), c0.copy()
+    oracle_mod.easgd(x, c, float(alpha))
+    fused_differs = 0
+    for j in range(n):
+        diff = rn(fr(x0[j]) - fr(c0[j]))
+        d = rn(fr(alpha) * fr(diff))
+        assert x[j] == rn(fr(x0[j]) - fr(d)) and c[j] == rn(fr(c0[j]) + fr(d)), j
+        fused_differs += rn(fr(x0[j]) - fr(alpha) * fr(diff)) != x[j]
+    assert fused_differs > 0
 
 
 # ---------------------------------------------------------------- elastic averaging
