@@ -902,10 +902,11 @@ Launch launch_shape(const pxchg_table *t, int64_t n_virtual, int nt_default) {
 //   * the non-temporal hint on loads helps every kernel (+10..17 %);
 //   * the reduce (one written byte in nine) and the widening unpack are fastest with agent-scope stores without
 //     the streaming hint (policy 5: +3..4 % over plain stores, +7 % over non-temporal stores);
-//   * pack, the update with a binary16 gradient and the single elastic meeting are fastest with agent-scope
-//     streaming stores (policy 4: +1..2 % over plain non-temporal stores);
-//   * the update with a binary32 gradient, the fused reduce+update and the fused elastic round are fastest with
-//     plain non-temporal stores (policy 3; policy 4 is 2..5 % slower there).
+//   * pack, the update with a binary16 gradient, the single elastic meeting and the fused elastic round of
+//     three or more workers are fastest with agent-scope streaming stores (policy 4: +1..3 % over plain
+//     non-temporal stores);
+//   * the update with a binary32 gradient, the fused reduce+update and the fused round of two are fastest with
+//     plain non-temporal stores (policy 3; policy 4 is 0..3 % slower there).
 constexpr int NT_BOTH = 3, NT_LOADS_SC1NT_STORES = 4, NT_LOADS_SC1_STORES = 5;
 
 // Expands CALL(n) for the run-time cache policy n = 0..5.
@@ -1186,11 +1187,11 @@ int pxchg_easgd_round(const pxchg_table *table, int k, pxchg_bufset *const *x, p
     }
     if (table->n_chunks == 0) return PXCHG_OK;
     hipStream_t s = (hipStream_t)stream;
-    const Launch l = launch_shape(table, table->n_chunks, k == 1 ? NT_LOADS_SC1NT_STORES : NT_BOTH);
     // More than 8 workers: successive launches of up to 8, the center carried
     // through memory between them (same arithmetic, same order).
     for (int i0 = 0; i0 < k; i0 += 8) {
         const int kk = std::min(8, k - i0);
+        const Launch l = launch_shape(table, table->n_chunks, kk == 2 ? NT_BOTH : NT_LOADS_SC1NT_STORES);
         ElasticArgs a;
         for (int i = 0; i < kk; ++i) a.x[i] = (void *const *)x[i0 + i]->d_ptrs;
         a.c = (void *const *)c->d_ptrs;
