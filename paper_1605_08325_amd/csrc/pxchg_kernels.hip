@@ -1224,7 +1224,10 @@ int pxchg_buffer_stats(const pxchg_table *table, const pxchg_bufset *set, pxchg_
     // two 16-wavefront workgroups per compute unit, each wavefront looping over chunks: the card is full,
     // and only three atomics per workgroup reach `out`
     const int waves = STATS_BLOCK / 64 * (set->dtype == PXCHG_F32 ? stats_group<float>() : stats_group<_Float16>());
-    const int64_t need = (table->n_chunks + waves - 1) / waves;  // `waves` chunks per workgroup and trip
+    // `waves` chunks per workgroup and trip; a small set gets fewer workgroups of four trips each rather than
+    // one trip in many, because every workgroup ends in atomics on the one result (14 MB: 15 -> 10 us)
+    const int64_t per_wg = (int64_t)waves * 4;
+    const int64_t need = (table->n_chunks + per_wg - 1) / per_wg;
     const dim3 grid((unsigned)std::min<int64_t>(need, (int64_t)px_cu_count(table->device) * 2));
     const void *const *ptrs = (const void *const *)set->d_ptrs;
     if (set->dtype == PXCHG_F32)
