@@ -252,6 +252,41 @@ def test_sgd_momentum_tiny_values_keep_subnormals(px, oracle_mod):
     assert np.any((np.abs(v[0]) < 1.1754944e-38) & (v[0] != 0))     # subnormals did occur
 
 
+def test_update_and_elastic_special_values(px, oracle_mod):
+    """Infinities, NaN, signed zeros, subnormals and the extremes of the range through the update (staged and
+    fused) and the elastic step: the same bits as the oracle, NaN compared as a class (Inf - Inf, 0 * Inf)."""
+    sp = np.array([0.0, -0.0, np.inf, -np.inf, np.nan, 1e-45, -1e-45, 1.1754942e-38, 3e38, -3e38, 1.0, -2.5],
+                  np.float32)
+    m = sp.size
+    g = [np.repeat(sp, m * m)]
+    w0 = [np.tile(np.repeat(sp, m), m)]
+    v0 = [np.tile(sp, m * m)]
+    n = g[0].size
+    table = px.Table([n])
+    for lr, mu, wd in ((0.01, 0.9, 5e-4), (0.0, 0.0, 0.0), (1.0, 1.0, 0.0)):
+        w, v = [w0[0].copy()], [v0[0].copy()]
+        d_w, d_v = to_device(w), to_device(v)
+        px.sgd_momentum(table, table.bufset(to_device(g)), table.bufset(d_w), table.bufset(d_v), lr, mu, wd)
+        oracle_mod.sgd_momentum_tensors(g, w, v, lr, mu, wd)
+        assert_bits_equal(to_host(d_w), w, f"w lr={lr}", nan_as_class=True)
+        assert_bits_equal(to_host(d_v), v, f"v lr={lr}", nan_as_class=True)
+        # fused, two workers: the mean of (g, g) is g wherever 2g does not overflow; the oracle decides
+        w2, v2 = [w0[0].copy()], [v0[0].copy()]
+        d_w2, d_v2 = to_device(w2), to_device(v2)
+        sets = [table.bufset(to_device(g)), table.bufset(to_device(g))]
+        px.reduce_avg_sgd_momentum(table, sets, table.bufset(d_w2), table.bufset(d_v2), lr, mu, wd)
+        oracle_mod.sgd_momentum_tensors(oracle_mod.reduce_avg_tensors([g, g]), w2, v2, lr, mu, wd)
+        assert_bits_equal(to_host(d_w2), w2, f"fused w lr={lr}", nan_as_class=True)
+        assert_bits_equal(to_host(d_v2), v2, f"fused v lr={lr}", nan_as_class=True)
+    for alpha in (0.0625, 0.0, 0.5, 1.0):
+        x, c = [w0[0].copy()], [v0[0].copy()]
+        d_x, d_c = to_device(x), to_device(c)
+        px.easgd(table, table.bufset(d_x), table.bufset(d_c), alpha)
+        oracle_mod.easgd_tensors(x, c, alpha)
+        assert_bits_equal(to_host(d_x), x, f"x alpha={alpha}", nan_as_class=True)
+        assert_bits_equal(to_host(d_c), c, f"c alpha={alpha}", nan_as_class=True)
+
+
 # ------------------------------------------------------------------ fused reduce + update
 
 @pytest.mark.parametrize("k", [1, 2, 3, 8])
