@@ -12,7 +12,7 @@ _LIB_PATH = os.path.join(_HERE, "libpxchg.so")
 AVG, SUM = 0, 1
 F32, F16 = 0, 1
 MAX_K = 64
-OPT_CHUNK_ELEMS, OPT_BLOCKS_PER_CU, OPT_CHECK_RANGES, OPT_NONTEMPORAL = 0, 1, 2, 3
+OPT_CHUNK_ELEMS, OPT_BLOCKS_PER_CU, OPT_CHECK_RANGES, OPT_NONTEMPORAL, OPT_CENTER_RESIDENT = 0, 1, 2, 3, 4
 
 _i64 = ctypes.c_int64
 _vp = ctypes.c_void_p

@@ -15,7 +15,8 @@ constexpr int64_t kMaxChunk = 1 << 20;
 }  // namespace
 
 PxOptions &px_options() {
-    static PxOptions o{{/*chunk_elems=*/512}, {/*blocks_per_cu=*/0}, {/*check_ranges=*/1}, {/*nontemporal=*/-1}};
+    static PxOptions o{{/*chunk_elems=*/512}, {/*blocks_per_cu=*/0}, {/*check_ranges=*/1}, {/*nontemporal=*/-1},
+                       {/*center_resident=*/0}};
     return o;
 }
 
@@ -69,6 +70,10 @@ int pxchg_set_option(int option, int64_t value) {
             if (value < -1 || value > 5) return PXCHG_ERR_INVALID_ARG;
             o.nontemporal = value;
             return PXCHG_OK;
+        case PXCHG_OPT_CENTER_RESIDENT:
+            if (value != 0 && value != 1) return PXCHG_ERR_INVALID_ARG;
+            o.center_resident = value;
+            return PXCHG_OK;
         default:
             return PXCHG_ERR_INVALID_ARG;
     }
@@ -81,6 +86,7 @@ int64_t pxchg_get_option(int option) {
         case PXCHG_OPT_BLOCKS_PER_CU: return o.blocks_per_cu;
         case PXCHG_OPT_CHECK_RANGES: return o.check_ranges;
         case PXCHG_OPT_NONTEMPORAL: return o.nontemporal;
+        case PXCHG_OPT_CENTER_RESIDENT: return o.center_resident;
         default: return -1;
     }
 }

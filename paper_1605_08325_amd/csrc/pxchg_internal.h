@@ -49,6 +49,7 @@ struct PxOptions {
     std::atomic<int64_t> blocks_per_cu;
     std::atomic<int64_t> check_ranges;
     std::atomic<int64_t> nontemporal;
+    std::atomic<int64_t> center_resident;
 };
 PxOptions &px_options();
 

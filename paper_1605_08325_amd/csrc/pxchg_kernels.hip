@@ -691,8 +691,11 @@ struct ElasticArgs {
     float alpha;
 };
 
-template <int K, int NT, int U>
+// CR ("center resident"): the center is read with plain loads and written with agent-scope stores, whatever
+// the policy of the worker operands, so that it stays in the memory-side cache between meetings.
+template <int K, int NT, int U, bool CR>
 struct ElasticOp {
+    static constexpr int C_LOAD = CR ? 0 : NT, C_STORE = CR ? 5 : NT;
     float *x[K];
     float *c;
     float alpha;
@@ -713,7 +716,7 @@ struct ElasticOp {
     __device__ __forceinline__ void load(State &st, int i) const {
 #pragma unroll
         for (int q = 0; q < K; ++q) st.xs[q] = loadv<NT, U, SP>(x[q] + i);
-        st.cc = loadv<NT, U, SP>(c + i);
+        st.cc = loadv<C_LOAD, U, SP>(c + i);
     }
     __device__ __forceinline__ void compute(State &st) const {
 #pragma unroll
@@ -725,18 +728,18 @@ struct ElasticOp {
     __device__ __forceinline__ void store(const State &st, int i) const {
 #pragma unroll
         for (int q = 0; q < K; ++q) storev<NT, U, SP>(x[q] + i, st.xs[q]);
-        storev<NT, U, SP>(c + i, st.cc);
+        storev<C_STORE, U, SP>(c + i, st.cc);
     }
 };
 
-template <int K, int NT>
+template <int K, int NT, bool CR>
 __global__ __launch_bounds__((elastic_lanes<K>())) void pxchg_easgd_kernel(const PxChunk *__restrict__ chunks,
                                                                         int n_chunks, ElasticArgs args) {
     constexpr int NTH = elastic_lanes<K>(), U = 512 / NTH;
     constexpr bool SPLIT = false;
     for (int c = blockIdx.x; c < n_chunks; c += gridDim.x) {
         const PxChunk ch = chunks[c];
-        ElasticOp<K, NT, U> op;
+        ElasticOp<K, NT, U, CR> op;
         op.c = table_ptr<float>(args.c, ch.tensor) + ch.start;
         op.alpha = args.alpha;
 #pragma unroll
@@ -1040,8 +1043,15 @@ int launch_fused(const pxchg_table *t, int k, const FusedArgs &a, bool wire16, h
 template <int K>
 void launch_elastic_k(const pxchg_table *t, const Launch &l, const ElasticArgs &a, hipStream_t stream) {
 #define PX_CALL(N) \
-    hipLaunchKernelGGL((pxchg_easgd_kernel<K, N>), l.grid, dim3(elastic_lanes<K>()), 0, stream, t->d_chunks, (int)t->n_chunks, a)
-    PX_DISPATCH_NT(l.nt, PX_CALL)
+    hipLaunchKernelGGL((pxchg_easgd_kernel<K, N, false>), l.grid, dim3(elastic_lanes<K>()), 0, stream, t->d_chunks, (int)t->n_chunks, a)
+#define PX_CALL_CR(N) \
+    hipLaunchKernelGGL((pxchg_easgd_kernel<K, N, true>), l.grid, dim3(elastic_lanes<K>()), 0, stream, t->d_chunks, (int)t->n_chunks, a)
+    if (px_options().center_resident) {
+        PX_DISPATCH_NT(l.nt, PX_CALL_CR)
+    } else {
+        PX_DISPATCH_NT(l.nt, PX_CALL)
+    }
+#undef PX_CALL_CR
 #undef PX_CALL
 }
 

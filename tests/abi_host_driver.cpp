@@ -31,6 +31,10 @@ int main() {
     CHECK(pxchg_set_option(PXCHG_OPT_NONTEMPORAL, -2) == PXCHG_ERR_INVALID_ARG);
     CHECK(pxchg_set_option(PXCHG_OPT_BLOCKS_PER_CU, 65) == PXCHG_ERR_INVALID_ARG);
     CHECK(pxchg_set_option(PXCHG_OPT_CHECK_RANGES, 2) == PXCHG_ERR_INVALID_ARG);
+    CHECK(pxchg_get_option(PXCHG_OPT_CENTER_RESIDENT) == 0);
+    CHECK(pxchg_set_option(PXCHG_OPT_CENTER_RESIDENT, 2) == PXCHG_ERR_INVALID_ARG);
+    CHECK(pxchg_set_option(PXCHG_OPT_CENTER_RESIDENT, 1) == PXCHG_OK && pxchg_get_option(PXCHG_OPT_CENTER_RESIDENT) == 1);
+    CHECK(pxchg_set_option(PXCHG_OPT_CENTER_RESIDENT, 0) == PXCHG_OK);
     CHECK(pxchg_set_option(99, 0) == PXCHG_ERR_INVALID_ARG && pxchg_get_option(99) == -1);
 
     // chunk planning: count first, then fill exactly that many, then a too-small capacity

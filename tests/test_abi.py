@@ -75,15 +75,19 @@ def test_status_strings_and_version(px):
 
 
 def test_options_validate_their_values(px):
-    old = [px.get_option(o) for o in range(4)]
+    old = [px.get_option(o) for o in range(5)]
+    assert old == [512, 0, 1, -1, 0]          # the documented defaults
     try:
+        px.set_option(px.OPT_CENTER_RESIDENT, 1)
+        assert px.get_option(px.OPT_CENTER_RESIDENT) == 1
         px.set_option(px.OPT_CHUNK_ELEMS, 4096)
         assert px.get_option(px.OPT_CHUNK_ELEMS) == 4096
         for bad in (0, 100, 513, 1 << 21, -512):
             with pytest.raises(px.PxchgError):
                 px.set_option(px.OPT_CHUNK_ELEMS, bad)
         for opt, bad in ((px.OPT_BLOCKS_PER_CU, -1), (px.OPT_BLOCKS_PER_CU, 65), (px.OPT_CHECK_RANGES, 2),
-                         (px.OPT_NONTEMPORAL, 6), (px.OPT_NONTEMPORAL, -2), (17, 0)):
+                         (px.OPT_NONTEMPORAL, 6), (px.OPT_NONTEMPORAL, -2), (px.OPT_CENTER_RESIDENT, 2),
+                         (px.OPT_CENTER_RESIDENT, -1), (17, 0)):
             with pytest.raises(px.PxchgError):
                 px.set_option(opt, bad)
         assert px.get_option(17) == -1

@@ -485,6 +485,33 @@ def test_every_cache_policy_gives_the_same_bits(px, oracle_mod, policy):
         px.set_option(px.OPT_NONTEMPORAL, old)
 
 
+@pytest.mark.parametrize("policy", [-1, 0, 3])
+@pytest.mark.parametrize("offset", [0, 1])
+def test_center_resident_option_gives_the_same_bits(px, oracle_mod, policy, offset):
+    """Keeping the center in the memory-side cache changes how it is loaded and stored, never a result:
+    single meetings and fused rounds of every specialised size, with the option on."""
+    old = px.get_option(px.OPT_NONTEMPORAL)
+    try:
+        px.set_option(px.OPT_CENTER_RESIDENT, 1)
+        px.set_option(px.OPT_NONTEMPORAL, policy)
+        table = px.Table(RAGGED)
+        for k in (1, 2, 3, 4, 5, 8, 9):
+            xs = [_gauss(RAGGED, 970 + k, w, role="worker") for w in range(k)]
+            c = _gauss(RAGGED, 971 + k, role="center")
+            d_xs, d_c = [to_device(x, offset) for x in xs], to_device(c, offset)
+            sets, sc = [table.bufset(x) for x in d_xs], table.bufset(d_c)
+            px.easgd_round(table, sets, sc, 0.0625)
+            px.easgd(table, sets[0], sc, 0.0625)
+            for i in list(range(k)) + [0]:
+                oracle_mod.easgd_tensors(xs[i], c, np.float32(0.0625))
+            for i in range(k):
+                assert_bits_equal(to_host(d_xs[i]), xs[i], f"k={k} x[{i}]")
+            assert_bits_equal(to_host(d_c), c, f"k={k} center")
+    finally:
+        px.set_option(px.OPT_CENTER_RESIDENT, 0)
+        px.set_option(px.OPT_NONTEMPORAL, old)
+
+
 # ------------------------------------------------------------------ argument errors on a live device
 
 def test_argument_errors(px):
