@@ -432,6 +432,21 @@ def main() -> int:
     copy_ms = ev[0].elapsed_time(ev[1]) / args.steps
     copy_gbps = 8 * n / copy_ms / 1e6
 
+    # ---- weight averaging (Section 4's other scheme): the same reduce over the k workers' float32 weights and
+    # over their velocities (the float32 gradient buffers stand in for those), one launch each
+    for i in range(3):
+        px.reduce_avg(table, s_xs, s_copy, px.AVG, stream=stream)
+    ev[0].record()
+    for i in range(args.steps):
+        px.reduce_avg(table, s_xs if i % 2 == 0 else grad_sets[0], s_copy, px.AVG, stream=stream)
+    ev[1].record()
+    torch.cuda.synchronize()
+    ms = ev[0].elapsed_time(ev[1]) / args.steps
+    fb = (4 * k + 4) * n
+    fused["weight_averaging"] = {"ms": round(ms, 5), "algorithmic_bytes": fb, "GBps": round(fb / ms / 1e6, 1),
+                                 "frac_of_hbm_peak": round(fb / ms / 1e6 / HBM_PEAK_GBPS, 4),
+                                 "note": f"pxchg_reduce_avg over {k} float32 sets, per launch (weights, then velocities)"}
+
     # ---- the oracle on the host cores, same workload (a baseline, not a target)
     baseline = None
     if not args.no_cpu_baseline:
