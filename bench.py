@@ -17,6 +17,12 @@ times come from HIP events recorded on the launch stream between the stages of
 every timed step; the `roofline` object is for the kernel with the largest share
 of the step, `stages` lists all of them.
 
+`extras` holds what is measured after the timed region, each over the same number
+of repetitions: the fused reduce+update and the fused elastic round, the elastic
+kernels with the center kept in the memory-side cache, the diagnostics pass, the
+same reduce+update issued layer by layer on two streams, the whole step replayed
+from a HIP graph, and weight averaging (the reduce over float32 sets).
+
 `cpu_baseline` is the CPU oracle timed on the host cores on the same workload.
 It is a reported baseline (and the only place this program touches the oracle),
 never a fallback: without the built HIP library this program fails.
