@@ -137,6 +137,22 @@ def cpu_baseline(counts, grads, w, v, xs, c, order, cfg, alpha, threads):
     return run(threads, 2), run(1, 1)
 
 
+def device_facts(torch) -> dict:
+    """What the runtime reports about GPU 0, to check the figures the roofline is priced against."""
+    p = torch.cuda.get_device_properties(0)
+    facts = {"name": p.name, "compute_units": p.multi_processor_count, "memory_GiB": round(p.total_memory / 2 ** 30, 1)}
+    for key, attr, scale in (("arch", "gcnArchName", None), ("l2_cache_MiB", "L2_cache_size", 2 ** 20),
+                             ("clock_MHz", "clock_rate", 1000), ("memory_clock_MHz", "memory_clock_rate", 1000),
+                             ("memory_bus_bits", "memory_bus_width", 1), ("wavefront", "warp_size", 1)):
+        v = getattr(p, attr, None)
+        if v is not None:
+            facts[key] = v if scale is None else round(v / scale, 1) if scale != 1 else v
+    if "memory_clock_MHz" in facts and "memory_bus_bits" in facts:
+        # double data rate: two transfers per clock over the whole bus
+        facts["memory_GBps_from_clock_and_bus"] = round(2 * facts["memory_clock_MHz"] * 1e6 * facts["memory_bus_bits"] / 8 / 1e9, 1)
+    return facts
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -498,7 +514,11 @@ def main() -> int:
                            "frac_of_hbm_peak": round(copy_gbps / HBM_PEAK_GBPS, 4)},
         "cpu_baseline": baseline,
         "setup_seconds": round(t_gen, 1),
+        "device": device_facts(torch),
     }
+    # the same achieved rates against what a plain copy through the same kernel family sustains on this machine
+    out["roofline"]["frac_of_copy_kernel"] = round(out["roofline"]["achieved"] / copy_gbps, 4)
+    out["value_frac_of_copy_kernel"] = round(value / copy_gbps, 4)
     print(json.dumps(out))
     return 0
 
