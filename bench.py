@@ -158,7 +158,9 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--sets", type=int, default=2, help="rotating sets of fresh gradients resident in HBM")
+    ap.add_argument("--sets", type=int, default=0,
+                    help="rotating sets of fresh gradients resident in HBM; 0 = as many as make the rotating "
+                         "inputs exceed 1 GB (the caches hold 256 MB), at least 2 and at most 16")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--config", type=int, default=3, choices=[1, 2, 3, 4, 5],
                     help="benchmark configuration (3 = the graded one: AlexNet-shaped, k = 8, half-precision transfer)")
@@ -205,7 +207,9 @@ def main() -> int:
     host_grads0 = None
     grad_sets, pack_sets = [], []
     keep = []
-    for s in range(max(1, args.sets)):
+    set_bytes = k * n * (4 + (2 if half else 0))      # one set: k float32 gradients and, if packed, k halves
+    n_sets = args.sets if args.sets > 0 else max(2, min(16, -(-10 ** 9 // set_bytes)))
+    for s in range(n_sets):
         grads = wl.gaussian_workers(counts, cfg.grad_sigma, cfg.seed, "grad", k, step=s, threads=threads)
         if s == 0:
             host_grads0 = grads
