@@ -220,8 +220,6 @@ def main() -> int:
             pack_sets.append([table.bufset(h) for h in d_h])
         else:
             pack_sets.append(grad_sets[-1])       # binary32 transfer: the contributions are the gradients themselves
-        if s == 0:
-            contrib_tensors0 = d_h if half else d_g
         if s > 0:
             del grads
     w = wl.gaussian_tensors(counts, cfg.param_sigma, cfg.seed, "param")
@@ -386,12 +384,7 @@ def main() -> int:
 
     # ---- the same reduce -> update issued layer by layer (weight and bias of a layer together, last layer
     # first, as back-propagation would hand the gradients over) on two alternating side streams
-    layer_slices = [slice(i, min(i + 2, len(counts))) for i in range(0, len(counts), 2)]
-    per_layer = []
-    for sl in reversed(layer_slices):
-        tb = px.Table(counts[sl])
-        per_layer.append((tb, [tb.bufset(contrib_tensors0[i][sl]) for i in range(k)], tb.bufset(d_avg[sl]),
-                          tb.bufset(d_w[sl]), tb.bufset(d_v[sl])))
+    per_layer = [table.view(i, min(2, len(counts) - i)) for i in reversed(range(0, len(counts), 2))]
     main_stream = torch.cuda.current_stream()
     side = [torch.cuda.Stream(), torch.cuda.Stream()]
     go, done = torch.cuda.Event(), [torch.cuda.Event(), torch.cuda.Event()]
@@ -400,10 +393,10 @@ def main() -> int:
         go.record(main_stream)
         for st in side:
             st.wait_event(go)
-        for li, (tb, sh, sa, sw, sv) in enumerate(per_layer):
+        for li, layer in enumerate(per_layer):          # a view per layer, the whole set's buffer sets
             sp = side[li % 2].cuda_stream
-            px.reduce_avg(tb, sh, sa, px.AVG, stream=sp)
-            px.sgd_momentum(tb, sa, sw, sv, cfg.lr, cfg.mu, cfg.wd, stream=sp)
+            px.reduce_avg(layer, pack_sets[0], s_avg, px.AVG, stream=sp)
+            px.sgd_momentum(layer, s_avg, s_w, s_v, cfg.lr, cfg.mu, cfg.wd, stream=sp)
         for st, d in zip(side, done):
             d.record(st)
             main_stream.wait_event(d)
@@ -419,7 +412,7 @@ def main() -> int:
     fused["per_layer_two_streams"] = {"ms": round(ms, 5), "algorithmic_bytes": ru_bytes, "layers": len(per_layer),
                                       "launches": 2 * len(per_layer), "GBps": round(ru_bytes / ms / 1e6, 1),
                                       "frac_of_hbm_peak": round(ru_bytes / ms / 1e6 / HBM_PEAK_GBPS, 4),
-                                      "note": "reduce+update of the whole set, one table per layer"}
+                                      "note": "reduce+update of the whole set, one view of the table per layer"}
 
     # ---- the whole step captured once into a HIP graph and replayed (the calls allocate nothing and record
     # no memset): what is left of a step when the host's per-call cost is gone

@@ -117,10 +117,23 @@ int pxchg_plan_chunks(int n_tensors, const int64_t *counts /*host*/, int64_t chu
  * The table is bound to the device current at creation; the library keeps a
  * device copy of the chunk list.  Destroying a table or a buffer set waits for
  * the device to go idle first (launches may still be reading their device-side
- * lists).
+ * lists) and frees device memory; neither is allowed while any stream of the
+ * process is being captured into a graph (the capture would be invalidated), so
+ * destroy objects before a capture starts or after it has ended.
  */
 int pxchg_table_create(int n_tensors, const int64_t *counts /*host*/, pxchg_table **out);
 int pxchg_table_destroy(pxchg_table *table);
+/*
+ * A view of `n_tensors` consecutive tensors of `parent`, starting at `first_tensor`: a table handle that
+ * every call accepts in place of the parent, together with the PARENT's buffer sets (a view has none of its
+ * own), and that makes the call work on those tensors only.  It is how one layer, or a group of layers, is
+ * exchanged on its own stream as soon as its gradients exist (Section 3.2 notes that the exchange could overlap
+ * with the rest of the step) without a second set of tables and buffer sets.  A view owns no device memory
+ * (it points into the parent's chunk list), is created and destroyed without synchronising, uses the parent's
+ * multipliers, and must be destroyed before the parent.  Views of views, buffer sets on a view and multipliers
+ * on a view are PXCHG_ERR_INVALID_ARG.
+ */
+int pxchg_table_view(const pxchg_table *parent, int first_tensor, int n_tensors, pxchg_table **out);
 /*
  * Optional per-tensor multipliers for the update calls (the usual way to give biases another learning rate or
  * no weight decay; the paper names weight decay and the learning-rate policy among the hyper-parameters,

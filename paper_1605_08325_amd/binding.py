@@ -4,6 +4,7 @@ from __future__ import annotations
 
 import ctypes
 import os
+import sys
 from typing import List, Optional, Sequence, Tuple
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -30,6 +31,7 @@ SIGNATURES = {
                                  ctypes.POINTER(_i64), ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(_i64)]),
     "pxchg_table_create": (_int, [_int, ctypes.POINTER(_i64), _pp]),
     "pxchg_table_destroy": (_int, [_vp]),
+    "pxchg_table_view": (_int, [_vp, _int, _int, _pp]),
     "pxchg_table_set_multipliers": (_int, [_vp, ctypes.POINTER(_f), ctypes.POINTER(_f)]),
     "pxchg_table_total": (_i64, [_vp]),
     "pxchg_table_n_tensors": (_int, [_vp]),
@@ -129,6 +131,39 @@ def _stream_ptr(stream) -> Optional[int]:
     return stream.cuda_stream or None
 
 
+# Destruction waits for the device and frees device memory, which would invalidate a stream capture in progress.
+# Python decides by itself when an object dies (a collector run can fall into the middle of a capture), so a
+# handle that dies while this thread's current stream is capturing is put aside and destroyed later.
+_deferred: List = []
+
+
+def _capturing() -> bool:
+    torch = sys.modules.get("torch")
+    try:
+        return bool(torch is not None and torch.cuda.is_available() and torch.cuda.is_current_stream_capturing())
+    except Exception:
+        return False
+
+
+def flush_deferred() -> int:
+    """Destroys what was put aside during captures; returns how many handles that were.  Called by itself
+    whenever an object is destroyed outside a capture."""
+    n = 0
+    while _deferred and not _capturing():
+        fname, handle = _deferred.pop()
+        getattr(load(), fname)(handle)
+        n += 1
+    return n
+
+
+def _destroy(fname: str, handle) -> None:
+    if _capturing():
+        _deferred.append((fname, handle))
+        return
+    flush_deferred()
+    getattr(load(), fname)(handle)
+
+
 class Table:
     """pxchg_table: element counts of the parameter set's tensors."""
 
@@ -168,9 +203,20 @@ class Table:
     def bufset(self, tensors, dtype: Optional[int] = None) -> "BufSet":
         return BufSet(self, tensors, dtype)
 
+    def view(self, first_tensor: int, n_tensors: int) -> "Table":
+        """pxchg_table_view: a handle for tensors first_tensor .. first_tensor + n_tensors - 1, to be used with
+        this table's buffer sets.  The view keeps this table alive."""
+        v = Table.__new__(Table)
+        v.counts = self.counts[first_tensor:first_tensor + n_tensors]
+        v._h = _vp()
+        v._parent = self
+        _check(load().pxchg_table_view(self._h, int(first_tensor), int(n_tensors), ctypes.byref(v._h)),
+               "pxchg_table_view")
+        return v
+
     def close(self) -> None:
         if self._h:
-            load().pxchg_table_destroy(self._h)
+            _destroy("pxchg_table_destroy", self._h)
             self._h = _vp()
 
     def __del__(self):
@@ -225,7 +271,7 @@ class BufSet:
 
     def close(self) -> None:
         if self._h:
-            load().pxchg_bufset_destroy(self._h)
+            _destroy("pxchg_bufset_destroy", self._h)
             self._h = _vp()
 
     def __del__(self):

@@ -146,6 +146,8 @@ int pxchg_table_create(int n_tensors, const int64_t *counts, pxchg_table **out) 
     t->counts.assign(counts, counts + n_tensors);
     t->d_chunks = nullptr;
     t->d_mult = nullptr;
+    t->parent = nullptr;
+    t->first_tensor = 0;
 
     if (n_chunks > 0) {
         std::vector<PxChunk> h(n_chunks);
@@ -170,9 +172,44 @@ int pxchg_table_create(int n_tensors, const int64_t *counts, pxchg_table **out) 
     return PXCHG_OK;
 }
 
+int pxchg_table_view(const pxchg_table *parent, int first_tensor, int n_tensors, pxchg_table **out) {
+    if (!out) return PXCHG_ERR_INVALID_ARG;
+    *out = nullptr;
+    if (!px_valid(parent) || parent->parent) return PXCHG_ERR_INVALID_ARG;  // no views of views
+    if (first_tensor < 0 || n_tensors < 1 || first_tensor > parent->n_tensors - n_tensors) return PXCHG_ERR_INVALID_ARG;
+    // chunks never straddle tensors, so a run of tensors is a run of chunks
+    const int64_t ce = parent->chunk_elems;
+    int64_t first_chunk = 0, n_chunks = 0, total = 0;
+    for (int t = 0; t < first_tensor; ++t) first_chunk += (parent->counts[t] + ce - 1) / ce;
+    for (int t = first_tensor; t < first_tensor + n_tensors; ++t) {
+        n_chunks += (parent->counts[t] + ce - 1) / ce;
+        total += parent->counts[t];
+    }
+    pxchg_table *v = new (std::nothrow) pxchg_table();
+    if (!v) return PXCHG_ERR_RUNTIME;
+    v->magic = PX_TABLE_MAGIC;
+    v->device = parent->device;
+    v->n_tensors = n_tensors;
+    v->total = total;
+    v->chunk_elems = ce;
+    v->n_chunks = n_chunks;
+    v->counts.assign(parent->counts.begin() + first_tensor, parent->counts.begin() + first_tensor + n_tensors);
+    v->d_chunks = n_chunks ? parent->d_chunks + first_chunk : nullptr;
+    v->d_mult = nullptr;  // the parent's multipliers apply (looked up at each call)
+    v->parent = parent;
+    v->first_tensor = first_tensor;
+    *out = v;
+    return PXCHG_OK;
+}
+
 int pxchg_table_destroy(pxchg_table *table) {
     if (!table) return PXCHG_OK;
     if (!px_valid(table)) return PXCHG_ERR_INVALID_ARG;
+    if (table->parent) {  // a view owns nothing on the device
+        table->magic = 0;
+        delete table;
+        return PXCHG_OK;
+    }
     int rc = PXCHG_OK;
     (void)hipDeviceSynchronize();  // launches still reading the chunk list must finish first
     if (table->d_chunks && hipFree(table->d_chunks) != hipSuccess) {
@@ -189,7 +226,7 @@ int pxchg_table_destroy(pxchg_table *table) {
 }
 
 int pxchg_table_set_multipliers(pxchg_table *table, const float *lr_mult, const float *wd_mult) {
-    if (!px_valid(table)) return PXCHG_ERR_INVALID_ARG;
+    if (!px_valid(table) || table->parent) return PXCHG_ERR_INVALID_ARG;  // set them on the parent
     int device = -1;
     if (hipGetDevice(&device) != hipSuccess || device != table->device) {
         (void)hipGetLastError();
@@ -230,6 +267,7 @@ int pxchg_bufset_create(const pxchg_table *table, int dtype, const void *const *
     if (!out) return PXCHG_ERR_INVALID_ARG;
     *out = nullptr;
     if (!px_valid(table) || !ptrs) return PXCHG_ERR_INVALID_ARG;
+    if (table->parent) return PXCHG_ERR_INVALID_ARG;  // buffer sets belong to the parent and serve its views
     if (dtype != PXCHG_F32 && dtype != PXCHG_F16) return PXCHG_ERR_INVALID_ARG;
     const size_t es = dtype == PXCHG_F32 ? 4 : 2;
     int device = -1;

@@ -27,9 +27,14 @@ struct pxchg_table {
     int64_t chunk_elems;
     int64_t n_chunks;
     std::vector<int64_t> counts;
-    PxChunk *d_chunks;  // device copy of the chunk list
+    PxChunk *d_chunks;  // device copy of the chunk list (a view: the part of its parent's list it covers)
     float *d_mult;      // optional: n_tensors pairs (lr multiplier, decay multiplier); null = all ones
+    const pxchg_table *parent;  // null for a table of its own; a view owns no device memory
+    int first_tensor;           // a view covers the parent's tensors first_tensor .. first_tensor + n_tensors - 1
 };
+
+// The table that owns the device-side lists, the multipliers and the buffer sets.
+inline const pxchg_table *px_root(const pxchg_table *t) { return t->parent ? t->parent : t; }
 
 struct pxchg_bufset {
     uint32_t magic;

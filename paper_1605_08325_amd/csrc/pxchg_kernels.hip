@@ -935,7 +935,7 @@ int check_table(const pxchg_table *t) {
 
 int check_set(const pxchg_table *t, const pxchg_bufset *s, int dtype /* -1: either */) {
     if (!px_valid(s)) return PXCHG_ERR_INVALID_ARG;
-    if (s->table != t) return PXCHG_ERR_SHAPE_MISMATCH;
+    if (s->table != px_root(t)) return PXCHG_ERR_SHAPE_MISMATCH;  // a view takes its parent's sets
     if (dtype >= 0 && s->dtype != dtype) return PXCHG_ERR_SHAPE_MISMATCH;
     return PXCHG_OK;
 }
@@ -1125,7 +1125,7 @@ int pxchg_sgd_momentum(const pxchg_table *table, const pxchg_bufset *grad, pxchg
     a.grad = (const void *const *)grad->d_ptrs;
     a.param = (void *const *)param->d_ptrs;
     a.vel = (void *const *)vel->d_ptrs;
-    a.mult = table->d_mult;
+    a.mult = px_root(table)->d_mult;
     a.lr = lr;
     a.mu = mu;
     a.wd = wd;
@@ -1171,7 +1171,7 @@ int pxchg_reduce_avg_sgd_momentum(const pxchg_table *table, int k, const pxchg_b
     }
     a.param = (void *const *)param->d_ptrs;
     a.vel = (void *const *)vel->d_ptrs;
-    a.mult = table->d_mult;
+    a.mult = px_root(table)->d_mult;
     a.k = k;
     fill_scale(k, mode, &a.use_div, &a.kf, &a.scale);
     a.lr = lr;

@@ -100,6 +100,10 @@ int main() {
     CHECK(pxchg_bufset_create(not_a_table, PXCHG_F32, ptrs, &set) == PXCHG_ERR_INVALID_ARG && set == nullptr);
     CHECK(pxchg_bufset_create(nullptr, PXCHG_F32, ptrs, &set) == PXCHG_ERR_INVALID_ARG);
     CHECK(pxchg_table_set_multipliers(not_a_table, nullptr, nullptr) == PXCHG_ERR_INVALID_ARG);
+    pxchg_table *view = (pxchg_table *)0x1;
+    CHECK(pxchg_table_view(not_a_table, 0, 1, &view) == PXCHG_ERR_INVALID_ARG && view == nullptr);
+    CHECK(pxchg_table_view(nullptr, 0, 1, &view) == PXCHG_ERR_INVALID_ARG);
+    CHECK(pxchg_table_view(not_a_table, 0, 1, nullptr) == PXCHG_ERR_INVALID_ARG);
     std::printf("ok\n");
     return 0;
 }

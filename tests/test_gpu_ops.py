@@ -654,6 +654,108 @@ def test_per_layer_exchange_on_two_streams_equals_whole_set(px, oracle_mod):
     assert_bits_equal(to_host(d_v), v, "v")
 
 
+def test_views_exchange_layer_by_layer_with_the_parents_sets(px, oracle_mod):
+    """pxchg_table_view: every call restricted to a run of tensors, with the parent's buffer sets and
+    multipliers.  Layer by layer on two streams (staged for some layers, fused for others), then the elastic
+    round, the conversions and the diagnostics through views; everything equals the whole-set oracle."""
+    import torch
+    counts = [34_848, 96, 0, 20_001, 3, 8192 * 2 + 5, 1000, 513, 70_000, 7]
+    k = 3
+    table = px.Table(counts)
+    lr_mult = [1.0, 2.0, 1.0, 1.0, 2.0, 1.0, 2.0, 0.5, 1.0, 2.0]
+    wd_mult = [1.0, 0.0, 1.0, 1.0, 0.0, 1.0, 0.0, 1.0, 1.0, 0.0]
+    table.set_multipliers(lr_mult, wd_mult)
+    grads = [_gauss(counts, 1100, w) for w in range(k)]
+    w = _gauss(counts, 1101, role="param")
+    v = _gauss(counts, 1102, sigma=1e-3, role="velocity")
+    xs = [_gauss(counts, 1103, i, role="worker") for i in range(k)]
+    c = _gauss(counts, 1104, role="center")
+    d_g = [to_device(g) for g in grads]
+    d_h = [empty_like_device(counts, np.float16) for _ in range(k)]
+    d_avg = empty_like_device(counts, np.float16)
+    d_w, d_v = to_device(w), to_device(v)
+    d_xs, d_c = [to_device(x) for x in xs], to_device(c)
+    s_g, s_h = [table.bufset(t) for t in d_g], [table.bufset(t) for t in d_h]
+    s_avg, s_w, s_v = table.bufset(d_avg), table.bufset(d_w), table.bufset(d_v)
+    s_xs, s_c = [table.bufset(t) for t in d_xs], table.bufset(d_c)
+    layers = [(8, 2), (6, 2), (3, 3), (2, 1), (0, 2)]            # (first tensor, tensors), last layer first
+    assert sorted(t for f, m in layers for t in range(f, f + m)) == list(range(len(counts)))
+    views = [table.view(f, m) for f, m in layers]
+    assert [vw.total for vw in views] == [sum(counts[f:f + m]) for f, m in layers]
+    assert sum(vw.n_chunks for vw in views) == table.n_chunks
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    torch.cuda.synchronize()
+    for li, vw in enumerate(views):
+        st = streams[li % 2]
+        px.pack_fp16(vw, s_g, s_h, stream=st)
+        if li % 2 == 0:
+            px.reduce_avg(vw, s_h, s_avg, stream=st)
+            px.sgd_momentum(vw, s_avg, s_w, s_v, 0.01, 0.9, 5e-4, stream=st)
+        else:
+            px.reduce_avg_sgd_momentum(vw, s_h, s_w, s_v, 0.01, 0.9, 5e-4, px.AVG, px.F16, stream=st)
+        px.easgd_round(vw, s_xs, s_c, 0.125, stream=st)
+    for st in streams:
+        st.synchronize()
+    packed = [oracle_mod.pack_fp16_tensors(g) for g in grads]
+    avg = oracle_mod.reduce_avg_tensors(packed, np.float16)
+    for t in range(len(counts)):
+        oracle_mod.sgd_momentum(avg[t], w[t], v[t], float(np.float32(0.01) * np.float32(lr_mult[t])), 0.9,
+                                float(np.float32(5e-4) * np.float32(wd_mult[t])))
+    for i in range(k):
+        oracle_mod.easgd_tensors(xs[i], c, 0.125)
+    for i in range(k):
+        assert_bits_equal(to_host(d_h[i]), packed[i], f"packed[{i}]")
+        assert_bits_equal(to_host(d_xs[i]), xs[i], f"x[{i}]")
+    assert_bits_equal(to_host(d_w), w, "w")
+    assert_bits_equal(to_host(d_v), v, "v")
+    assert_bits_equal(to_host(d_c), c, "center")
+    # the staged layers wrote their part of the mean, the fused ones left theirs alone
+    got_avg = to_host(d_avg)
+    for li, (f, m) in enumerate(layers):
+        if li % 2 == 0:
+            assert_bits_equal(got_avg[f:f + m], avg[f:f + m], f"mean of layer {li}")
+    # diagnostics and widening through a view see only its tensors
+    out = torch.zeros(3, dtype=torch.int64, device="cuda")
+    px.buffer_stats(views[0], s_w, out)
+    torch.cuda.synchronize()
+    bad, mx, ss = px.read_stats(out)
+    wbad, wmx, wss = oracle_mod.stats_tensors(w[8:10])
+    assert (bad, mx) == (wbad, wmx) and abs(ss - wss) <= 1e-12 * wss
+    d_back = empty_like_device(counts, np.float32, fill=7.0)
+    px.unpack_fp16(views[2], [s_h[0]], [table.bufset(d_back)])
+    back = to_host(d_back)
+    assert_bits_equal(back[3:6], oracle_mod.unpack_fp16_tensors(packed[0][3:6]), "unpack through a view")
+    assert all(np.all(b == 7.0) for t, b in enumerate(back) if not 3 <= t < 6)
+
+
+def test_view_argument_errors(px):
+    import torch
+    table = px.Table([100, 200, 300])
+    other = px.Table([100, 200, 300])
+    a = [torch.zeros(c, device="cuda") for c in (100, 200, 300)]
+    sa, so = table.bufset(a), other.bufset([t.clone() for t in a])
+    view = table.view(1, 2)
+    assert (view.total, view.n_tensors, view.n_chunks) == (500, 2, 2)
+    for first, m in ((-1, 1), (0, 0), (0, 4), (3, 1), (2, 2)):
+        with pytest.raises(px.PxchgError) as e:
+            table.view(first, m)
+        assert e.value.status == 1
+    with pytest.raises(px.PxchgError) as e:
+        view.view(0, 1)                                   # no views of views
+    assert e.value.status == 1
+    with pytest.raises(px.PxchgError) as e:
+        view.bufset(a[1:])                                # sets belong to the parent
+    assert e.value.status == 1
+    with pytest.raises(px.PxchgError) as e:
+        view.set_multipliers([1.0, 1.0], None)
+    assert e.value.status == 1
+    with pytest.raises(px.PxchgError) as e:
+        px.easgd(view, sa, so, 0.1)                       # a set of another table
+    assert e.value.status == 2
+    empty = px.Table([0, 5, 0]).view(0, 1)
+    assert empty.n_chunks == 0 and empty.total == 0
+
+
 # ------------------------------------------------------------------ degenerate and maximum sizes
 
 def test_table_of_empty_tensors_is_a_no_op(px):
@@ -776,6 +878,42 @@ def test_exchange_step_replayed_from_a_hip_graph(px, oracle_mod):
         bad, mx, ss = px.read_stats(d_stats)
         wbad, wmx, wss = oracle_mod.stats_tensors(avg)
         assert bad == wbad and mx == wmx and abs(ss - wss) <= 1e-12 * wss
+
+
+def test_destroying_unrelated_objects_does_not_break_a_capture(px, oracle_mod):
+    """A garbage collector may drop an old table or buffer set at any moment, also while a stream is being
+    captured into a graph.  Destruction waits for the device and frees memory, which a capture in progress would
+    answer by invalidating itself; the binding puts such a handle aside and destroys it after the capture."""
+    import torch
+    counts = [5000, 77]
+    table = px.Table(counts)
+    x, c = _gauss(counts, 1200, role="worker"), _gauss(counts, 1201, role="center")
+    d_x, d_c = to_device(x), to_device(c)
+    sx, sc = table.bufset(d_x), table.bufset(d_c)
+    old_table = px.Table([123, 4567])
+    old_set = old_table.bufset([torch.zeros(123, device="cuda"), torch.zeros(4567, device="cuda")])
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            px.easgd(table, sx, sc, 0.25)
+            old_set.close()                     # what a collector would do, in the middle of the capture
+            old_table.close()
+            put_aside = len(px.binding._deferred)
+            px.easgd(table, sx, sc, 0.25)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    assert put_aside >= 2                       # both were put aside during the capture ...
+    px.flush_deferred()
+    assert not px.binding._deferred             # ... and are destroyed now
+    for r in range(2):
+        graph.replay()
+        torch.cuda.synchronize()
+        for _ in range(2):
+            oracle_mod.easgd_tensors(x, c, 0.25)
+        assert_bits_equal(to_host(d_x), x, f"replay {r} x")
+        assert_bits_equal(to_host(d_c), c, f"replay {r} center")
 
 
 # ------------------------------------------------------------------ per-tensor multipliers
