@@ -159,7 +159,18 @@ int main(void)
             if (oracle_easgd((float *)x[i].host[t], (float *)c.host[t], alpha, counts[t])) return 1;
         if (oracle_easgd((float *)x[1].host[t], (float *)c.host[t], alpha, counts[t])) return 1;
     }
+    /* one more meeting of worker 0, on tensors 2 and 3 only, through a view of the table */
+    pxchg_table *view = NULL;
+    PX_OK(pxchg_table_view(table, 2, 2, &view));
+    if (pxchg_table_total(view) != counts[2] + counts[3] || pxchg_table_n_tensors(view) != 2) {
+        printf("the view reports the wrong size\n");
+        return 1;
+    }
+    PX_OK(pxchg_easgd(view, x[0].set, c.set, alpha, stream));
+    for (int t = 2; t < 4; ++t)
+        if (oracle_easgd((float *)x[0].host[t], (float *)c.host[t], alpha, counts[t])) return 1;
     HIP_OK(hipStreamSynchronize(stream));
+    PX_OK(pxchg_table_destroy(view));
 
     int bad = 0;
     for (int i = 0; i < K; ++i) bad |= buffer_same(&h[i], "packed gradient");
