@@ -414,6 +414,48 @@ def main() -> int:
                                       "frac_of_hbm_peak": round(ru_bytes / ms / 1e6 / HBM_PEAK_GBPS, 4),
                                       "note": "reduce+update of the whole set, one view of the table per layer"}
 
+    # ---- one rank's real share of the exchange on a k-GPU node (the transfer legs left out): it packs its own
+    # gradient (N elements), sums the k slices of N/k elements it received, and after the second leg updates
+    # all N parameters.  The slice is the leading N/k elements of the flat parameter vector.
+    share, pieces = n // k, []
+    for t_i, cnt in enumerate(counts):
+        take = min(cnt, share - sum(p[1] for p in pieces))
+        if take <= 0:
+            break
+        pieces.append((t_i, take))
+    slice_table = px.Table([take for _, take in pieces])
+    slice_in = [slice_table.bufset([pack_sets[0][i].tensors[t_i][:take] for t_i, take in pieces]) for i in range(k)]
+    slice_out = slice_table.bufset([d_avg[t_i][:take] for t_i, take in pieces])
+    own_g, own_h = [grad_sets[0][0]], [pack_sets[0][0]]
+
+    def rank_step(e=None):
+        if e:
+            e[0].record()
+        if half:
+            px.pack_fp16(table, own_g, own_h, stream=stream)
+        if e:
+            e[1].record()
+        px.reduce_avg(slice_table, slice_in, slice_out, px.AVG, stream=stream)
+        if e:
+            e[2].record()
+        px.sgd_momentum(table, s_avg, s_w, s_v, cfg.lr, cfg.mu, cfg.wd, stream=stream)
+        if e:
+            e[3].record()
+
+    for i in range(3):
+        rank_step()
+    rank_ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    for i in range(args.steps):
+        rank_step(rank_ev[i])
+    torch.cuda.synchronize()
+    r_ms = [sum(e[q].elapsed_time(e[q + 1]) for e in rank_ev) / args.steps for q in range(3)]
+    r_bytes = [6 * n if half else 0, (wire_es * k + wire_es) * share, (wire_es + 16) * n]
+    fused["one_rank_share"] = {
+        "ms": round(sum(r_ms), 5), "algorithmic_bytes": sum(r_bytes), "GBps": round(sum(r_bytes) / sum(r_ms) / 1e6, 1),
+        "stages_ms": {"pack_own": round(r_ms[0], 5), "reduce_slice": round(r_ms[1], 5), "update_all": round(r_ms[2], 5)},
+        "slice_elems": share,
+        "note": f"pack of the rank's own gradient, reduce of {k} slices of N/{k} elements, update of all N"}
+
     # ---- the whole step captured once into a HIP graph and replayed (the calls allocate nothing and record
     # no memset): what is left of a step when the host's per-call cost is gone
     graph = torch.cuda.CUDAGraph()
