@@ -50,10 +50,10 @@ HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E, published peak
 # what the same counters read for a plain copy of known size); see the files named.
 MEASURED_TRAFFIC_BYTES = {
     # stage: (bytes per launch, profile summary it comes from)
-    "pack": (2_925_996_381, "profiles/bench_alexnet_k8_hbm_counters.txt"),
-    "reduce": (1_054_199_401, "profiles/bench_alexnet_k8_hbm_counters.txt"),
-    "update": (1_075_754_895, "profiles/bench_alexnet_k8_hbm_counters.txt"),
-    "elastic": (961_011_504, "profiles/bench_alexnet_k8_hbm_counters.txt"),
+    "pack": (2_925_992_383, "profiles/bench_alexnet_k8_hbm_counters.txt"),
+    "reduce": (1_054_197_464, "profiles/bench_alexnet_k8_hbm_counters.txt"),
+    "update": (1_075_750_001, "profiles/bench_alexnet_k8_hbm_counters.txt"),
+    "elastic": (961_010_466, "profiles/bench_alexnet_k8_hbm_counters.txt"),
 }
 
 
