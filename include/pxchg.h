@@ -16,7 +16,8 @@
  *   - Plain C ABI.  Every function returns a PXCHG_* status (0 = success) unless
  *     stated otherwise; nothing throws or aborts, and only the set-up calls that
  *     say so (the two destroy calls, pxchg_table_set_multipliers) synchronise the
- *     device.
+ *     device.  The exchange calls allocate nothing, copy nothing from the host and
+ *     record no memset, so a sequence of them can be captured into a HIP graph.
  *   - "host" / "device" says where a pointer must live.  Data buffers are device
  *     memory owned by the caller; the library owns only tables and buffer sets.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
@@ -218,7 +219,8 @@ int pxchg_easgd_round(const pxchg_table *table, int k, pxchg_bufset *const *x /*
  * intermediate buffer.  `wire_dtype` says how the average would have travelled
  * on the second transfer leg: PXCHG_F16 rounds it once to binary16 and widens it
  * again before the update, PXCHG_F32 uses it as is.  Bit-identical to the two
- * separate calls with an `out` set of that type.
+ * separate calls with an `out` set of that type.  For 1 to 8 workers;
+ * PXCHG_ERR_UNSUPPORTED above that (use the two calls).
  */
 int pxchg_reduce_avg_sgd_momentum(const pxchg_table *table, int k, const pxchg_bufset *const *contrib /*host*/,
                                   int mode, int wire_dtype, pxchg_bufset *param, pxchg_bufset *vel,
@@ -236,8 +238,8 @@ int pxchg_reduce_avg_sgd_momentum(const pxchg_table *table, int k, const pxchg_b
  * `out` is DEVICE memory, 8-byte aligned, written by this call (no need to clear
  * it); it is valid once the stream has reached this point.  Two launches: one
  * that clears `out`, one that reads every element once and combines per-lane
- * partial results across each wavefront before a single atomic update per
- * wavefront.  nonfinite and max_abs are exact; sum_sq is summed in no fixed
+ * partial results across each wavefront, then across the wavefronts of a
+ * workgroup, before one atomic update per workgroup.  nonfinite and max_abs are exact; sum_sq is summed in no fixed
  * order, so it is reproducible only to binary64 rounding (like any binary64 sum
  * of n non-negative terms it is within n * 2^-53 relative of the exact sum, and
  * in practice within 1e-12).
