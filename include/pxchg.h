@@ -219,8 +219,8 @@ int pxchg_easgd_round(const pxchg_table *table, int k, pxchg_bufset *const *x /*
  * intermediate buffer.  `wire_dtype` says how the average would have travelled
  * on the second transfer leg: PXCHG_F16 rounds it once to binary16 and widens it
  * again before the update, PXCHG_F32 uses it as is.  Bit-identical to the two
- * separate calls with an `out` set of that type.  For 1 to 8 workers;
- * PXCHG_ERR_UNSUPPORTED above that (use the two calls).
+ * separate calls with an `out` set of that type.  1 to 8 workers take kernels
+ * specialised for that number, 9 to PXCHG_MAX_K a general one.
  */
 int pxchg_reduce_avg_sgd_momentum(const pxchg_table *table, int k, const pxchg_bufset *const *contrib /*host*/,
                                   int mode, int wire_dtype, pxchg_bufset *param, pxchg_bufset *vel,

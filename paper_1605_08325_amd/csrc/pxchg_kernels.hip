@@ -674,6 +674,101 @@ __global__ __launch_bounds__((fused_lanes<K, TI>())) void pxchg_reduce_avg_sgd_m
     }
 }
 
+// Any k up to PXCHG_MAX_K (more than 8 workers): the chunk's k source pointers sit in LDS and the sum is
+// formed while loading, four contributions at a time, as in the any-k reduce.  Two wavefronts of 4-element
+// lanes per chunk.
+template <typename TI, bool WIRE16, int NT, int U>
+struct FusedOpAnyK {
+    const TI *const *src;  // LDS
+    float *w, *v;
+    int k, use_div;
+    float kf, scale, lr, mu, wd;
+    __device__ __forceinline__ static float wire(float a) {
+        if constexpr (WIRE16)
+            return (float)(_Float16)a;
+        else
+            return a;
+    }
+    __device__ __forceinline__ void scalar(int i) const {
+        float s = load1(src[0] + i);
+        for (int q = 1; q < k; ++q) s = s + load1(src[q] + i);
+        float wi = load1(w + i), vi = load1(v + i);
+        momentum_step(wire(scale_sum(s, use_div, kf, scale)), wi, vi, lr, mu, wd);
+        store1(v + i, vi);
+        store1(w + i, wi);
+    }
+    struct State {
+        FV<U> s, ww, vv;
+    };
+    template <bool SP>
+    __device__ __forceinline__ void load(State &st, int i) const {
+        st.ww = loadv<NT, U, SP>(w + i);
+        st.vv = loadv<NT, U, SP>(v + i);
+        FV<U> s = loadv<NT, U, SP>(src[0] + i);
+        int q = 1;
+        for (; q + 4 <= k; q += 4) {
+            FV<U> c[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) c[r] = loadv<NT, U, SP>(src[q + r] + i);
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+#pragma unroll
+                for (int e = 0; e < U; ++e) s.v[e] = s.v[e] + c[r].v[e];  // worker order
+        }
+        for (; q < k; ++q) {
+            const FV<U> c = loadv<NT, U, SP>(src[q] + i);
+#pragma unroll
+            for (int e = 0; e < U; ++e) s.v[e] = s.v[e] + c.v[e];
+        }
+        st.s = s;
+    }
+    __device__ __forceinline__ void compute(State &st) const {
+        scale_sumv(st.s, use_div, kf, scale);
+#pragma unroll
+        for (int e = 0; e < U; ++e) momentum_step(wire(st.s.v[e]), st.ww.v[e], st.vv.v[e], lr, mu, wd);
+    }
+    template <bool SP>
+    __device__ __forceinline__ void store(const State &st, int i) const {
+        storev<NT, U, SP>(v + i, st.vv);
+        storev<NT, U, SP>(w + i, st.ww);
+    }
+};
+
+template <typename TI, bool WIRE16, int NT>
+__global__ __launch_bounds__(128) void pxchg_reduce_avg_sgd_momentum_anyk_kernel(const PxChunk *__restrict__ chunks,
+                                                                                 int n_chunks, FusedArgs args) {
+    constexpr int NTH = 128, U = 4;
+    __shared__ const TI *sp[PXCHG_MAX_K];
+    __shared__ int s_head;
+    for (int c = blockIdx.x; c < n_chunks; c += gridDim.x) {
+        const PxChunk ch = chunks[c];
+        FusedOpAnyK<TI, WIRE16, NT, U> op;
+        op.w = table_ptr<float>(args.param, ch.tensor) + ch.start;
+        op.v = table_ptr<float>(args.vel, ch.tensor) + ch.start;
+        op.k = args.k;
+        op.use_div = args.use_div;
+        op.kf = args.kf;
+        op.scale = args.scale;
+        op.lr = args.lr;
+        op.mu = args.mu;
+        op.wd = args.wd;
+        tensor_rates(args.mult, ch.tensor, op.lr, op.wd);
+        const int head0 = head_of((uintptr_t)op.w, 4);
+        __syncthreads();  // previous chunk's readers are done with sp
+        if (threadIdx.x == 0)
+            s_head = (misalign_after<U>((uintptr_t)op.w, 4, head0) | misalign_after<U>((uintptr_t)op.v, 4, head0)) ? -1 : head0;
+        __syncthreads();
+        if ((int)threadIdx.x < args.k) {
+            const TI *p = table_ptr<const TI>(args.contrib[threadIdx.x], ch.tensor) + ch.start;
+            sp[threadIdx.x] = p;
+            if (misalign_after<U>((uintptr_t)p, sizeof(TI), head0)) s_head = -1;  // benign race: all write -1
+        }
+        __syncthreads();
+        op.src = sp;
+        run_chunk<U, false, NTH>(op, ch.len, s_head, threadIdx.x);
+    }
+}
+
 // ---------------------------------------------------------------- elastic averaging
 
 // Lanes per 512-element chunk in the elastic kernels: a wavefront should load 2..4 KiB in all, so the more
@@ -1035,7 +1130,21 @@ int launch_fused(const pxchg_table *t, int k, const FusedArgs &a, bool wire16, h
         case 6: launch_fused_k<6, TI>(t, l, a, wire16, stream); break;
         case 7: launch_fused_k<7, TI>(t, l, a, wire16, stream); break;
         case 8: launch_fused_k<8, TI>(t, l, a, wire16, stream); break;
-        default: return PXCHG_ERR_UNSUPPORTED;
+        default: {
+#define PX_CALL16(N)                                                                                         \
+    hipLaunchKernelGGL((pxchg_reduce_avg_sgd_momentum_anyk_kernel<TI, true, N>), l.grid, dim3(128), 0, stream, \
+                       t->d_chunks, (int)t->n_chunks, a)
+#define PX_CALL32(N)                                                                                          \
+    hipLaunchKernelGGL((pxchg_reduce_avg_sgd_momentum_anyk_kernel<TI, false, N>), l.grid, dim3(128), 0, stream, \
+                       t->d_chunks, (int)t->n_chunks, a)
+            if (wire16) {
+                PX_DISPATCH_NT(l.nt, PX_CALL16)
+            } else {
+                PX_DISPATCH_NT(l.nt, PX_CALL32)
+            }
+#undef PX_CALL16
+#undef PX_CALL32
+        }
     }
     return after_launch();
 }
@@ -1156,7 +1265,6 @@ int pxchg_reduce_avg_sgd_momentum(const pxchg_table *table, int k, const pxchg_b
     if (mode != PXCHG_AVG && mode != PXCHG_SUM) return PXCHG_ERR_INVALID_ARG;
     if (wire_dtype != PXCHG_F32 && wire_dtype != PXCHG_F16) return PXCHG_ERR_INVALID_ARG;
     if (k < 1 || k > PXCHG_MAX_K) return PXCHG_ERR_UNSUPPORTED;
-    if (k > 8) return PXCHG_ERR_UNSUPPORTED;  // the fused form is specialised for 1..8 workers
     if ((rc = check_set(table, param, PXCHG_F32))) return rc;
     if ((rc = check_set(table, vel, PXCHG_F32))) return rc;
     if (param == vel) return PXCHG_ERR_INVALID_ARG;

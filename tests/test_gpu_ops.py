@@ -289,7 +289,7 @@ def test_update_and_elastic_special_values(px, oracle_mod):
 
 # ------------------------------------------------------------------ fused reduce + update
 
-@pytest.mark.parametrize("k", [1, 2, 3, 8])
+@pytest.mark.parametrize("k", [1, 2, 3, 8, 9, 13, 64])
 @pytest.mark.parametrize("in_dt", [np.float32, np.float16])
 @pytest.mark.parametrize("wire", ["f32", "f16"])
 def test_fused_reduce_update_equals_two_calls_and_oracle(px, oracle_mod, k, in_dt, wire):
@@ -336,7 +336,7 @@ def test_easgd_pair(px, oracle_mod, offset):
     assert_bits_equal(to_host(d_c), c, "c")
 
 
-@pytest.mark.parametrize("k", [1, 2, 3, 4, 8])
+@pytest.mark.parametrize("k", [1, 2, 3, 4, 8, 11])
 @pytest.mark.parametrize("in_dt", [np.float32, np.float16])
 @pytest.mark.parametrize("offsets", [(1, 1, 1), (2, 2, 2), (2, 1, 1), (0, 1, 0)])
 def test_fused_reduce_update_misaligned(px, oracle_mod, k, in_dt, offsets):

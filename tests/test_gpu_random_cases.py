@@ -80,7 +80,7 @@ def test_random_case(px, oracle_mod, case):
         px.reduce_avg(table, s_c, s_out, mode)
         avg = oracle_mod.reduce_avg_tensors(contrib, out_dt, mode)
         assert_bits_equal(to_host(d_out), avg, "reduce")
-        # update, staged and (k <= 8) fused
+        # update, staged and fused
         w, v = _draw(rng, counts, np.float32, 0.05), _draw(rng, counts, np.float32, 0.001)
         w2, v2 = [a.copy() for a in w], [a.copy() for a in v]
         d_w, d_v = to_device(w, off()), to_device(v, off())
@@ -88,12 +88,11 @@ def test_random_case(px, oracle_mod, case):
         oracle_mod.sgd_momentum_tensors(avg, w, v, lr, mu, wd)
         assert_bits_equal(to_host(d_w), w, "w")
         assert_bits_equal(to_host(d_v), v, "v")
-        if k <= 8:
-            d_w2, d_v2 = to_device(w2, off()), to_device(v2, off())
-            wire = px.F16 if out_dt == np.float16 else px.F32
-            px.reduce_avg_sgd_momentum(table, s_c, table.bufset(d_w2), table.bufset(d_v2), lr, mu, wd, mode, wire)
-            assert_bits_equal(to_host(d_w2), w, "fused w")
-            assert_bits_equal(to_host(d_v2), v, "fused v")
+        d_w2, d_v2 = to_device(w2, off()), to_device(v2, off())
+        wire = px.F16 if out_dt == np.float16 else px.F32
+        px.reduce_avg_sgd_momentum(table, s_c, table.bufset(d_w2), table.bufset(d_v2), lr, mu, wd, mode, wire)
+        assert_bits_equal(to_host(d_w2), w, "fused w")
+        assert_bits_equal(to_host(d_v2), v, "fused v")
         # elastic: a fused round, then one more meeting of the last worker
         xs = [_draw(rng, counts, np.float32) for _ in range(k)]
         c = _draw(rng, counts, np.float32)
