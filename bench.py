@@ -50,10 +50,10 @@ HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E, published peak
 # what the same counters read for a plain copy of known size); see the files named.
 MEASURED_TRAFFIC_BYTES = {
     # stage: (bytes per launch, profile summary it comes from)
-    "pack": (2_925_992_383, "profiles/bench_alexnet_k8_hbm_counters.txt"),
-    "reduce": (1_054_197_464, "profiles/bench_alexnet_k8_hbm_counters.txt"),
-    "update": (1_075_750_001, "profiles/bench_alexnet_k8_hbm_counters.txt"),
-    "elastic": (961_010_466, "profiles/bench_alexnet_k8_hbm_counters.txt"),
+    "pack": (2_925_961_070, "profiles/bench_alexnet_k8_hbm_counters.txt"),
+    "reduce": (1_054_182_083, "profiles/bench_alexnet_k8_hbm_counters.txt"),
+    "update": (1_075_740_713, "profiles/bench_alexnet_k8_hbm_counters.txt"),
+    "elastic": (960_996_176, "profiles/bench_alexnet_k8_hbm_counters.txt"),
 }
 
 
