@@ -95,14 +95,17 @@ __device__ __forceinline__ V ldv(const PX_GLOBAL V *p) {
 }
 // Streaming store with agent scope ("sc1 nt"): measured 1-4 % faster than the plain non-temporal store on the
 // kernels that write half of their traffic.  The compiler has no builtin that sets both bits on a 16-byte
-// vector store, hence the instruction is written out; the trailing s_nop covers the one wait state the
-// hardware wants between a wide store and a later write of its data registers, which the compiler cannot
-// see through inline assembly.
+// vector store, hence the instruction is written out.  A store of more than 8 bytes reads its data registers
+// over several cycles, and this chip family wants TWO wait states before a vector-ALU instruction may overwrite
+// them; the compiler inserts those for its own stores but cannot see through inline assembly, hence the
+// trailing `s_nop 1` (N + 1 wait states) after the 16-byte form.  (With one wait state a kernel shape tried
+// during tuning, six such stores in a row, stored 16 wrong elements in 70,001; no shipped shape did, but that
+// was luck.)  The 8-byte form needs none; its `s_nop 0` is a margin.
 template <typename V>
 __device__ __forceinline__ void store_sc1_nt(PX_GLOBAL V *p, V x) {
     static_assert(sizeof(V) == 16 || sizeof(V) == 8 || sizeof(V) == 4, "dwordx4, dwordx2 or dword");
     if constexpr (sizeof(V) == 16)
-        asm volatile("global_store_dwordx4 %0, %1, off sc1 nt\n\ts_nop 0" ::"v"(p), "v"(x) : "memory");
+        asm volatile("global_store_dwordx4 %0, %1, off sc1 nt\n\ts_nop 1" ::"v"(p), "v"(x) : "memory");
     else if constexpr (sizeof(V) == 8)
         asm volatile("global_store_dwordx2 %0, %1, off sc1 nt\n\ts_nop 0" ::"v"(p), "v"(x) : "memory");
     else
@@ -114,7 +117,7 @@ template <typename V>
 __device__ __forceinline__ void store_sc1(PX_GLOBAL V *p, V x) {
     static_assert(sizeof(V) == 16 || sizeof(V) == 8 || sizeof(V) == 4, "dwordx4, dwordx2 or dword");
     if constexpr (sizeof(V) == 16)
-        asm volatile("global_store_dwordx4 %0, %1, off sc1\n\ts_nop 0" ::"v"(p), "v"(x) : "memory");
+        asm volatile("global_store_dwordx4 %0, %1, off sc1\n\ts_nop 1" ::"v"(p), "v"(x) : "memory");
     else if constexpr (sizeof(V) == 8)
         asm volatile("global_store_dwordx2 %0, %1, off sc1\n\ts_nop 0" ::"v"(p), "v"(x) : "memory");
     else
