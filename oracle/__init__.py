@@ -68,6 +68,10 @@ def lib() -> ctypes.CDLL:
         L.oracle_stats.argtypes = [vp, ctypes.c_int, i64, ctypes.POINTER(ctypes.c_uint64),
                                    ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_double)]
         L.oracle_stats.restype = ctypes.c_int
+        L.oracle_stats_ordered.argtypes = [ctypes.c_int, ctypes.POINTER(vp), ctypes.POINTER(i64), ctypes.c_int, i64,
+                                           ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.POINTER(ctypes.c_uint64),
+                                           ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_double)]
+        L.oracle_stats_ordered.restype = ctypes.c_int
         _lib = L
     return _lib
 
@@ -172,6 +176,23 @@ def stats_tensors(ts):
         b, m, s2 = stats(t)
         bad, mx, ss = bad + b, max(mx, m), ss + s2
     return bad, mx, ss
+
+
+def stats_ordered_tensors(ts, chunk_elems: int, waves: int, block_chunks: int, combine_threads: int):
+    """(non-finite count, largest finite magnitude, sum of squares in the fixed tree order that the four
+    parameters define) over a tensor list; see oracle_stats_ordered in the C file for the order."""
+    n = len(ts)
+    dt = ts[0].dtype
+    for t in ts:
+        _chk(t, dt)
+    ptrs = (ctypes.c_void_p * n)(*[t.ctypes.data if t.size else None for t in ts])
+    counts = (ctypes.c_int64 * n)(*[t.size for t in ts])
+    bad, mx, ss = ctypes.c_uint64(0), ctypes.c_float(0), ctypes.c_double(0)
+    rc = lib().oracle_stats_ordered(n, ptrs, counts, _dtype_of(ts[0]), chunk_elems, waves, block_chunks,
+                                    combine_threads, ctypes.byref(bad), ctypes.byref(mx), ctypes.byref(ss))
+    if rc:
+        raise ValueError("oracle_stats_ordered rejected its arguments")
+    return int(bad.value), float(mx.value), float(ss.value)
 
 
 # -- tensor lists: a plain loop over tensors ---------------------------------------

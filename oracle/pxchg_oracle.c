@@ -27,9 +27,13 @@
  * sum against exact rational arithmetic and order-sensitive hand cases; the
  * momentum update against its closed form and torch.optim.SGD on the CPU; the
  * elastic update against conservation, midpoint and geometric-decay closed
- * forms.  No function here is unpinned.
+ * forms; the tree-ordered sum of squares against hand-derived cases in which
+ * the owner of an element (lane, wavefront, block) decides a rounding, against
+ * the index-order sum where every order is exact, and against the exactly
+ * rounded sum within the bound of a binary64 sum.  No function here is unpinned.
  */
 #include <stdint.h>
+#include <stdlib.h>
 #include <string.h>
 
 enum { ORACLE_F32 = 0, ORACLE_F16 = 1 };
@@ -226,5 +230,109 @@ int oracle_stats(const void *a, int dtype, int64_t n, uint64_t *nonfinite, float
     *nonfinite = bad;
     *max_abs = mx;
     *sum_sq = ss;
+    return 0;
+}
+
+/*
+ * The same diagnostics with the sum of squares taken in a FIXED TREE ORDER, so
+ * that a parallel implementation can reproduce it bit for bit run after run
+ * (a binary64 sum in index order cannot be parallelised without changing its
+ * rounding).  The paper defines no such quantity (Section 4 only reports what
+ * the half-precision exchange costs in accuracy); the order below is this
+ * library's definition, stated in its header, and written out here with plain
+ * loops.  `waves`, `block_chunks` and `combine_threads` are parameters of that
+ * definition, not of an implementation.
+ *
+ *   Work list.  Tensor t is cut into chunks of at most chunk_elems consecutive
+ *   elements, tensors in order, empty tensors giving none; chunks are numbered
+ *   g = 0, 1, ... over the whole list.  `block_chunks` consecutive chunks form
+ *   block b = g / block_chunks; j = g % block_chunks is the chunk's place in it.
+ *
+ *   Accumulators.  A block has waves x 64 of them, all starting at +0.
+ *   Element i of a chunk (i counted from the chunk's start) belongs to
+ *   accumulator (wave, lane) = (j % waves, (i / piece) % 64), where `piece` is
+ *   the number of elements in 16 bytes (4 for binary32, 8 for binary16).  An
+ *   accumulator takes its elements in increasing (g, i): acc = acc + x*x, the
+ *   square exact in binary64, the sum rounded once.  Elements that are not
+ *   finite are counted and add nothing.
+ *
+ *   combine(values[0..n), T), T a multiple of 64: "thread" t adds values t,
+ *   t + T, t + 2T, ... in that order onto +0; the 64 threads of each group
+ *   t / 64 then exchange in a butterfly, a[l] = a[l] + a[l ^ off] for off = 32,
+ *   16, 8, 4, 2, 1 (all 64 at once per step), after which a[0] is the group's
+ *   value; the groups' values are added in group order, starting from group 0's.
+ *
+ *   A block's sum is combine(its accumulators in (wave, lane) order, waves*64);
+ *   the result is combine(the blocks' sums in block order, combine_threads).
+ *
+ * The count and the maximum are exact in any order.
+ */
+static double ordered_combine(const double *values, int64_t n, int threads)
+{
+    double *a = (double *)calloc((size_t)threads, sizeof(double));
+    double tmp[64];
+    double total = 0.0;
+    if (!a) return -1.0;
+    for (int t = 0; t < threads; ++t)
+        for (int64_t i = t; i < n; i += threads) a[t] = a[t] + values[i];
+    for (int grp = 0; grp < threads / 64; ++grp) {
+        double *lane = a + 64 * grp;
+        for (int off = 32; off >= 1; off /= 2) {
+            for (int l = 0; l < 64; ++l) tmp[l] = lane[l] + lane[l ^ off];
+            memcpy(lane, tmp, sizeof(tmp));
+        }
+        total = (grp == 0) ? lane[0] : total + lane[0];
+    }
+    free(a);
+    return total;
+}
+
+int oracle_stats_ordered(int n_tensors, const void *const *tensors, const int64_t *counts, int dtype,
+                         int64_t chunk_elems, int waves, int block_chunks, int combine_threads,
+                         uint64_t *nonfinite, float *max_abs, double *sum_sq)
+{
+    if (n_tensors < 1 || !tensors || !counts || !nonfinite || !max_abs || !sum_sq) return 1;
+    if (dtype != ORACLE_F32 && dtype != ORACLE_F16) return 1;
+    if (chunk_elems < 1 || waves < 1 || block_chunks < 1 || combine_threads < 64 || combine_threads % 64) return 1;
+    const int piece = (dtype == ORACLE_F32) ? 4 : 8;
+    int64_t n_chunks = 0;
+    for (int t = 0; t < n_tensors; ++t) {
+        if (counts[t] < 0 || (counts[t] > 0 && !tensors[t])) return 1;
+        n_chunks += (counts[t] + chunk_elems - 1) / chunk_elems;
+    }
+    const int64_t n_blocks = (n_chunks + block_chunks - 1) / block_chunks;
+    double *block_sum = (double *)calloc((size_t)(n_blocks > 0 ? n_blocks : 1), sizeof(double));
+    double *acc = (double *)calloc((size_t)waves * 64, sizeof(double));
+    if (!block_sum || !acc) { free(block_sum); free(acc); return 1; }
+
+    uint64_t bad = 0;
+    float mx = 0.0f;
+    int64_t g = 0;                               /* running chunk number */
+    for (int t = 0; t < n_tensors; ++t) {
+        for (int64_t start = 0; start < counts[t]; start += chunk_elems, ++g) {
+            const int64_t len = counts[t] - start < chunk_elems ? counts[t] - start : chunk_elems;
+            const int j = (int)(g % block_chunks);
+            double *wave_acc = acc + 64 * (j % waves);
+            for (int64_t i = 0; i < len; ++i) {
+                float x = (dtype == ORACLE_F32) ? ((const float *)tensors[t])[start + i]
+                                                : widen(((const uint16_t *)tensors[t])[start + i]);
+                const int finite = (bits_of(x) & 0x7f800000u) != 0x7f800000u;   /* neither infinity nor NaN */
+                if (!finite) { ++bad; continue; }
+                float mag = x < 0.0f ? -x : x;
+                if (mag > mx) mx = mag;
+                double *slot = wave_acc + (i / piece) % 64;
+                *slot = *slot + (double)x * (double)x;
+            }
+            if (j == block_chunks - 1 || g == n_chunks - 1) {    /* the block is complete */
+                block_sum[g / block_chunks] = ordered_combine(acc, (int64_t)waves * 64, waves * 64);
+                memset(acc, 0, (size_t)waves * 64 * sizeof(double));
+            }
+        }
+    }
+    *nonfinite = bad;
+    *max_abs = mx;
+    *sum_sq = ordered_combine(block_sum, n_blocks, combine_threads);
+    free(block_sum);
+    free(acc);
     return 0;
 }

@@ -11,7 +11,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 SRC = os.path.join(ROOT, "oracle", "pxchg_oracle.c")
 
-FP16, REDUCE, UPDATE = "test_oracle_fp16.py", "test_oracle_reduce.py", "test_oracle_update.py"
+FP16, REDUCE, UPDATE, STATS = ("test_oracle_fp16.py", "test_oracle_reduce.py", "test_oracle_update.py",
+                               "test_oracle_stats.py")
 
 # (name, text in the oracle, replacement, pin file that must notice)
 MUTANTS = [
@@ -78,6 +79,36 @@ MUTANTS = [
      "ss = ss + (double)x * (double)x;", "ss = ss + (double)ax;", UPDATE),
     ("diagnostics square in binary32",
      "ss = ss + (double)x * (double)x;", "ss = ss + (double)(x * x);", UPDATE),
+    ("ordered sum: lane taken from the element, not from its 16-byte piece",
+     "double *slot = wave_acc + (i / piece) % 64;", "double *slot = wave_acc + i % 64;", STATS),
+    ("ordered sum: binary16 pieces as short as binary32 ones",
+     "const int piece = (dtype == ORACLE_F32) ? 4 : 8;", "const int piece = 4;", STATS),
+    ("ordered sum: lanes do not wrap after 64 pieces",
+     "double *slot = wave_acc + (i / piece) % 64;", "double *slot = wave_acc + ((i / piece) < 64 ? (i / piece) : 63);", STATS),
+    ("ordered sum: a block's chunks dealt to the waves in runs instead of round-robin",
+     "double *wave_acc = acc + 64 * (j % waves);", "double *wave_acc = acc + 64 * (int)((int64_t)j * waves / block_chunks);", STATS),
+    ("ordered sum: chunks run on across tensor boundaries",
+     "const int j = (int)(g % block_chunks);", "const int j = (int)((g - t) % block_chunks);", STATS),
+    ("ordered sum: butterfly steps in ascending order",
+     "for (int off = 32; off >= 1; off /= 2) {", "for (int off = 1; off <= 32; off *= 2) {", STATS),
+    ("ordered sum: lanes added one after the other instead of the butterfly",
+     "for (int l = 0; l < 64; ++l) tmp[l] = lane[l] + lane[l ^ off];",
+     "for (int l = 0; l < 64; ++l) tmp[l] = (l == 0 && off == 1) ? lane[0] : lane[l]; if (off == 1) for (int l = 1; l < 64; ++l) tmp[0] = tmp[0] + lane[l];", STATS),
+    ("ordered sum: group 1 added last instead of second",
+     "total = (grp == 0) ? lane[0] : total + lane[0];",
+     "total = (grp == 0) ? lane[0] : (grp == 1 ? total : total + lane[0]); "
+     "if (grp >= 1 && grp == threads / 64 - 1) total = total + a[64];", STATS),
+    ("ordered sum: a combine thread takes a run of values instead of every T-th",
+     "for (int64_t i = t; i < n; i += threads) a[t] = a[t] + values[i];",
+     "for (int64_t i = t * ((n + threads - 1) / threads); i < (t + 1) * ((n + threads - 1) / threads) && i < n; ++i) a[t] = a[t] + values[i];", STATS),
+    ("ordered sum: the last, incomplete block is dropped",
+     "if (j == block_chunks - 1 || g == n_chunks - 1) {", "if (j == block_chunks - 1) {", STATS),
+    ("ordered sum: squares taken in binary32",
+     "*slot = *slot + (double)x * (double)x;", "*slot = *slot + (double)(x * x);", STATS),
+    ("ordered sum: an element that is not finite is added",
+     "if (!finite) { ++bad; continue; }", "if (!finite) { ++bad; }", STATS),
+    ("ordered sum: largest magnitude keeps its sign",
+     "float mag = x < 0.0f ? -x : x;", "float mag = x;", STATS),
 ]
 
 
@@ -123,6 +154,6 @@ def test_the_unmodified_oracle_passes_in_the_same_harness(tmp_path):
     so = tmp_path / "liboracle.so"
     flags = [f for f in oracle.CFLAGS if f not in ("-Wall", "-Wextra")]
     subprocess.run(["gcc", *flags, SRC, "-o", str(so)], check=True)
-    for pins in (FP16, REDUCE, UPDATE):
+    for pins in (FP16, REDUCE, UPDATE, STATS):
         run = _run_pins(so, pins)
         assert run.returncode == 0, run.stdout[-2000:]
