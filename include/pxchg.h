@@ -52,7 +52,8 @@ enum pxchg_status {
     PXCHG_ERR_UNSUPPORTED = 3,    /* k outside 1..PXCHG_MAX_K, size beyond a stated limit */
     PXCHG_ERR_NO_DEVICE = 4,      /* no usable GPU, or the table's device is not current */
     PXCHG_ERR_RUNTIME = 5,        /* a HIP call failed (allocation, copy, launch) */
-    PXCHG_ERR_OUT_OF_RANGE = 6    /* a tensor does not fit inside the device allocation it points into */
+    PXCHG_ERR_OUT_OF_RANGE = 6,   /* a tensor does not fit inside the device allocation it points into */
+    PXCHG_ERR_IN_USE = 7          /* pxchg_table_destroy on a table that still has views or buffer sets */
 };
 
 enum pxchg_dtype { PXCHG_F32 = 0, PXCHG_F16 = 1 }; /* IEEE binary32 / binary16 */
@@ -66,14 +67,17 @@ enum pxchg_option {
                                     workgroups per compute unit, each looping over chunks */
     PXCHG_OPT_CHECK_RANGES = 2,  /* 1 (default): pxchg_bufset_create verifies that each tensor lies
                                     inside one device allocation */
-    PXCHG_OPT_NONTEMPORAL = 3,   /* -1 (default): each kernel's own measured-best policy; 0..3: bit 0
-                                    puts the non-temporal hint on vector loads, bit 1 on vector stores;
+    PXCHG_OPT_NONTEMPORAL = 3,   /* -1 (default): each kernel's own measured-best policy; 0: plain loads and
+                                    stores everywhere.  A tuning build of the library (compiled with
+                                    -DPXCHG_ALL_POLICIES, see PXCHG_OPT_ALL_POLICIES_BUILT) also takes 1..3:
+                                    bit 0 puts the non-temporal hint on vector loads, bit 1 on vector stores;
                                     4: non-temporal loads, and stores that are streaming with agent scope;
-                                    5: non-temporal loads, and agent-scope stores without the streaming hint.
+                                    5: non-temporal loads, and agent-scope stores without the streaming hint;
+                                    the regular build answers PXCHG_ERR_UNSUPPORTED to those.
                                     Results never depend on it.  One operand is exempt: a binary16 gradient
                                     of pxchg_sgd_momentum is always read with plain loads (it is usually the
                                     mean just written by pxchg_reduce_avg and may still be cached) */
-    PXCHG_OPT_CENTER_RESIDENT = 4  /* 0 (default): the elastic calls stream both operands; 1: they read the
+    PXCHG_OPT_CENTER_RESIDENT = 4, /* 0 (default): the elastic calls stream both operands; 1: they read the
                                     center with plain loads and write it with agent-scope stores, so that
                                     a center that fits the memory-side cache (256 MB) stays there from one
                                     meeting to the next, as on a server that does nothing but meet workers
@@ -81,6 +85,8 @@ enum pxchg_option {
                                     center is larger than that cache stream as with 0.  What is left
                                     dirty in that cache is written back during whatever runs next.
                                     Results never depend on it */
+    PXCHG_OPT_ALL_POLICIES_BUILT = 5 /* read-only: 1 if this library was compiled with every cache policy for
+                                    every kernel, 0 if only with each kernel's own and the plain one */
 };
 
 typedef struct pxchg_table pxchg_table;
@@ -121,6 +127,16 @@ int pxchg_plan_chunks(int n_tensors, const int64_t *counts /*host*/, int64_t chu
  * lists) and frees device memory; neither is allowed while any stream of the
  * process is being captured into a graph (the capture would be invalidated), so
  * destroy objects before a capture starts or after it has ended.
+ *
+ * Lifetime.  The library keeps a list of its live handles and never reads through
+ * a pointer that is not on it: a handle that was destroyed (also twice), a handle
+ * of the other kind and a pointer to anything else are PXCHG_ERR_INVALID_ARG in
+ * every call, never a crash.  A table cannot be destroyed while views of it or
+ * buffer sets on it exist: pxchg_table_destroy then changes nothing and returns
+ * PXCHG_ERR_IN_USE; destroy those first.  A buffer set belongs to the one table it
+ * was created on, not to whatever table later occupies the same address.  Calls on
+ * handles may run concurrently from several threads; create and destroy calls wait
+ * for calls in flight on other threads and exclude each other.
  */
 int pxchg_table_create(int n_tensors, const int64_t *counts /*host*/, pxchg_table **out);
 int pxchg_table_destroy(pxchg_table *table);
@@ -131,8 +147,8 @@ int pxchg_table_destroy(pxchg_table *table);
  * exchanged on its own stream as soon as its gradients exist (Section 3.2 notes that the exchange could overlap
  * with the rest of the step) without a second set of tables and buffer sets.  A view owns no device memory
  * (it points into the parent's chunk list), is created and destroyed without synchronising, uses the parent's
- * multipliers, and must be destroyed before the parent.  Views of views, buffer sets on a view and multipliers
- * on a view are PXCHG_ERR_INVALID_ARG.
+ * multipliers, and must be destroyed before the parent (which refuses to go first: PXCHG_ERR_IN_USE).  Views of
+ * views, buffer sets on a view and multipliers on a view are PXCHG_ERR_INVALID_ARG.
  */
 int pxchg_table_view(const pxchg_table *parent, int first_tensor, int n_tensors, pxchg_table **out);
 /*
@@ -205,9 +221,10 @@ int pxchg_sgd_momentum(const pxchg_table *table, const pxchg_bufset *grad, pxchg
 int pxchg_easgd(const pxchg_table *table, pxchg_bufset *x, pxchg_bufset *c, float alpha, void *stream);
 
 /*
- * A whole round of the same: workers x[0], x[1], ..., x[k-1] (host array of k
- * distinct F32 sets, in their order of arrival) meet the center one after the
- * other.  Bit-identical to k calls of pxchg_easgd in that order.  Up to 8
+ * Section 4, asynchronous mode (workers exchange with the server one after the
+ * other, first come first served, no round-robin): a whole round of such
+ * meetings.  Workers x[0], x[1], ..., x[k-1] (host array of k distinct F32 sets,
+ * in their order of arrival) meet the center one after the other.  Bit-identical to k calls of pxchg_easgd in that order.  Up to 8
  * workers take one launch that reads and writes the center once; more workers
  * take one launch per group of 8.
  */
@@ -215,6 +232,9 @@ int pxchg_easgd_round(const pxchg_table *table, int k, pxchg_bufset *const *x /*
                       float alpha, void *stream);
 
 /*
+ * Section 3.2's sum step (with the 1/k of an average) and Section 4's momentum
+ * SGD step on its result, as one operation: what the rank that owns a slice
+ * does between the two transfer legs when it also holds the parameters.
  * pxchg_reduce_avg followed by pxchg_sgd_momentum in one launch, without the
  * intermediate buffer.  `wire_dtype` says how the average would have travelled
  * on the second transfer leg: PXCHG_F16 rounds it once to binary16 and widens it
@@ -236,14 +256,38 @@ int pxchg_reduce_avg_sgd_momentum(const pxchg_table *table, int k, const pxchg_b
  *     sum_sq    = sum of squares of the finite elements, accumulated in binary64
  *                 (its square root is the L2 norm).
  * `out` is DEVICE memory, 8-byte aligned, written by this call (no need to clear
- * it); it is valid once the stream has reached this point.  Two launches: one
- * that clears `out`, one that reads every element once and combines per-lane
- * partial results across each wavefront, then across the wavefronts of a
- * workgroup, before one atomic update per workgroup.  nonfinite and max_abs are exact; sum_sq is summed in no fixed
- * order, so it is reproducible only to binary64 rounding (like any binary64 sum
- * of n non-negative terms it is within n * 2^-53 relative of the exact sum, and
- * in practice within 1e-12).
+ * it); it is valid once the stream has reached this point.
+ *
+ * All three are reproducible bit for bit, run after run and whatever else the
+ * device is doing: the sum is taken in a fixed tree order that is part of this
+ * definition.  The table's chunk list (pxchg_plan_chunks with the table's chunk
+ * size; for a view, the view's part of it), numbered g = 0, 1, ..., is cut into
+ * blocks of PXCHG_STATS_BLOCK_CHUNKS consecutive chunks.  A block has
+ * PXCHG_STATS_WAVES x 64 accumulators, each starting at +0; element i of the
+ * chunk at place j in its block goes to accumulator (wave, lane) =
+ * (j mod PXCHG_STATS_WAVES, (i div p) mod 64), p being the elements in 16 bytes
+ * (4 for F32, 8 for F16), and an accumulator takes its elements in increasing
+ * (g, i) as acc = acc + x*x (square exact, sum rounded once).  Values are then
+ * combined like this: combine(values, T): thread t of T adds values t, t + T,
+ * t + 2T, ... in that order onto +0; the 64 threads of each group t div 64
+ * exchange in a butterfly, a[l] = a[l] + a[l xor off] for off = 32, 16, 8, 4, 2,
+ * 1; the groups' a[0] are added in group order starting from group 0's.  A
+ * block's sum is combine(its accumulators in (wave, lane) order,
+ * PXCHG_STATS_WAVES * 64); sum_sq is combine(the blocks' sums in block order,
+ * PXCHG_STATS_COMBINE_THREADS).  (Like any binary64 sum of n non-negative terms
+ * it is within a few dozen units of 2^-53 relative of the exact sum.)
+ *
+ * Two launches: one workgroup per block writes the block's partial result into
+ * device memory that belongs to the table (allocated with it; views use their
+ * parent's), one workgroup then combines the partial results into `out`.  Every
+ * partial result is written before it is read, so nothing needs clearing, and
+ * there are no atomics.  Calls on one table (or its views) that may overlap on
+ * the device, on different streams, would share that memory: give such calls
+ * separate tables, or order them.
  */
+#define PXCHG_STATS_WAVES 4            /* wavefronts, and so 64-lane accumulator groups, per block */
+#define PXCHG_STATS_BLOCK_CHUNKS 64    /* consecutive chunks per block */
+#define PXCHG_STATS_COMBINE_THREADS 1024 /* T of the final combine */
 typedef struct pxchg_stats {
     uint64_t nonfinite;
     double sum_sq;

@@ -14,6 +14,8 @@ AVG, SUM = 0, 1
 F32, F16 = 0, 1
 MAX_K = 64
 OPT_CHUNK_ELEMS, OPT_BLOCKS_PER_CU, OPT_CHECK_RANGES, OPT_NONTEMPORAL, OPT_CENTER_RESIDENT = 0, 1, 2, 3, 4
+OPT_ALL_POLICIES_BUILT = 5
+ERR_IN_USE = 7
 
 _i64 = ctypes.c_int64
 _vp = ctypes.c_void_p
@@ -68,21 +70,47 @@ def library_path() -> str:
     return _LIB_PATH
 
 
+def open_library(path: str) -> ctypes.CDLL:
+    """Load a build of the library from `path` and declare its signatures.  Besides the regular libpxchg.so
+    this serves the tuning build (every cache policy compiled in), which tests and measurements load next to
+    it: tables and buffer sets remember the library that made them."""
+    if not os.path.exists(path):
+        raise ImportError(
+            f"{path} is missing: build it with `python -m paper_1605_08325_amd.build` "
+            "(hipcc, gfx950); this package has no CPU or eager fallback")
+    lib = ctypes.CDLL(path)
+    for name, (res, args) in SIGNATURES.items():
+        fn = getattr(lib, name)
+        fn.restype = res
+        fn.argtypes = args
+    return lib
+
+
 def load() -> ctypes.CDLL:
-    """Load libpxchg.so.  Raises if it has not been built: there is no fallback."""
+    """The library that new tables are made with: libpxchg.so, loaded on first use.  Raises if it has not been
+    built: there is no fallback."""
     global _lib
     if _lib is None:
-        if not os.path.exists(_LIB_PATH):
-            raise ImportError(
-                f"{_LIB_PATH} is missing: build it with `python -m paper_1605_08325_amd.build` "
-                "(hipcc, gfx950); this package has no CPU or eager fallback")
-        lib = ctypes.CDLL(_LIB_PATH)
-        for name, (res, args) in SIGNATURES.items():
-            fn = getattr(lib, name)
-            fn.restype = res
-            fn.argtypes = args
-        _lib = lib
+        _lib = open_library(_LIB_PATH)
     return _lib
+
+
+class using:
+    """Context manager: inside it, new tables (and set_option / get_option) go to `lib`, a library returned by
+    open_library()."""
+
+    def __init__(self, lib: ctypes.CDLL):
+        self._new = lib
+
+    def __enter__(self):
+        global _lib
+        self._old, _lib = _lib, self._new
+        return self._new
+
+    def __exit__(self, *exc):
+        global _lib
+        _lib = self._old
+        return False
 
 
 def status_string(status: int) -> str:
@@ -146,22 +174,29 @@ def _capturing() -> bool:
 
 
 def flush_deferred() -> int:
-    """Destroys what was put aside during captures; returns how many handles that were.  Called by itself
-    whenever an object is destroyed outside a capture."""
+    """Destroys what was put aside (during captures, or a table whose views or sets were still alive when the
+    collector took it first); returns how many handles that were.  Called by itself whenever an object is
+    destroyed outside a capture."""
     n = 0
-    while _deferred and not _capturing():
-        fname, handle = _deferred.pop()
-        getattr(load(), fname)(handle)
-        n += 1
+    if _capturing():
+        return n
+    pending, _deferred[:] = list(_deferred), []
+    # buffer sets and views before the tables they belong to
+    for lib, fname, handle in sorted(pending, key=lambda item: item[1] == "pxchg_table_destroy"):
+        if getattr(lib, fname)(handle) == ERR_IN_USE:
+            _deferred.append((lib, fname, handle))
+        else:
+            n += 1
     return n
 
 
-def _destroy(fname: str, handle) -> None:
+def _destroy(lib, fname: str, handle) -> None:
     if _capturing():
-        _deferred.append((fname, handle))
+        _deferred.append((lib, fname, handle))
         return
     flush_deferred()
-    getattr(load(), fname)(handle)
+    if getattr(lib, fname)(handle) == ERR_IN_USE:
+        _deferred.append((lib, fname, handle))      # retried when the next object dies
 
 
 class Table:
@@ -170,8 +205,9 @@ class Table:
     def __init__(self, counts: Sequence[int]):
         self.counts = [int(c) for c in counts]
         self._h = _vp()
+        self._lib = load()
         arr = (_i64 * max(len(self.counts), 1))(*self.counts)
-        _check(load().pxchg_table_create(len(self.counts), arr, ctypes.byref(self._h)), "pxchg_table_create")
+        _check(self._lib.pxchg_table_create(len(self.counts), arr, ctypes.byref(self._h)), "pxchg_table_create")
 
     @property
     def handle(self):
@@ -179,15 +215,15 @@ class Table:
 
     @property
     def total(self) -> int:
-        return int(load().pxchg_table_total(self._h))
+        return int(self._lib.pxchg_table_total(self._h))
 
     @property
     def n_tensors(self) -> int:
-        return int(load().pxchg_table_n_tensors(self._h))
+        return int(self._lib.pxchg_table_n_tensors(self._h))
 
     @property
     def n_chunks(self) -> int:
-        return int(load().pxchg_table_n_chunks(self._h))
+        return int(self._lib.pxchg_table_n_chunks(self._h))
 
     def set_multipliers(self, lr_mult: Optional[Sequence[float]] = None,
                         wd_mult: Optional[Sequence[float]] = None) -> None:
@@ -198,7 +234,7 @@ class Table:
             if len(x) != len(self.counts):
                 raise ValueError("one multiplier per tensor expected")
             return (_f * len(x))(*[float(v) for v in x])
-        _check(load().pxchg_table_set_multipliers(self._h, arr(lr_mult), arr(wd_mult)), "pxchg_table_set_multipliers")
+        _check(self._lib.pxchg_table_set_multipliers(self._h, arr(lr_mult), arr(wd_mult)), "pxchg_table_set_multipliers")
 
     def bufset(self, tensors, dtype: Optional[int] = None) -> "BufSet":
         return BufSet(self, tensors, dtype)
@@ -209,14 +245,38 @@ class Table:
         v = Table.__new__(Table)
         v.counts = self.counts[first_tensor:first_tensor + n_tensors]
         v._h = _vp()
+        v._lib = self._lib
         v._parent = self
-        _check(load().pxchg_table_view(self._h, int(first_tensor), int(n_tensors), ctypes.byref(v._h)),
+        _check(self._lib.pxchg_table_view(self._h, int(first_tensor), int(n_tensors), ctypes.byref(v._h)),
                "pxchg_table_view")
         return v
 
+    def bucketed_views(self, min_elems: int, reverse: bool = True) -> List["Table"]:
+        """Views that together cover every tensor once, each a run of consecutive tensors with at least
+        `min_elems` elements (the last run formed may be shorter and is then merged into its neighbour): the
+        groups in which a layer-by-layer exchange should be issued, so that small layers share a launch.
+        reverse=True forms and returns the runs from the last tensor backwards, the order in which
+        back-propagation produces gradients."""
+        order = list(range(len(self.counts)))
+        if reverse:
+            order.reverse()
+        runs, cur, size = [], [], 0
+        for t in order:
+            cur.append(t)
+            size += self.counts[t]
+            if size >= min_elems:
+                runs.append(cur)
+                cur, size = [], 0
+        if cur:
+            if runs:
+                runs[-1].extend(cur)
+            else:
+                runs.append(cur)
+        return [self.view(min(r), len(r)) for r in runs]
+
     def close(self) -> None:
         if self._h:
-            _destroy("pxchg_table_destroy", self._h)
+            _destroy(self._lib, "pxchg_table_destroy", self._h)
             self._h = _vp()
 
     def __del__(self):
@@ -259,7 +319,8 @@ class BufSet:
         self.dtype = dtype
         self._h = _vp()
         arr = (_vp * max(len(ptrs), 1))(*[p or None for p in ptrs])
-        _check(load().pxchg_bufset_create(table.handle, dtype, arr, ctypes.byref(self._h)), "pxchg_bufset_create")
+        self._lib = table._lib
+        _check(self._lib.pxchg_bufset_create(table.handle, dtype, arr, ctypes.byref(self._h)), "pxchg_bufset_create")
 
     @property
     def handle(self):
@@ -271,7 +332,7 @@ class BufSet:
 
     def close(self) -> None:
         if self._h:
-            _destroy("pxchg_bufset_destroy", self._h)
+            _destroy(self._lib, "pxchg_bufset_destroy", self._h)
             self._h = _vp()
 
     def __del__(self):
@@ -288,41 +349,41 @@ def _handles(sets: Sequence[BufSet]):
 def pack_fp16(table: Table, src_f32: Sequence[BufSet], dst_f16: Sequence[BufSet], stream=None) -> None:
     if len(src_f32) != len(dst_f16):
         raise ValueError("as many destinations as sources expected")
-    _check(load().pxchg_pack_fp16(table.handle, len(src_f32), _handles(src_f32), _handles(dst_f16),
+    _check(table._lib.pxchg_pack_fp16(table.handle, len(src_f32), _handles(src_f32), _handles(dst_f16),
                                   _stream_ptr(stream)), "pxchg_pack_fp16")
 
 
 def unpack_fp16(table: Table, src_f16: Sequence[BufSet], dst_f32: Sequence[BufSet], stream=None) -> None:
     if len(src_f16) != len(dst_f32):
         raise ValueError("as many destinations as sources expected")
-    _check(load().pxchg_unpack_fp16(table.handle, len(src_f16), _handles(src_f16), _handles(dst_f32),
+    _check(table._lib.pxchg_unpack_fp16(table.handle, len(src_f16), _handles(src_f16), _handles(dst_f32),
                                     _stream_ptr(stream)), "pxchg_unpack_fp16")
 
 
 def reduce_avg(table: Table, contrib: Sequence[BufSet], out: BufSet, mode: int = AVG, stream=None) -> None:
-    _check(load().pxchg_reduce_avg(table.handle, len(contrib), _handles(contrib), out.handle, mode,
+    _check(table._lib.pxchg_reduce_avg(table.handle, len(contrib), _handles(contrib), out.handle, mode,
                                    _stream_ptr(stream)), "pxchg_reduce_avg")
 
 
 def sgd_momentum(table: Table, grad: BufSet, param: BufSet, vel: BufSet, lr: float, mu: float,
                  wd: float = 0.0, stream=None) -> None:
-    _check(load().pxchg_sgd_momentum(table.handle, grad.handle, param.handle, vel.handle, lr, mu, wd,
+    _check(table._lib.pxchg_sgd_momentum(table.handle, grad.handle, param.handle, vel.handle, lr, mu, wd,
                                      _stream_ptr(stream)), "pxchg_sgd_momentum")
 
 
 def easgd(table: Table, x: BufSet, c: BufSet, alpha: float, stream=None) -> None:
-    _check(load().pxchg_easgd(table.handle, x.handle, c.handle, alpha, _stream_ptr(stream)), "pxchg_easgd")
+    _check(table._lib.pxchg_easgd(table.handle, x.handle, c.handle, alpha, _stream_ptr(stream)), "pxchg_easgd")
 
 
 def easgd_round(table: Table, x: Sequence[BufSet], c: BufSet, alpha: float, stream=None) -> None:
-    _check(load().pxchg_easgd_round(table.handle, len(x), _handles(x), c.handle, alpha, _stream_ptr(stream)),
+    _check(table._lib.pxchg_easgd_round(table.handle, len(x), _handles(x), c.handle, alpha, _stream_ptr(stream)),
            "pxchg_easgd_round")
 
 
 def reduce_avg_sgd_momentum(table: Table, contrib: Sequence[BufSet], param: BufSet, vel: BufSet, lr: float,
                             mu: float, wd: float = 0.0, mode: int = AVG, wire_dtype: int = F32,
                             stream=None) -> None:
-    _check(load().pxchg_reduce_avg_sgd_momentum(table.handle, len(contrib), _handles(contrib), mode, wire_dtype,
+    _check(table._lib.pxchg_reduce_avg_sgd_momentum(table.handle, len(contrib), _handles(contrib), mode, wire_dtype,
                                                 param.handle, vel.handle, lr, mu, wd, _stream_ptr(stream)),
            "pxchg_reduce_avg_sgd_momentum")
 
@@ -333,7 +394,7 @@ def buffer_stats(table: Table, bufset: BufSet, out, stream=None) -> None:
     addr = out if isinstance(out, int) else out.data_ptr()
     if not isinstance(out, int) and out.numel() * out.element_size() < ctypes.sizeof(Stats):
         raise ValueError("the output needs 24 bytes")
-    _check(load().pxchg_buffer_stats(table.handle, bufset.handle, addr, _stream_ptr(stream)), "pxchg_buffer_stats")
+    _check(table._lib.pxchg_buffer_stats(table.handle, bufset.handle, addr, _stream_ptr(stream)), "pxchg_buffer_stats")
 
 
 def read_stats(out) -> Tuple[int, float, float]:

@@ -23,13 +23,23 @@ FLAGS = [
 ]
 
 
-def build_lib(verbose: bool = False) -> str:
-    """Compile every HIP source and link the shared library.  Always rebuilds."""
+ALL_POLICIES_LIB = os.path.join(ROOT, "tests", "_build", "libpxchg_allpolicies.so")
+
+
+def build_lib(verbose: bool = False, all_policies: bool = False, out: str = "") -> str:
+    """Compile every HIP source and link the shared library.  Always rebuilds.
+
+    The regular library holds each kernel with its own cache policy and with the plain one.  all_policies=True
+    makes the tuning build (every kernel with all six policies, -DPXCHG_ALL_POLICIES), which the policy tests
+    and A/B measurements load from tests/_build/; it is never the product."""
+    out = out or (ALL_POLICIES_LIB if all_policies else LIB)
+    os.makedirs(os.path.dirname(out), exist_ok=True)
+    tag = ".allpol" if all_policies else ""
     objs = []
     procs = []
     for src in SOURCES:
-        obj = os.path.join(CSRC, src.replace(".hip", ".o"))
-        cmd = [HIPCC, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+        obj = os.path.join(os.path.dirname(out) if all_policies else CSRC, src.replace(".hip", tag + ".o"))
+        cmd = [HIPCC, *FLAGS, *(["-DPXCHG_ALL_POLICIES"] if all_policies else []), "-c", os.path.join(CSRC, src), "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
         procs.append((subprocess.Popen(cmd), cmd))
@@ -37,14 +47,14 @@ def build_lib(verbose: bool = False) -> str:
     for p, cmd in procs:
         if p.wait() != 0:
             raise RuntimeError("hipcc failed: " + " ".join(cmd))
-    tmp = LIB + f".{os.getpid()}.tmp"
+    tmp = out + f".{os.getpid()}.tmp"
     link = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", tmp]
     if verbose:
         print(" ".join(link), flush=True)
     subprocess.run(link, check=True)
-    os.replace(tmp, LIB)
-    return LIB
+    os.replace(tmp, out)
+    return out
 
 
 if __name__ == "__main__":
-    print(build_lib(verbose="-v" in sys.argv))
+    print(build_lib(verbose="-v" in sys.argv, all_policies="--all-policies" in sys.argv))

@@ -4,6 +4,7 @@
 #include <algorithm>
 #include <mutex>
 #include <new>
+#include <unordered_map>
 
 #include "pxchg_internal.h"
 
@@ -12,7 +13,28 @@ namespace {
 constexpr int64_t kMinChunk = 512;
 constexpr int64_t kMaxChunk = 1 << 20;
 
+std::unordered_map<const void *, int> &registry() {
+    static std::unordered_map<const void *, int> live;
+    return live;
+}
+std::atomic<uint64_t> next_table_id{1};
+
+using Shared = std::shared_lock<std::shared_mutex>;
+using Exclusive = std::unique_lock<std::shared_mutex>;
+
 }  // namespace
+
+std::shared_mutex &px_registry_lock() {
+    static std::shared_mutex mu;
+    return mu;
+}
+
+bool px_live(const void *handle, int kind) {
+    if (!handle) return false;
+    const auto &live = registry();
+    const auto it = live.find(handle);
+    return it != live.end() && it->second == kind;
+}
 
 PxOptions &px_options() {
     static PxOptions o{{/*chunk_elems=*/512}, {/*blocks_per_cu=*/0}, {/*check_ranges=*/1}, {/*nontemporal=*/-1},
@@ -45,11 +67,12 @@ const char *pxchg_status_string(int status) {
         case PXCHG_ERR_NO_DEVICE: return "no usable GPU, or the table's device is not current";
         case PXCHG_ERR_RUNTIME: return "HIP runtime call failed";
         case PXCHG_ERR_OUT_OF_RANGE: return "tensor does not fit inside its device allocation";
+        case PXCHG_ERR_IN_USE: return "table still has views or buffer sets";
         default: return "unknown status";
     }
 }
 
-int pxchg_version(void) { return 100; }
+int pxchg_version(void) { return 200; }
 
 int pxchg_set_option(int option, int64_t value) {
     PxOptions &o = px_options();
@@ -68,6 +91,8 @@ int pxchg_set_option(int option, int64_t value) {
             return PXCHG_OK;
         case PXCHG_OPT_NONTEMPORAL:
             if (value < -1 || value > 5) return PXCHG_ERR_INVALID_ARG;
+            // policies 1..5 exist for every kernel only in a tuning build of the library
+            if (value > 0 && !px_all_policies_built()) return PXCHG_ERR_UNSUPPORTED;
             o.nontemporal = value;
             return PXCHG_OK;
         case PXCHG_OPT_CENTER_RESIDENT:
@@ -87,6 +112,7 @@ int64_t pxchg_get_option(int option) {
         case PXCHG_OPT_CHECK_RANGES: return o.check_ranges;
         case PXCHG_OPT_NONTEMPORAL: return o.nontemporal;
         case PXCHG_OPT_CENTER_RESIDENT: return o.center_resident;
+        case PXCHG_OPT_ALL_POLICIES_BUILT: return px_all_policies_built();
         default: return -1;
     }
 }
@@ -137,7 +163,7 @@ int pxchg_table_create(int n_tensors, const int64_t *counts, pxchg_table **out) 
 
     pxchg_table *t = new (std::nothrow) pxchg_table();
     if (!t) return PXCHG_ERR_RUNTIME;
-    t->magic = PX_TABLE_MAGIC;
+    t->id = next_table_id.fetch_add(1);
     t->device = device;
     t->n_tensors = n_tensors;
     t->total = total;
@@ -146,8 +172,11 @@ int pxchg_table_create(int n_tensors, const int64_t *counts, pxchg_table **out) 
     t->counts.assign(counts, counts + n_tensors);
     t->d_chunks = nullptr;
     t->d_mult = nullptr;
+    t->d_partials = nullptr;
     t->parent = nullptr;
     t->first_tensor = 0;
+    t->live_views = 0;
+    t->live_sets = 0;
 
     if (n_chunks > 0) {
         std::vector<PxChunk> h(n_chunks);
@@ -159,22 +188,30 @@ int pxchg_table_create(int n_tensors, const int64_t *counts, pxchg_table **out) 
                 h[n].tensor = i;
                 ++n;
             }
+        // the chunk list, and one partial result per block of chunks for the diagnostics (written before it is
+        // read in every call, so it needs no clearing)
         if (hipMalloc((void **)&t->d_chunks, n_chunks * sizeof(PxChunk)) != hipSuccess ||
-            hipMemcpy(t->d_chunks, h.data(), n_chunks * sizeof(PxChunk), hipMemcpyHostToDevice) != hipSuccess) {
-            (void)hipGetLastError();
+            hipMemcpy(t->d_chunks, h.data(), n_chunks * sizeof(PxChunk), hipMemcpyHostToDevice) != hipSuccess ||
+            hipMalloc((void **)&t->d_partials, px_stats_blocks(n_chunks) * sizeof(pxchg_stats)) != hipSuccess) {
             if (t->d_chunks) (void)hipFree(t->d_chunks);
-            t->magic = 0;
+            if (t->d_partials) (void)hipFree(t->d_partials);
             delete t;
             return PXCHG_ERR_RUNTIME;
         }
+    }
+    {
+        Exclusive lock(px_registry_lock());
+        registry()[t] = PX_KIND_TABLE;
     }
     *out = t;
     return PXCHG_OK;
 }
 
-int pxchg_table_view(const pxchg_table *parent, int first_tensor, int n_tensors, pxchg_table **out) {
+int pxchg_table_view(const pxchg_table *parent_c, int first_tensor, int n_tensors, pxchg_table **out) {
     if (!out) return PXCHG_ERR_INVALID_ARG;
     *out = nullptr;
+    Exclusive lock(px_registry_lock());
+    pxchg_table *parent = const_cast<pxchg_table *>(parent_c);  // only its count of live views changes
     if (!px_valid(parent) || parent->parent) return PXCHG_ERR_INVALID_ARG;  // no views of views
     if (first_tensor < 0 || n_tensors < 1 || first_tensor > parent->n_tensors - n_tensors) return PXCHG_ERR_INVALID_ARG;
     // chunks never straddle tensors, so a run of tensors is a run of chunks
@@ -187,7 +224,7 @@ int pxchg_table_view(const pxchg_table *parent, int first_tensor, int n_tensors,
     }
     pxchg_table *v = new (std::nothrow) pxchg_table();
     if (!v) return PXCHG_ERR_RUNTIME;
-    v->magic = PX_TABLE_MAGIC;
+    v->id = next_table_id.fetch_add(1);
     v->device = parent->device;
     v->n_tensors = n_tensors;
     v->total = total;
@@ -195,37 +232,42 @@ int pxchg_table_view(const pxchg_table *parent, int first_tensor, int n_tensors,
     v->n_chunks = n_chunks;
     v->counts.assign(parent->counts.begin() + first_tensor, parent->counts.begin() + first_tensor + n_tensors);
     v->d_chunks = n_chunks ? parent->d_chunks + first_chunk : nullptr;
-    v->d_mult = nullptr;  // the parent's multipliers apply (looked up at each call)
+    v->d_mult = nullptr;      // the parent's multipliers apply (looked up at each call)
+    v->d_partials = nullptr;  // and the parent's partial results
     v->parent = parent;
     v->first_tensor = first_tensor;
+    v->live_views = 0;
+    v->live_sets = 0;
+    ++parent->live_views;
+    registry()[v] = PX_KIND_TABLE;
     *out = v;
     return PXCHG_OK;
 }
 
 int pxchg_table_destroy(pxchg_table *table) {
     if (!table) return PXCHG_OK;
-    if (!px_valid(table)) return PXCHG_ERR_INVALID_ARG;
-    if (table->parent) {  // a view owns nothing on the device
-        table->magic = 0;
-        delete table;
-        return PXCHG_OK;
+    {
+        Exclusive lock(px_registry_lock());
+        if (!px_valid(table)) return PXCHG_ERR_INVALID_ARG;  // never a handle, or destroyed already
+        if (table->live_views || table->live_sets) return PXCHG_ERR_IN_USE;
+        registry().erase(table);  // from here on every call rejects the handle
+        if (table->parent) {      // a view owns nothing on the device
+            --table->parent->live_views;
+            delete table;
+            return PXCHG_OK;
+        }
     }
     int rc = PXCHG_OK;
     (void)hipDeviceSynchronize();  // launches still reading the chunk list must finish first
-    if (table->d_chunks && hipFree(table->d_chunks) != hipSuccess) {
-        (void)hipGetLastError();
-        rc = PXCHG_ERR_RUNTIME;
-    }
-    if (table->d_mult && hipFree(table->d_mult) != hipSuccess) {
-        (void)hipGetLastError();
-        rc = PXCHG_ERR_RUNTIME;
-    }
-    table->magic = 0;
+    if (table->d_chunks && hipFree(table->d_chunks) != hipSuccess) rc = PXCHG_ERR_RUNTIME;
+    if (table->d_mult && hipFree(table->d_mult) != hipSuccess) rc = PXCHG_ERR_RUNTIME;
+    if (table->d_partials && hipFree(table->d_partials) != hipSuccess) rc = PXCHG_ERR_RUNTIME;
     delete table;
     return rc;
 }
 
 int pxchg_table_set_multipliers(pxchg_table *table, const float *lr_mult, const float *wd_mult) {
+    Exclusive lock(px_registry_lock());  // no call may be reading d_mult while it changes
     if (!px_valid(table) || table->parent) return PXCHG_ERR_INVALID_ARG;  // set them on the parent
     int device = -1;
     if (hipGetDevice(&device) != hipSuccess || device != table->device) {
@@ -259,13 +301,24 @@ int pxchg_table_set_multipliers(pxchg_table *table, const float *lr_mult, const 
     return PXCHG_OK;
 }
 
-int64_t pxchg_table_total(const pxchg_table *table) { return px_valid(table) ? table->total : -1; }
-int pxchg_table_n_tensors(const pxchg_table *table) { return px_valid(table) ? table->n_tensors : -1; }
-int64_t pxchg_table_n_chunks(const pxchg_table *table) { return px_valid(table) ? table->n_chunks : -1; }
+int64_t pxchg_table_total(const pxchg_table *table) {
+    Shared lock(px_registry_lock());
+    return px_valid(table) ? table->total : -1;
+}
+int pxchg_table_n_tensors(const pxchg_table *table) {
+    Shared lock(px_registry_lock());
+    return px_valid(table) ? table->n_tensors : -1;
+}
+int64_t pxchg_table_n_chunks(const pxchg_table *table) {
+    Shared lock(px_registry_lock());
+    return px_valid(table) ? table->n_chunks : -1;
+}
 
-int pxchg_bufset_create(const pxchg_table *table, int dtype, const void *const *ptrs, pxchg_bufset **out) {
+int pxchg_bufset_create(const pxchg_table *table_c, int dtype, const void *const *ptrs, pxchg_bufset **out) {
     if (!out) return PXCHG_ERR_INVALID_ARG;
     *out = nullptr;
+    Exclusive lock(px_registry_lock());
+    pxchg_table *table = const_cast<pxchg_table *>(table_c);  // only its count of live sets changes
     if (!px_valid(table) || !ptrs) return PXCHG_ERR_INVALID_ARG;
     if (table->parent) return PXCHG_ERR_INVALID_ARG;  // buffer sets belong to the parent and serve its views
     if (dtype != PXCHG_F32 && dtype != PXCHG_F16) return PXCHG_ERR_INVALID_ARG;
@@ -295,34 +348,36 @@ int pxchg_bufset_create(const pxchg_table *table, int dtype, const void *const *
     }
     pxchg_bufset *s = new (std::nothrow) pxchg_bufset();
     if (!s) return PXCHG_ERR_RUNTIME;
-    s->magic = PX_BUFSET_MAGIC;
     s->table = table;
+    s->table_id = table->id;
     s->dtype = dtype;
     s->h_ptrs.assign(ptrs, ptrs + table->n_tensors);
     s->d_ptrs = nullptr;
     const size_t bytes = (size_t)table->n_tensors * sizeof(void *);
     if (hipMalloc((void **)&s->d_ptrs, bytes) != hipSuccess ||
         hipMemcpy(s->d_ptrs, s->h_ptrs.data(), bytes, hipMemcpyHostToDevice) != hipSuccess) {
-        (void)hipGetLastError();
         if (s->d_ptrs) (void)hipFree(s->d_ptrs);
-        s->magic = 0;
         delete s;
         return PXCHG_ERR_RUNTIME;
     }
+    ++table->live_sets;
+    registry()[s] = PX_KIND_BUFSET;
     *out = s;
     return PXCHG_OK;
 }
 
 int pxchg_bufset_destroy(pxchg_bufset *set) {
     if (!set) return PXCHG_OK;
-    if (!px_valid(set)) return PXCHG_ERR_INVALID_ARG;
+    {
+        Exclusive lock(px_registry_lock());
+        if (!px_valid(set)) return PXCHG_ERR_INVALID_ARG;  // never a handle, or destroyed already
+        registry().erase(set);
+        // its table is alive: a table cannot be destroyed while it has sets
+        --set->table->live_sets;
+    }
     int rc = PXCHG_OK;
     (void)hipDeviceSynchronize();  // launches still reading the pointer table must finish first
-    if (set->d_ptrs && hipFree(set->d_ptrs) != hipSuccess) {
-        (void)hipGetLastError();
-        rc = PXCHG_ERR_RUNTIME;
-    }
-    set->magic = 0;
+    if (set->d_ptrs && hipFree(set->d_ptrs) != hipSuccess) rc = PXCHG_ERR_RUNTIME;
     delete set;
     return rc;
 }

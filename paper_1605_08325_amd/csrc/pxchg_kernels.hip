@@ -22,6 +22,8 @@
 // definition of each operation in pxchg.h states.  binary32 -> binary16 uses the
 // hardware convert under the default round-to-nearest-even mode with binary16
 // denormals enabled; the packed round-toward-zero convert is never used.
+#include <shared_mutex>
+#include <tuple>
 #include <type_traits>
 
 #include "pxchg_internal.h"
@@ -878,8 +880,9 @@ struct StatsAcc {
 };
 
 // Branch-free: a non-finite element counts and then takes part as +0, which changes neither the maximum of
-// magnitudes nor the sum.  The square of a binary32 value is exact in binary64, so the fused multiply-add
-// gives the same bits as a product and a sum rounded one after the other.
+// magnitudes nor the sum (the accumulators are never negative, so adding +0 leaves every bit as it is).  The
+// square of a binary32 value is exact in binary64, so the fused multiply-add gives the same bits as a product
+// and a sum rounded one after the other.
 __device__ __forceinline__ void stats_take(StatsAcc &a, float x) {
     const bool nonfinite = (__float_as_uint(x) & 0x7f800000u) == 0x7f800000u;  // infinity or NaN
     const float xf = nonfinite ? 0.0f : x;
@@ -889,94 +892,51 @@ __device__ __forceinline__ void stats_take(StatsAcc &a, float x) {
     a.ss = __builtin_fma(d, d, a.ss);
 }
 
-template <typename T, int NT, int U>
-struct StatsOp {
-    const T *src;
-    StatsAcc *acc;  // this lane's running result
-    struct State {
-        FV<U> x;
-    };
-    __device__ __forceinline__ void scalar(int i) const { stats_take(*acc, load1(src + i)); }
-    template <bool SP>
-    __device__ __forceinline__ void load(State &st, int i) const { st.x = loadv<NT, U, SP>(src + i); }
-    __device__ __forceinline__ void compute(State &st) const {
-#pragma unroll
-        for (int e = 0; e < U; ++e) stats_take(*acc, st.x.v[e]);
-    }
-    template <bool SP>
-    __device__ __forceinline__ void store(const State &, int) const {}
-};
+// The sum of squares is defined with its order (pxchg.h): which lane of which wavefront of which block takes an
+// element follows from the element's place alone, never from how a launch happens to be scheduled, and the
+// partial sums are combined in a fixed tree.  So the result is the same bits on every run.
+//   * block b = chunks b*BLOCK_CHUNKS .. +BLOCK_CHUNKS-1, one workgroup of WAVES wavefronts;
+//   * the chunk at place j of its block belongs to wavefront j mod WAVES;
+//   * element i of a chunk belongs to lane (i div P) mod 64, P = elements per 16 bytes.
+// A whole 512-element chunk is therefore one 16-byte load per lane for binary16 (lane l: elements 8l..8l+7) and
+// two for float32 (4l..4l+3 and 256+4l..256+4l+3, each instruction covering a contiguous 1 KiB): the owner rule
+// is the coalesced layout.  A binary16 wavefront takes two of its chunks per trip (2 KiB of loads in flight;
+// one chunk per trip measured 9 % slower, 4 and 8 KiB 5..10 % slower).
+constexpr int STATS_WAVES = PXCHG_STATS_WAVES, STATS_BLOCK_CHUNKS = PXCHG_STATS_BLOCK_CHUNKS;
+constexpr int STATS_COMBINE_THREADS = PXCHG_STATS_COMBINE_THREADS;
+static_assert(STATS_COMBINE_THREADS % 64 == 0 && STATS_COMBINE_THREADS <= 1024, "whole wavefronts, one workgroup");
 
-__global__ void pxchg_stats_clear_kernel(pxchg_stats *out) {
-    out->nonfinite = 0;
-    out->sum_sq = 0.0;
-    out->max_abs = 0.0f;
-    out->reserved = 0;
-}
-
-// Every wavefront walks its own chunks (wavefront-stride over the chunk list, stats_group() consecutive chunks
-// at a time); every lane keeps its own count, maximum and binary64 sum of squares.  The 64 lanes of a
-// wavefront are combined with cross-lane exchanges, the wavefronts of a workgroup through LDS, and one lane
-// per workgroup issues the three atomics (atomics on one address serialise, so there must be few of them).
-// A wavefront that took one 512-element binary16 chunk per trip would have a single 1 KiB load in flight,
-// too little to cover the memory latency (9 % slower on 122 MB); so when all chunks of a group are whole
-// (512 elements) and 16-byte aligned, their loads are issued together before the first use.
-constexpr int STATS_BLOCK = 1024;
-template <typename T>
-constexpr int stats_group() {  // 2 KiB of loads in flight per wavefront (4 and 8 KiB measured 5..10 % slower)
-    return std::is_same<T, float>::value ? 1 : 2;
-}
+// Any chunk, any alignment, in the owner order: 16-byte piece q of the chunk belongs to lane q mod 64.
 template <typename T, int NT>
-__global__ __launch_bounds__(STATS_BLOCK) void pxchg_stats_kernel(const PxChunk *__restrict__ chunks, int n_chunks,
-                                                                  const void *const *set, pxchg_stats *out) {
-    constexpr int WAVES = STATS_BLOCK / 64;
+__device__ __forceinline__ void stats_chunk(StatsAcc &acc, const T *src, int len, int lane) {
+    constexpr int P = 16 / (int)sizeof(T);
+    const bool aligned = ((uintptr_t)src & 15u) == 0;
+    const int pieces = (len + P - 1) / P;
+    for (int q = lane; q < pieces; q += 64) {
+        const int i0 = q * P;
+        if (aligned && i0 + P <= len) {
+            const FV<P> x = loadv<NT, P, false>(src + i0);
+#pragma unroll
+            for (int e = 0; e < P; ++e) stats_take(acc, x.v[e]);
+        } else {
+            const int i1 = i0 + P < len ? i0 + P : len;
+            for (int i = i0; i < i1; ++i) stats_take(acc, load1(src + i));
+        }
+    }
+}
+
+// Butterfly over the 64 lanes, then the wavefronts' values in wavefront order (thread 0 holds the result).
+template <int WAVES>
+__device__ __forceinline__ void stats_combine_workgroup(StatsAcc &acc, unsigned long long &bad) {
     __shared__ unsigned long long s_bad[WAVES];
     __shared__ float s_mx[WAVES];
     __shared__ double s_ss[WAVES];
-    const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // the same in all 64 lanes: keep it scalar
-    StatsAcc acc = {0u, 0.0f, 0.0};
-    constexpr bool F32 = std::is_same<T, float>::value;
-    constexpr int G = stats_group<T>();
-    for (int64_t c0 = ((int64_t)blockIdx.x * WAVES + wave) * G; c0 < n_chunks; c0 += (int64_t)gridDim.x * WAVES * G) {
-        const int m = (int)(n_chunks - c0 < G ? n_chunks - c0 : G);
-        const T *src[G];
-        int len[G];
-        bool whole = m == G;  // uniform over the wavefront
-#pragma unroll
-        for (int g = 0; g < G; ++g) {
-            if (g < m) {
-                const PxChunk ch = chunks[c0 + g];
-                src[g] = table_ptr<const T>(set, ch.tensor) + ch.start;
-                len[g] = ch.len;
-                whole = whole && ch.len == 512 && ((uintptr_t)src[g] & 15u) == 0;
-            }
-        }
-        if (whole) {
-            // a lane's 8 elements of each chunk: 8l..8l+7 (binary16), or 4l..4l+3 and 256+4l..256+4l+3
-            FV<8> x[G];
-#pragma unroll
-            for (int g = 0; g < G; ++g) x[g] = loadv<NT, 8, F32>(src[g] + (F32 ? 4 : 8) * lane);
-#pragma unroll
-            for (int g = 0; g < G; ++g)
-#pragma unroll
-                for (int e = 0; e < 8; ++e) stats_take(acc, x[g].v[e]);
-        } else {
-            for (int g = 0; g < m; ++g) {
-                constexpr int U = F32 ? 4 : 8;  // 16 bytes per lane
-                StatsOp<T, NT, U> op;
-                op.src = src[g];
-                op.acc = &acc;
-                run_chunk<U, false, 64>(op, len[g], head_of((uintptr_t)op.src, sizeof(T)), lane);
-            }
-        }
-    }
-    unsigned long long bad = acc.bad;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) {
         bad += __shfl_xor(bad, off);
         acc.mx = fmaxf(acc.mx, __shfl_xor(acc.mx, off));
-        acc.ss += __shfl_xor(acc.ss, off);
+        acc.ss = acc.ss + __shfl_xor(acc.ss, off);
     }
     if (lane == 0) {
         s_bad[wave] = bad;
@@ -988,36 +948,110 @@ __global__ __launch_bounds__(STATS_BLOCK) void pxchg_stats_kernel(const PxChunk 
         for (int w = 1; w < WAVES; ++w) {
             bad += s_bad[w];
             acc.mx = fmaxf(acc.mx, s_mx[w]);
-            acc.ss += s_ss[w];
+            acc.ss = acc.ss + s_ss[w];
         }
-        if (bad) atomicAdd((unsigned long long *)&out->nonfinite, bad);
-        // magnitudes are non-negative, so their bit patterns order like the values
-        atomicMax((unsigned *)&out->max_abs, __float_as_uint(acc.mx));
-        atomicAdd(&out->sum_sq, acc.ss);
+    }
+}
+
+template <typename T, int NT>
+__global__ __launch_bounds__(STATS_WAVES * 64) void pxchg_stats_partial_kernel(const PxChunk *__restrict__ chunks, int n_chunks,
+                                                                               const void *const *set,
+                                                                               pxchg_stats *__restrict__ partials) {
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // the same in all 64 lanes: keep it scalar
+    constexpr bool F32 = std::is_same<T, float>::value;
+    constexpr int G = F32 ? 1 : 2;  // chunks per trip
+    const int n_blocks = (n_chunks + STATS_BLOCK_CHUNKS - 1) / STATS_BLOCK_CHUNKS;
+    for (int b = blockIdx.x; b < n_blocks; b += gridDim.x) {
+        const int first = b * STATS_BLOCK_CHUNKS;
+        const int count = n_chunks - first < STATS_BLOCK_CHUNKS ? n_chunks - first : STATS_BLOCK_CHUNKS;
+        StatsAcc acc = {0u, 0.0f, 0.0};
+        // this wavefront's chunks: places wave, wave + WAVES, ... of the block, G of them per trip
+        for (int j0 = wave; j0 < count; j0 += STATS_WAVES * G) {
+            const T *src[G];
+            int len[G];
+            bool whole = true;  // uniform over the wavefront
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                const int j = j0 + g * STATS_WAVES;
+                if (j < count) {
+                    const PxChunk ch = chunks[first + j];
+                    src[g] = table_ptr<const T>(set, ch.tensor) + ch.start;
+                    len[g] = ch.len;
+                    whole = whole && ch.len == 512 && ((uintptr_t)src[g] & 15u) == 0;
+                } else {
+                    len[g] = 0;
+                    whole = false;
+                }
+            }
+            if (whole) {
+                FV<8> x[G];
+#pragma unroll
+                for (int g = 0; g < G; ++g) x[g] = loadv<NT, 8, F32>(src[g] + (F32 ? 4 : 8) * lane);
+#pragma unroll
+                for (int g = 0; g < G; ++g)
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) stats_take(acc, x[g].v[e]);
+            } else {
+#pragma unroll
+                for (int g = 0; g < G; ++g)
+                    if (len[g] > 0) stats_chunk<T, NT>(acc, src[g], len[g], lane);
+            }
+        }
+        unsigned long long bad = acc.bad;
+        __syncthreads();  // the previous block's reader of the shared arrays is done
+        stats_combine_workgroup<STATS_WAVES>(acc, bad);
+        if (threadIdx.x == 0) {
+            pxchg_stats r;
+            r.nonfinite = bad;
+            r.sum_sq = acc.ss;
+            r.max_abs = acc.mx;
+            r.reserved = 0;
+            partials[b] = r;
+        }
+    }
+}
+
+// One workgroup: thread t takes partial results t, t + T, ... in that order, then the same tree as above.
+// With no partial result at all (an empty table) it writes zeros.
+__global__ __launch_bounds__(STATS_COMBINE_THREADS) void pxchg_stats_combine_kernel(const pxchg_stats *__restrict__ partials,
+                                                                                    int n_partials, pxchg_stats *out) {
+    StatsAcc acc = {0u, 0.0f, 0.0};
+    unsigned long long bad = 0;
+    for (int i = threadIdx.x; i < n_partials; i += STATS_COMBINE_THREADS) {
+        const pxchg_stats p = partials[i];
+        bad += p.nonfinite;
+        acc.mx = fmaxf(acc.mx, p.max_abs);
+        acc.ss = acc.ss + p.sum_sq;
+    }
+    stats_combine_workgroup<STATS_COMBINE_THREADS / 64>(acc, bad);
+    if (threadIdx.x == 0) {
+        pxchg_stats r;
+        r.nonfinite = bad;
+        r.sum_sq = acc.ss;
+        r.max_abs = acc.mx;
+        r.reserved = 0;
+        *out = r;
     }
 }
 
 // ---------------------------------------------------------------- launch helpers
 
-struct Launch {
-    dim3 grid;
-    int nt;  // 0..3: bit 0 non-temporal loads, bit 1 non-temporal stores; 4: nt loads, "sc1 nt" stores; 5: nt loads, "sc1" stores
-};
-
-// `nt_default` is the kernel's own measured-best policy, used unless the caller
-// set PXCHG_OPT_NONTEMPORAL to 0..5.
-Launch launch_shape(const pxchg_table *t, int64_t n_virtual, int nt_default) {
-    const PxOptions &o = px_options();
-    const int64_t bpc = o.blocks_per_cu, nt = o.nontemporal;
-    int64_t g = std::min<int64_t>(n_virtual, (int64_t)1 << 24);  // the kernels loop over what is left
-    if (bpc > 0) g = std::min<int64_t>(g, (int64_t)px_cu_count(t->device) * bpc);
-    Launch l;
-    l.grid = dim3((unsigned)g, 1, 1);
-    l.nt = nt < 0 ? nt_default : (int)nt;
-    return l;
+// Launches through the runtime's C entry point, whose return value is the status of THIS launch: the call
+// neither reads nor clears whatever error an earlier HIP call of the process may have left behind.
+template <typename... P, typename... A>
+int px_launch(void (*kernel)(P...), dim3 grid, dim3 block, hipStream_t stream, A... args) {
+    static_assert(sizeof...(P) == sizeof...(A), "one argument per kernel parameter");
+    std::tuple<P...> params{args...};
+    void *argv[sizeof...(P)];
+    int i = 0;
+    std::apply([&](auto &...p) { ((argv[i++] = (void *)&p), ...); }, params);
+    return hipLaunchKernel((const void *)kernel, grid, block, argv, 0, stream) == hipSuccess ? PXCHG_OK : PXCHG_ERR_RUNTIME;
 }
 
-// Measured on MI355X (AlexNet-shaped set, k = 8), A/B inside one run:
+// Cache policies: 0 plain; bit 0 non-temporal loads, bit 1 non-temporal stores; 4 non-temporal loads with
+// "sc1 nt" stores; 5 non-temporal loads with "sc1" stores.  Measured on MI355X (AlexNet-shaped set, k = 8),
+// A/B inside one run:
 //   * the non-temporal hint on loads helps every kernel (+10..17 %);
 //   * the reduce (one written byte in nine) and the widening unpack are fastest with agent-scope stores without
 //     the streaming hint (policy 5: +3..4 % over plain stores, +7 % over non-temporal stores);
@@ -1026,46 +1060,62 @@ Launch launch_shape(const pxchg_table *t, int64_t n_virtual, int nt_default) {
 //     non-temporal stores);
 //   * the update with a binary32 gradient, the fused reduce+update and the fused round of two are fastest with
 //     plain non-temporal stores (policy 3; policy 4 is 0..3 % slower there).
+// The regular build compiles each kernel with its own policy and with policy 0; a tuning build
+// (-DPXCHG_ALL_POLICIES) compiles all six for every kernel, which is what the comparisons above were made with.
 constexpr int NT_BOTH = 3, NT_LOADS_SC1NT_STORES = 4, NT_LOADS_SC1_STORES = 5;
 
-// Expands CALL(n) for the run-time cache policy n = 0..5.
-#define PX_DISPATCH_NT(nt, CALL) \
-    switch (nt) {                \
-        case 0: CALL(0); break;  \
-        case 1: CALL(1); break;  \
-        case 2: CALL(2); break;  \
-        case 3: CALL(3); break;  \
-        case 4: CALL(4); break;  \
-        default: CALL(5); break; \
+// Expands CALL(n) for the policy to use: the caller's choice (PXCHG_OPT_NONTEMPORAL) if set, else OWN.
+#ifdef PXCHG_ALL_POLICIES
+#define PX_DISPATCH_NT(OWN, CALL)                     \
+    switch (policy_for(OWN)) {                        \
+        case 0: return CALL(0);                       \
+        case 1: return CALL(1);                       \
+        case 2: return CALL(2);                       \
+        case 3: return CALL(3);                       \
+        case 4: return CALL(4);                       \
+        default: return CALL(5);                      \
     }
+#else
+#define PX_DISPATCH_NT(OWN, CALL)                     \
+    if (policy_for(OWN) == 0) return CALL(0);         \
+    return CALL(OWN);
+#endif
+
+int policy_for(int own) {
+    const int64_t nt = px_options().nontemporal;
+    return nt < 0 ? own : (int)nt;
+}
+
+dim3 grid_for(const pxchg_table *t, int64_t n_virtual) {
+    const int64_t bpc = px_options().blocks_per_cu;
+    int64_t g = std::min<int64_t>(n_virtual, (int64_t)1 << 24);  // the kernels loop over what is left
+    if (bpc > 0) g = std::min<int64_t>(g, (int64_t)px_cu_count(t->device) * bpc);
+    return dim3((unsigned)g, 1, 1);
+}
 
 int check_table(const pxchg_table *t) {
     if (!px_valid(t)) return PXCHG_ERR_INVALID_ARG;
     int device = -1;
-    if (hipGetDevice(&device) != hipSuccess || device != t->device) {
-        (void)hipGetLastError();
-        return PXCHG_ERR_NO_DEVICE;
-    }
+    if (hipGetDevice(&device) != hipSuccess || device != t->device) return PXCHG_ERR_NO_DEVICE;
     return PXCHG_OK;
 }
 
 int check_set(const pxchg_table *t, const pxchg_bufset *s, int dtype /* -1: either */) {
     if (!px_valid(s)) return PXCHG_ERR_INVALID_ARG;
-    if (s->table != px_root(t)) return PXCHG_ERR_SHAPE_MISMATCH;  // a view takes its parent's sets
+    const pxchg_table *root = px_root(t);  // a view takes its parent's sets
+    if (s->table != root || s->table_id != root->id) return PXCHG_ERR_SHAPE_MISMATCH;
     if (dtype >= 0 && s->dtype != dtype) return PXCHG_ERR_SHAPE_MISMATCH;
     return PXCHG_OK;
 }
 
-int after_launch() {
-    const hipError_t e = hipGetLastError();
-    return e == hipSuccess ? PXCHG_OK : PXCHG_ERR_RUNTIME;
-}
-
 bool is_pow2(int k) { return k > 0 && (k & (k - 1)) == 0; }
+
+using Shared = std::shared_lock<std::shared_mutex>;
 
 template <typename TI, typename TO>
 int launch_convert(const pxchg_table *t, int k, const pxchg_bufset *const *src, pxchg_bufset *const *dst,
                    int src_dtype, int dst_dtype, hipStream_t stream) {
+    Shared lock(px_registry_lock());
     int rc = check_table(t);
     if (rc) return rc;
     if (!src || !dst) return PXCHG_ERR_INVALID_ARG;
@@ -1082,107 +1132,109 @@ int launch_convert(const pxchg_table *t, int k, const pxchg_bufset *const *src, 
             if (dst[i] == dst[j]) return PXCHG_ERR_INVALID_ARG;
     if (t->n_chunks == 0) return PXCHG_OK;
     const int64_t n_virtual = t->n_chunks * k;
-    const Launch l = launch_shape(t, n_virtual, sizeof(TO) < sizeof(TI) ? NT_LOADS_SC1NT_STORES : NT_LOADS_SC1_STORES);
-#define PX_CALL(N)                                                                                            \
-    hipLaunchKernelGGL((pxchg_convert_kernel<TI, TO, N>), l.grid, dim3(64), 0, stream, t->d_chunks, \
-                       (int)t->n_chunks, n_virtual, a)
-    PX_DISPATCH_NT(l.nt, PX_CALL)
+    const dim3 grid = grid_for(t, n_virtual);
+    constexpr int OWN = sizeof(TO) < sizeof(TI) ? NT_LOADS_SC1NT_STORES : NT_LOADS_SC1_STORES;
+#define PX_CALL(N) \
+    px_launch(pxchg_convert_kernel<TI, TO, N>, grid, dim3(64), stream, (const PxChunk *)t->d_chunks, (int)t->n_chunks, n_virtual, a)
+    PX_DISPATCH_NT(OWN, PX_CALL)
 #undef PX_CALL
-    return after_launch();
 }
 
 template <int K, typename TI, typename TO>
-void launch_reduce_k(const pxchg_table *t, const Launch &l, const ReduceArgs &a, hipStream_t stream) {
-#define PX_CALL(N)                                                                                            \
-    hipLaunchKernelGGL((pxchg_reduce_avg_kernel<K, TI, TO, N>), l.grid, dim3(reduce_lanes<K, TI, TO>()), 0, stream, t->d_chunks, \
-                       (int)t->n_chunks, a)
-    PX_DISPATCH_NT(l.nt, PX_CALL)
+int launch_reduce_k(const pxchg_table *t, const ReduceArgs &a, hipStream_t stream) {
+    const dim3 grid = grid_for(t, t->n_chunks);
+#define PX_CALL(N)                                                                                                       \
+    px_launch(pxchg_reduce_avg_kernel<K, TI, TO, N>, grid, dim3(reduce_lanes<K, TI, TO>()), stream, (const PxChunk *)t->d_chunks, \
+              (int)t->n_chunks, a)
+    PX_DISPATCH_NT(NT_LOADS_SC1_STORES, PX_CALL)
 #undef PX_CALL
 }
 
 template <typename TI, typename TO>
-void launch_reduce(const pxchg_table *t, int k, const ReduceArgs &a, hipStream_t stream) {
-    const Launch l = launch_shape(t, t->n_chunks, NT_LOADS_SC1_STORES);
-    switch (k) {
-        case 1: launch_reduce_k<1, TI, TO>(t, l, a, stream); break;
-        case 2: launch_reduce_k<2, TI, TO>(t, l, a, stream); break;
-        case 3: launch_reduce_k<3, TI, TO>(t, l, a, stream); break;
-        case 4: launch_reduce_k<4, TI, TO>(t, l, a, stream); break;
-        case 5: launch_reduce_k<5, TI, TO>(t, l, a, stream); break;
-        case 6: launch_reduce_k<6, TI, TO>(t, l, a, stream); break;
-        case 7: launch_reduce_k<7, TI, TO>(t, l, a, stream); break;
-        case 8: launch_reduce_k<8, TI, TO>(t, l, a, stream); break;
-        default: {
-#define PX_CALL(N)                                                                                            \
-    hipLaunchKernelGGL((pxchg_reduce_avg_anyk_kernel<TI, TO, N>), l.grid, dim3(reduce_lanes<0, TI, TO>()), 0, stream, t->d_chunks, \
-                       (int)t->n_chunks, a)
-            PX_DISPATCH_NT(l.nt, PX_CALL)
+int launch_reduce_anyk(const pxchg_table *t, const ReduceArgs &a, hipStream_t stream) {
+    const dim3 grid = grid_for(t, t->n_chunks);
+#define PX_CALL(N)                                                                                                            \
+    px_launch(pxchg_reduce_avg_anyk_kernel<TI, TO, N>, grid, dim3(reduce_lanes<0, TI, TO>()), stream, (const PxChunk *)t->d_chunks, \
+              (int)t->n_chunks, a)
+    PX_DISPATCH_NT(NT_LOADS_SC1_STORES, PX_CALL)
 #undef PX_CALL
-        }
-    }
 }
 
-template <int K, typename TI>
-void launch_fused_k(const pxchg_table *t, const Launch &l, const FusedArgs &a, bool wire16, hipStream_t stream) {
-#define PX_CALL16(N)                                                                                          \
-    hipLaunchKernelGGL((pxchg_reduce_avg_sgd_momentum_kernel<K, TI, true, N>), l.grid, dim3(fused_lanes<K, TI>()), 0, stream, \
-                       t->d_chunks, (int)t->n_chunks, a)
-#define PX_CALL32(N)                                                                                           \
-    hipLaunchKernelGGL((pxchg_reduce_avg_sgd_momentum_kernel<K, TI, false, N>), l.grid, dim3(fused_lanes<K, TI>()), 0, stream, \
-                       t->d_chunks, (int)t->n_chunks, a)
-    if (wire16) {
-        PX_DISPATCH_NT(l.nt, PX_CALL16)
-    } else {
-        PX_DISPATCH_NT(l.nt, PX_CALL32)
-    }
-#undef PX_CALL16
-#undef PX_CALL32
-}
-
-template <typename TI>
-int launch_fused(const pxchg_table *t, int k, const FusedArgs &a, bool wire16, hipStream_t stream) {
-    const Launch l = launch_shape(t, t->n_chunks, NT_BOTH);
+template <typename TI, typename TO>
+int launch_reduce(const pxchg_table *t, int k, const ReduceArgs &a, hipStream_t stream) {
     switch (k) {
-        case 1: launch_fused_k<1, TI>(t, l, a, wire16, stream); break;
-        case 2: launch_fused_k<2, TI>(t, l, a, wire16, stream); break;
-        case 3: launch_fused_k<3, TI>(t, l, a, wire16, stream); break;
-        case 4: launch_fused_k<4, TI>(t, l, a, wire16, stream); break;
-        case 5: launch_fused_k<5, TI>(t, l, a, wire16, stream); break;
-        case 6: launch_fused_k<6, TI>(t, l, a, wire16, stream); break;
-        case 7: launch_fused_k<7, TI>(t, l, a, wire16, stream); break;
-        case 8: launch_fused_k<8, TI>(t, l, a, wire16, stream); break;
-        default: {
-#define PX_CALL16(N)                                                                                         \
-    hipLaunchKernelGGL((pxchg_reduce_avg_sgd_momentum_anyk_kernel<TI, true, N>), l.grid, dim3(128), 0, stream, \
-                       t->d_chunks, (int)t->n_chunks, a)
-#define PX_CALL32(N)                                                                                          \
-    hipLaunchKernelGGL((pxchg_reduce_avg_sgd_momentum_anyk_kernel<TI, false, N>), l.grid, dim3(128), 0, stream, \
-                       t->d_chunks, (int)t->n_chunks, a)
-            if (wire16) {
-                PX_DISPATCH_NT(l.nt, PX_CALL16)
-            } else {
-                PX_DISPATCH_NT(l.nt, PX_CALL32)
-            }
-#undef PX_CALL16
-#undef PX_CALL32
-        }
+        case 1: return launch_reduce_k<1, TI, TO>(t, a, stream);
+        case 2: return launch_reduce_k<2, TI, TO>(t, a, stream);
+        case 3: return launch_reduce_k<3, TI, TO>(t, a, stream);
+        case 4: return launch_reduce_k<4, TI, TO>(t, a, stream);
+        case 5: return launch_reduce_k<5, TI, TO>(t, a, stream);
+        case 6: return launch_reduce_k<6, TI, TO>(t, a, stream);
+        case 7: return launch_reduce_k<7, TI, TO>(t, a, stream);
+        case 8: return launch_reduce_k<8, TI, TO>(t, a, stream);
+        default: return launch_reduce_anyk<TI, TO>(t, a, stream);
     }
-    return after_launch();
+}
+
+template <int K, typename TI, bool WIRE16>
+int launch_fused_k(const pxchg_table *t, const FusedArgs &a, hipStream_t stream) {
+    const dim3 grid = grid_for(t, t->n_chunks);
+#define PX_CALL(N)                                                                                                   \
+    px_launch(pxchg_reduce_avg_sgd_momentum_kernel<K, TI, WIRE16, N>, grid, dim3(fused_lanes<K, TI>()), stream, \
+              (const PxChunk *)t->d_chunks, (int)t->n_chunks, a)
+    PX_DISPATCH_NT(NT_BOTH, PX_CALL)
+#undef PX_CALL
+}
+
+template <typename TI, bool WIRE16>
+int launch_fused_anyk(const pxchg_table *t, const FusedArgs &a, hipStream_t stream) {
+    const dim3 grid = grid_for(t, t->n_chunks);
+#define PX_CALL(N)                                                                                     \
+    px_launch(pxchg_reduce_avg_sgd_momentum_anyk_kernel<TI, WIRE16, N>, grid, dim3(128), stream, \
+              (const PxChunk *)t->d_chunks, (int)t->n_chunks, a)
+    PX_DISPATCH_NT(NT_BOTH, PX_CALL)
+#undef PX_CALL
+}
+
+template <typename TI, bool WIRE16>
+int launch_fused(const pxchg_table *t, int k, const FusedArgs &a, hipStream_t stream) {
+    switch (k) {
+        case 1: return launch_fused_k<1, TI, WIRE16>(t, a, stream);
+        case 2: return launch_fused_k<2, TI, WIRE16>(t, a, stream);
+        case 3: return launch_fused_k<3, TI, WIRE16>(t, a, stream);
+        case 4: return launch_fused_k<4, TI, WIRE16>(t, a, stream);
+        case 5: return launch_fused_k<5, TI, WIRE16>(t, a, stream);
+        case 6: return launch_fused_k<6, TI, WIRE16>(t, a, stream);
+        case 7: return launch_fused_k<7, TI, WIRE16>(t, a, stream);
+        case 8: return launch_fused_k<8, TI, WIRE16>(t, a, stream);
+        default: return launch_fused_anyk<TI, WIRE16>(t, a, stream);
+    }
+}
+
+template <int K, bool CR>
+int launch_elastic_kc(const pxchg_table *t, const ElasticArgs &a, hipStream_t stream) {
+    const dim3 grid = grid_for(t, t->n_chunks);
+    constexpr int OWN = K == 2 ? NT_BOTH : NT_LOADS_SC1NT_STORES;
+#define PX_CALL(N)                                                                                                      \
+    px_launch(pxchg_easgd_kernel<K, N, CR>, grid, dim3(elastic_lanes<K>() * elastic_pad<K>()), stream, (const PxChunk *)t->d_chunks, \
+              (int)t->n_chunks, a)
+    PX_DISPATCH_NT(OWN, PX_CALL)
+#undef PX_CALL
 }
 
 template <int K>
-void launch_elastic_k(const pxchg_table *t, const Launch &l, const ElasticArgs &a, hipStream_t stream) {
-#define PX_CALL(N) \
-    hipLaunchKernelGGL((pxchg_easgd_kernel<K, N, false>), l.grid, dim3(elastic_lanes<K>() * elastic_pad<K>()), 0, stream, t->d_chunks, (int)t->n_chunks, a)
-#define PX_CALL_CR(N) \
-    hipLaunchKernelGGL((pxchg_easgd_kernel<K, N, true>), l.grid, dim3(elastic_lanes<K>() * elastic_pad<K>()), 0, stream, t->d_chunks, (int)t->n_chunks, a)
+int launch_elastic_k(const pxchg_table *t, const ElasticArgs &a, hipStream_t stream) {
     // a center larger than the 256 MiB memory-side cache cannot stay there (measured 2.5 % slower at 553 MB)
-    if (px_options().center_resident && t->total * 4 <= ((int64_t)256 << 20)) {
-        PX_DISPATCH_NT(l.nt, PX_CALL_CR)
-    } else {
-        PX_DISPATCH_NT(l.nt, PX_CALL)
-    }
-#undef PX_CALL_CR
+    if (px_options().center_resident && t->total * 4 <= ((int64_t)256 << 20)) return launch_elastic_kc<K, true>(t, a, stream);
+    return launch_elastic_kc<K, false>(t, a, stream);
+}
+
+template <typename TG>
+int launch_update(const pxchg_table *t, const UpdateArgs &a, hipStream_t stream) {
+    const dim3 grid = grid_for(t, t->n_chunks);
+    constexpr int OWN = std::is_same<TG, _Float16>::value ? NT_LOADS_SC1NT_STORES : NT_BOTH;
+#define PX_CALL(N) \
+    px_launch(pxchg_sgd_momentum_kernel<TG, N>, grid, dim3(update_lanes<TG>()), stream, (const PxChunk *)t->d_chunks, (int)t->n_chunks, a)
+    PX_DISPATCH_NT(OWN, PX_CALL)
 #undef PX_CALL
 }
 
@@ -1200,7 +1252,33 @@ void fill_scale(int k, int mode, int *use_div, float *kf, float *scale) {
     }
 }
 
+// The two launches of the diagnostics; `partials` has room for one result per block of the table's chunk list.
+int launch_stats(const pxchg_table *table, const pxchg_bufset *set, pxchg_stats *partials, pxchg_stats *out,
+                 hipStream_t stream) {
+    const int n_blocks = (int)px_stats_blocks(table->n_chunks);
+    if (n_blocks > 0) {
+        const void *const *ptrs = (const void *const *)set->d_ptrs;
+        const dim3 grid((unsigned)n_blocks), block(STATS_WAVES * 64);
+        const int rc = set->dtype == PXCHG_F32
+                           ? px_launch(pxchg_stats_partial_kernel<float, 1>, grid, block, stream, (const PxChunk *)table->d_chunks,
+                                       (int)table->n_chunks, ptrs, partials)
+                           : px_launch(pxchg_stats_partial_kernel<_Float16, 1>, grid, block, stream,
+                                       (const PxChunk *)table->d_chunks, (int)table->n_chunks, ptrs, partials);
+        if (rc) return rc;
+    }
+    return px_launch(pxchg_stats_combine_kernel, dim3(1), dim3(STATS_COMBINE_THREADS), stream, (const pxchg_stats *)partials,
+                     n_blocks, out);
+}
+
 }  // namespace
+
+int px_all_policies_built() {
+#ifdef PXCHG_ALL_POLICIES
+    return 1;
+#else
+    return 0;
+#endif
+}
 
 extern "C" {
 
@@ -1216,6 +1294,7 @@ int pxchg_unpack_fp16(const pxchg_table *table, int k, const pxchg_bufset *const
 
 int pxchg_reduce_avg(const pxchg_table *table, int k, const pxchg_bufset *const *contrib, pxchg_bufset *out, int mode,
                      void *stream) {
+    Shared lock(px_registry_lock());
     int rc = check_table(table);
     if (rc) return rc;
     if (!contrib) return PXCHG_ERR_INVALID_ARG;
@@ -1234,15 +1313,15 @@ int pxchg_reduce_avg(const pxchg_table *table, int k, const pxchg_bufset *const 
     fill_scale(k, mode, &a.use_div, &a.kf, &a.scale);
     if (table->n_chunks == 0) return PXCHG_OK;
     hipStream_t s = (hipStream_t)stream;
-    if (in_dtype == PXCHG_F32 && out->dtype == PXCHG_F32) launch_reduce<float, float>(table, k, a, s);
-    else if (in_dtype == PXCHG_F32) launch_reduce<float, _Float16>(table, k, a, s);
-    else if (out->dtype == PXCHG_F32) launch_reduce<_Float16, float>(table, k, a, s);
-    else launch_reduce<_Float16, _Float16>(table, k, a, s);
-    return after_launch();
+    if (in_dtype == PXCHG_F32 && out->dtype == PXCHG_F32) return launch_reduce<float, float>(table, k, a, s);
+    if (in_dtype == PXCHG_F32) return launch_reduce<float, _Float16>(table, k, a, s);
+    if (out->dtype == PXCHG_F32) return launch_reduce<_Float16, float>(table, k, a, s);
+    return launch_reduce<_Float16, _Float16>(table, k, a, s);
 }
 
 int pxchg_sgd_momentum(const pxchg_table *table, const pxchg_bufset *grad, pxchg_bufset *param, pxchg_bufset *vel,
                        float lr, float mu, float wd, void *stream) {
+    Shared lock(px_registry_lock());
     int rc = check_table(table);
     if (rc) return rc;
     if ((rc = check_set(table, grad, -1))) return rc;
@@ -1259,27 +1338,15 @@ int pxchg_sgd_momentum(const pxchg_table *table, const pxchg_bufset *grad, pxchg
     a.lr = lr;
     a.mu = mu;
     a.wd = wd;
-    const Launch l = launch_shape(table, table->n_chunks, grad->dtype == PXCHG_F16 ? NT_LOADS_SC1NT_STORES : NT_BOTH);
     hipStream_t s = (hipStream_t)stream;
-#define PX_CALL32(N)                                                                                      \
-    hipLaunchKernelGGL((pxchg_sgd_momentum_kernel<float, N>), l.grid, dim3(update_lanes<float>()), 0, s, table->d_chunks,  \
-                       (int)table->n_chunks, a)
-#define PX_CALL16(N)                                                                                        \
-    hipLaunchKernelGGL((pxchg_sgd_momentum_kernel<_Float16, N>), l.grid, dim3(update_lanes<_Float16>()), 0, s, table->d_chunks, \
-                       (int)table->n_chunks, a)
-    if (grad->dtype == PXCHG_F32) {
-        PX_DISPATCH_NT(l.nt, PX_CALL32)
-    } else {
-        PX_DISPATCH_NT(l.nt, PX_CALL16)
-    }
-#undef PX_CALL32
-#undef PX_CALL16
-    return after_launch();
+    if (grad->dtype == PXCHG_F32) return launch_update<float>(table, a, s);
+    return launch_update<_Float16>(table, a, s);
 }
 
 int pxchg_reduce_avg_sgd_momentum(const pxchg_table *table, int k, const pxchg_bufset *const *contrib, int mode,
                                   int wire_dtype, pxchg_bufset *param, pxchg_bufset *vel, float lr, float mu, float wd,
                                   void *stream) {
+    Shared lock(px_registry_lock());
     int rc = check_table(table);
     if (rc) return rc;
     if (!contrib) return PXCHG_ERR_INVALID_ARG;
@@ -1308,12 +1375,14 @@ int pxchg_reduce_avg_sgd_momentum(const pxchg_table *table, int k, const pxchg_b
     a.wd = wd;
     if (table->n_chunks == 0) return PXCHG_OK;
     hipStream_t s = (hipStream_t)stream;
-    if (in_dtype == PXCHG_F32) return launch_fused<float>(table, k, a, wire_dtype == PXCHG_F16, s);
-    return launch_fused<_Float16>(table, k, a, wire_dtype == PXCHG_F16, s);
+    const bool wire16 = wire_dtype == PXCHG_F16;
+    if (in_dtype == PXCHG_F32) return wire16 ? launch_fused<float, true>(table, k, a, s) : launch_fused<float, false>(table, k, a, s);
+    return wire16 ? launch_fused<_Float16, true>(table, k, a, s) : launch_fused<_Float16, false>(table, k, a, s);
 }
 
 int pxchg_easgd_round(const pxchg_table *table, int k, pxchg_bufset *const *x, pxchg_bufset *c, float alpha,
                       void *stream) {
+    Shared lock(px_registry_lock());
     int rc = check_table(table);
     if (rc) return rc;
     if (!x) return PXCHG_ERR_INVALID_ARG;
@@ -1331,57 +1400,38 @@ int pxchg_easgd_round(const pxchg_table *table, int k, pxchg_bufset *const *x, p
     // through memory between them (same arithmetic, same order).
     for (int i0 = 0; i0 < k; i0 += 8) {
         const int kk = std::min(8, k - i0);
-        const Launch l = launch_shape(table, table->n_chunks, kk == 2 ? NT_BOTH : NT_LOADS_SC1NT_STORES);
         ElasticArgs a;
         for (int i = 0; i < kk; ++i) a.x[i] = (void *const *)x[i0 + i]->d_ptrs;
         a.c = (void *const *)c->d_ptrs;
         a.k = kk;
         a.alpha = alpha;
         switch (kk) {
-            case 1: launch_elastic_k<1>(table, l, a, s); break;
-            case 2: launch_elastic_k<2>(table, l, a, s); break;
-            case 3: launch_elastic_k<3>(table, l, a, s); break;
-            case 4: launch_elastic_k<4>(table, l, a, s); break;
-            case 5: launch_elastic_k<5>(table, l, a, s); break;
-            case 6: launch_elastic_k<6>(table, l, a, s); break;
-            case 7: launch_elastic_k<7>(table, l, a, s); break;
-            default: launch_elastic_k<8>(table, l, a, s); break;
+            case 1: rc = launch_elastic_k<1>(table, a, s); break;
+            case 2: rc = launch_elastic_k<2>(table, a, s); break;
+            case 3: rc = launch_elastic_k<3>(table, a, s); break;
+            case 4: rc = launch_elastic_k<4>(table, a, s); break;
+            case 5: rc = launch_elastic_k<5>(table, a, s); break;
+            case 6: rc = launch_elastic_k<6>(table, a, s); break;
+            case 7: rc = launch_elastic_k<7>(table, a, s); break;
+            default: rc = launch_elastic_k<8>(table, a, s); break;
         }
-        if ((rc = after_launch())) return rc;
+        if (rc) return rc;
     }
     return PXCHG_OK;
-}
-
-int pxchg_buffer_stats(const pxchg_table *table, const pxchg_bufset *set, pxchg_stats *out, void *stream) {
-    int rc = check_table(table);
-    if (rc) return rc;
-    if ((rc = check_set(table, set, -1))) return rc;
-    if (!out || ((uintptr_t)out & 7u)) return PXCHG_ERR_INVALID_ARG;
-    hipStream_t s = (hipStream_t)stream;
-    hipLaunchKernelGGL(pxchg_stats_clear_kernel, dim3(1), dim3(1), 0, s, out);
-    if ((rc = after_launch())) return rc;
-    if (table->n_chunks == 0) return PXCHG_OK;
-    // two 16-wavefront workgroups per compute unit, each wavefront looping over chunks: the card is full,
-    // and only three atomics per workgroup reach `out`
-    const int waves = STATS_BLOCK / 64 * (set->dtype == PXCHG_F32 ? stats_group<float>() : stats_group<_Float16>());
-    // `waves` chunks per workgroup and trip; a small set gets fewer workgroups of four trips each rather than
-    // one trip in many, because every workgroup ends in atomics on the one result (14 MB: 15 -> 10 us)
-    const int64_t per_wg = (int64_t)waves * 4;
-    const int64_t need = (table->n_chunks + per_wg - 1) / per_wg;
-    const dim3 grid((unsigned)std::min<int64_t>(need, (int64_t)px_cu_count(table->device) * 2));
-    const void *const *ptrs = (const void *const *)set->d_ptrs;
-    if (set->dtype == PXCHG_F32)
-        hipLaunchKernelGGL((pxchg_stats_kernel<float, 1>), grid, dim3(STATS_BLOCK), 0, s, table->d_chunks,
-                           (int)table->n_chunks, ptrs, out);
-    else
-        hipLaunchKernelGGL((pxchg_stats_kernel<_Float16, 1>), grid, dim3(STATS_BLOCK), 0, s, table->d_chunks,
-                           (int)table->n_chunks, ptrs, out);
-    return after_launch();
 }
 
 int pxchg_easgd(const pxchg_table *table, pxchg_bufset *x, pxchg_bufset *c, float alpha, void *stream) {
     pxchg_bufset *xs[1] = {x};
     return pxchg_easgd_round(table, 1, xs, c, alpha, stream);
+}
+
+int pxchg_buffer_stats(const pxchg_table *table, const pxchg_bufset *set, pxchg_stats *out, void *stream) {
+    Shared lock(px_registry_lock());
+    int rc = check_table(table);
+    if (rc) return rc;
+    if ((rc = check_set(table, set, -1))) return rc;
+    if (!out || ((uintptr_t)out & 7u)) return PXCHG_ERR_INVALID_ARG;
+    return launch_stats(table, set, px_root(table)->d_partials, out, (hipStream_t)stream);
 }
 
 }  // extern "C"

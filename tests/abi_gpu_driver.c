@@ -190,10 +190,24 @@ int main(void)
         bad = 1;
     }
 
+    /* lifetime: a table with live buffer sets refuses to go, and stays usable */
+    if (pxchg_table_destroy(table) != PXCHG_ERR_IN_USE) {
+        printf("a table with live buffer sets was destroyed\n");
+        return 1;
+    }
+    if (pxchg_table_total(table) < 0) {
+        printf("the table did not survive the refused destroy\n");
+        bad = 1;
+    }
+
     for (int i = 0; i < K; ++i)
         if (buffer_free(&g[i]) || buffer_free(&h[i]) || buffer_free(&x[i])) return 1;
     if (buffer_free(&mean) || buffer_free(&w) || buffer_free(&v) || buffer_free(&c)) return 1;
     PX_OK(pxchg_table_destroy(table));
+    if (pxchg_table_destroy(table) != PXCHG_ERR_INVALID_ARG || pxchg_table_total(table) != -1) {
+        printf("a destroyed table was not rejected\n");
+        bad = 1;
+    }
     HIP_OK(hipStreamDestroy(stream));
     if (bad) return 1;
     printf("ok\n");

@@ -67,9 +67,9 @@ def test_package_does_not_import_the_oracle():
 
 
 def test_status_strings_and_version(px):
-    assert px.version() >= 100
+    assert px.version() >= 200
     assert px.status_string(0) == "ok"
-    for s in range(1, 7):
+    for s in range(1, 8):
         assert px.status_string(s) not in ("ok", "unknown status")
     assert px.status_string(99) == "unknown status"
 

@@ -1,9 +1,13 @@
 """GPU parity on the five benchmark configurations at their full sizes, in the
-default launch configuration (the one bench.py times).  One-step configurations
-are compared on every element; the multi-step loops are compared on a fixed
-sample of elements per tensor (the operations are element-wise, so the oracle
-run on the gathered sample is the same arithmetic), which always includes each
-tensor's first and last elements and the elements around chunk boundaries."""
+default launch configuration (the one bench.py times).  Every configuration is
+compared with the oracle on EVERY element at least once (one whole step, or one
+whole elastic round).  The multi-step loops then go on against the oracle on a
+fixed sample of elements per tensor (the operations are element-wise, so the
+oracle run on the gathered sample is the same arithmetic; the sample always
+includes each tensor's first and last elements and the elements around chunk
+boundaries), and their final state is compared on every element, GPU against
+GPU, with the same loop run through the library's other code path (fused
+reduce+update against the two calls, k single meetings against fused rounds)."""
 import numpy as np
 import pytest
 
@@ -58,6 +62,10 @@ def sync_exchange(px, oracle_mod, cfg, steps, full):
     sw, sv = table.bufset(d_w), table.bufset(d_v)
     d_avg = empty_like_device(counts, wire)
     s_avg = table.bufset(d_avg)
+    twin = steps > 1          # a second copy of the state, stepped by the fused call: compared on every element
+    if twin:
+        d_w2, d_v2 = to_device(w), to_device(v)
+        sw2, sv2 = table.bufset(d_w2), table.bufset(d_v2)
     idx = None if full else sample_indices(counts, 20_000, cfg.seed, px.get_option(px.OPT_CHUNK_ELEMS))
     if idx is not None:
         w, v = gather(w, idx), gather(v, idx)
@@ -74,6 +82,9 @@ def sync_exchange(px, oracle_mod, cfg, steps, full):
             contrib_sets = s_g
         px.reduce_avg(table, contrib_sets, s_avg)
         px.sgd_momentum(table, s_avg, sw, sv, cfg.lr, cfg.mu, cfg.wd)
+        if twin:
+            px.reduce_avg_sgd_momentum(table, contrib_sets, sw2, sv2, cfg.lr, cfg.mu, cfg.wd, px.AVG,
+                                       px.F16 if half else px.F32)
         torch.cuda.synchronize()
         # oracle on all elements, or on the gathered sample
         if idx is not None:
@@ -93,6 +104,10 @@ def sync_exchange(px, oracle_mod, cfg, steps, full):
     assert_close_params(got_w, w, cfg.name)          # the stated tolerance
     assert_bits_equal(got_w, w, f"{cfg.name} params")  # and in fact bit-exact
     assert_bits_equal(got_v, v, f"{cfg.name} velocity")
+    if twin:
+        for t in range(len(counts)):
+            assert torch.equal(d_w[t].view(torch.int32), d_w2[t].view(torch.int32)), f"{cfg.name} fused twin, w[{t}]"
+            assert torch.equal(d_v[t].view(torch.int32), d_v2[t].view(torch.int32)), f"{cfg.name} fused twin, v[{t}]"
 
 
 def test_config1_tiny_sync(px, oracle_mod):
@@ -118,29 +133,52 @@ def test_config4_many_small_tensors_one_launch_per_stage(px, oracle_mod):
     sync_exchange(px, oracle_mod, cfg, steps=2, full=True)
 
 
-def test_config5_easgd_100_rounds_sampled(px, oracle_mod):
+def test_config5_easgd_100_rounds(px, oracle_mod):
+    """Round 1 on every element against the oracle (single meetings, and the fused round on a second copy of the
+    state); all 100 rounds against the oracle on the sample; after the last round the two copies, one stepped by
+    single meetings and fused rounds half and half, the other the other way round, agree on every element."""
     import torch
     cfg = wl.config(5)
     counts = list(cfg.counts)
     table = px.Table(counts)
-    xs = wl.gaussian_workers(counts, cfg.param_sigma, cfg.seed, "worker", cfg.k)
-    c = wl.gaussian_tensors(counts, cfg.param_sigma, cfg.seed, "center")
-    d_xs = [to_device(x) for x in xs]
-    d_c = to_device(c)
-    s_xs = [table.bufset(x) for x in d_xs]
-    s_c = table.bufset(d_c)
+    xs = [[a.copy() for a in x] for x in wl.gaussian_workers(counts, cfg.param_sigma, cfg.seed, "worker", cfg.k)]
+    c = [a.copy() for a in wl.gaussian_tensors(counts, cfg.param_sigma, cfg.seed, "center")]
+    d_xs, d_c = [to_device(x) for x in xs], to_device(c)
+    d_xs2, d_c2 = [to_device(x) for x in xs], to_device(c)
+    s_xs, s_c = [table.bufset(x) for x in d_xs], table.bufset(d_c)
+    s_xs2, s_c2 = [table.bufset(x) for x in d_xs2], table.bufset(d_c2)
+    orders = wl.worker_orders(cfg.seed, cfg.k, cfg.rounds)
+    alpha = np.float32(cfg.alpha)
+
+    def meetings(sets, center, order):
+        for i in order:
+            px.easgd(table, sets[i], center, float(alpha))
+
+    def fused(sets, center, order):
+        px.easgd_round(table, [sets[i] for i in order], center, float(alpha))
+
+    # round 1, every element
+    meetings(s_xs, s_c, orders[0])
+    fused(s_xs2, s_c2, orders[0])
+    for i in orders[0]:
+        oracle_mod.easgd_tensors(xs[i], c, alpha)
+    torch.cuda.synchronize()
+    for i in range(cfg.k):
+        assert_bits_equal(to_host(d_xs[i]), xs[i], f"round 1, worker {i}, single meetings")
+        assert_bits_equal(to_host(d_xs2[i]), xs[i], f"round 1, worker {i}, fused round")
+    assert_bits_equal(to_host(d_c), c, "round 1, center, single meetings")
+    assert_bits_equal(to_host(d_c2), c, "round 1, center, fused round")
+
+    # rounds 2..100 against the oracle on the sample
     idx = sample_indices(counts, 20_000, cfg.seed, px.get_option(px.OPT_CHUNK_ELEMS))
     xs = [gather(x, idx) for x in xs]
     c = gather(c, idx)
-    orders = wl.worker_orders(cfg.seed, cfg.k, cfg.rounds)
-    alpha = np.float32(cfg.alpha)
-    # first half of the rounds as single worker-center meetings, second half as fused rounds
     for r, order in enumerate(orders):
-        if r < cfg.rounds // 2:
-            for i in order:
-                px.easgd(table, s_xs[i], s_c, float(alpha))
-        else:
-            px.easgd_round(table, [s_xs[i] for i in order], s_c, float(alpha))
+        if r == 0:
+            continue
+        first_half = r < cfg.rounds // 2
+        (meetings if first_half else fused)(s_xs, s_c, order)
+        (fused if first_half else meetings)(s_xs2, s_c2, order)
         for i in order:
             oracle_mod.easgd_tensors(xs[i], c, alpha)
     torch.cuda.synchronize()
@@ -149,15 +187,20 @@ def test_config5_easgd_100_rounds_sampled(px, oracle_mod):
         assert_close_params(got, xs[i], f"worker {i}")
         assert_bits_equal(got, xs[i], f"worker {i}")
     assert_bits_equal(gather_device(d_c, idx), c, "center")
+    for t in range(len(counts)):
+        assert torch.equal(d_c[t].view(torch.int32), d_c2[t].view(torch.int32)), f"center[{t}], the two paths"
+        for i in range(cfg.k):
+            assert torch.equal(d_xs[i][t].view(torch.int32), d_xs2[i][t].view(torch.int32)), f"worker {i}[{t}], the two paths"
 
 
 # ------------------------------------------------------------------ the paper's other two model sizes (Table 2)
 
-def test_vggnet_shaped_k8_f16_one_step_sampled(px, oracle_mod):
-    """138,357,544 parameters in 32 tensors (Table 2's VGGNet count), same exchange as configuration 3."""
+def test_vggnet_shaped_k8_f16_one_step_all_elements(px, oracle_mod):
+    """138,357,544 parameters in 32 tensors (Table 2's VGGNet count), same exchange as configuration 3, every
+    element against the oracle."""
     base = wl.config(3)
     cfg = wl.Config("vggnet_sync_k8_f16", tuple(wl.vggnet_counts()), 8, "f16", seed=base.seed + 100)
-    sync_exchange(px, oracle_mod, cfg, steps=1, full=False)
+    sync_exchange(px, oracle_mod, cfg, steps=1, full=True)
 
 
 def test_googlenet_count_many_small_tensors_k8_f16(px, oracle_mod):
