@@ -297,6 +297,24 @@ typedef struct pxchg_stats {
 
 int pxchg_buffer_stats(const pxchg_table *table, const pxchg_bufset *set, pxchg_stats *out /*device*/, void *stream);
 
+/*
+ * The same call for callers that can allocate nothing and must not depend on memory that some earlier call
+ * allocated for them: code running under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  It differs from pxchg_buffer_stats only in where the partial results live: in a fixed array of
+ * PXCHG_STATS_STATIC_MAX_BLOCKS entries (24 bytes each, 384 KiB) that is part of the library's code object, one
+ * copy per GPU, held until the process ends.  Same arguments, same results, bit for bit.  The call allocates and
+ * frees nothing, on the device or through any library.  The array's address on the current device is looked up
+ * once per device: by pxchg_table_create, or else by the first call on that device.
+ * Limits: a chunk list of more than PXCHG_STATS_STATIC_MAX_BLOCKS * PXCHG_STATS_BLOCK_CHUNKS chunks (536,870,912
+ * elements at the default chunk size) is PXCHG_ERR_UNSUPPORTED and launches nothing; use pxchg_buffer_stats.
+ * Every call on a GPU shares that GPU's array, whatever the table: calls that may overlap on one GPU (different
+ * streams) race on it, so order them.  Nothing in the array needs clearing between calls: each call writes the
+ * entries it reads.
+ */
+#define PXCHG_STATS_STATIC_MAX_BLOCKS 16384
+int pxchg_buffer_stats_static(const pxchg_table *table, const pxchg_bufset *set, pxchg_stats *out /*device*/,
+                              void *stream);
+
 #ifdef __cplusplus
 }
 #endif

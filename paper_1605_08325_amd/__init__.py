@@ -13,5 +13,5 @@ from .binding import (  # noqa: F401
     PxchgError, Table, BufSet,
     load, library_path, version, set_option, get_option, plan_chunks, status_string,
     pack_fp16, unpack_fp16, reduce_avg, sgd_momentum, easgd, easgd_round,
-    reduce_avg_sgd_momentum, buffer_stats, read_stats, Stats, flush_deferred,
+    reduce_avg_sgd_momentum, buffer_stats, buffer_stats_static, read_stats, Stats, flush_deferred,
 )

@@ -48,6 +48,7 @@ SIGNATURES = {
     "pxchg_easgd_round": (_int, [_vp, _int, _pp, _vp, _f, _vp]),
     "pxchg_reduce_avg_sgd_momentum": (_int, [_vp, _int, _pp, _int, _int, _vp, _vp, _f, _f, _f, _vp]),
     "pxchg_buffer_stats": (_int, [_vp, _vp, _vp, _vp]),
+    "pxchg_buffer_stats_static": (_int, [_vp, _vp, _vp, _vp]),
 }
 
 
@@ -395,6 +396,16 @@ def buffer_stats(table: Table, bufset: BufSet, out, stream=None) -> None:
     if not isinstance(out, int) and out.numel() * out.element_size() < ctypes.sizeof(Stats):
         raise ValueError("the output needs 24 bytes")
     _check(table._lib.pxchg_buffer_stats(table.handle, bufset.handle, addr, _stream_ptr(stream)), "pxchg_buffer_stats")
+
+
+def buffer_stats_static(table: Table, bufset: BufSet, out, stream=None) -> None:
+    """pxchg_buffer_stats_static: the same result, with the partial results in the library's static device array
+    (nothing allocated, by this call or for it)."""
+    addr = out if isinstance(out, int) else out.data_ptr()
+    if not isinstance(out, int) and out.numel() * out.element_size() < ctypes.sizeof(Stats):
+        raise ValueError("the output needs 24 bytes")
+    _check(table._lib.pxchg_buffer_stats_static(table.handle, bufset.handle, addr, _stream_ptr(stream)),
+           "pxchg_buffer_stats_static")
 
 
 def read_stats(out) -> Tuple[int, float, float]:

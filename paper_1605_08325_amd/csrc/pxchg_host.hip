@@ -199,6 +199,9 @@ int pxchg_table_create(int n_tensors, const int64_t *counts, pxchg_table **out) 
             return PXCHG_ERR_RUNTIME;
         }
     }
+    // set-up for the allocation-free diagnostics call (the device is current here); if the look-up fails, that
+    // call tries again and reports it
+    (void)px_prepare_static_scratch(device);
     {
         Exclusive lock(px_registry_lock());
         registry()[t] = PX_KIND_TABLE;

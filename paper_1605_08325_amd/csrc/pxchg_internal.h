@@ -75,6 +75,11 @@ PxOptions &px_options();
 // the plain one are.  Defined beside the kernels.
 int px_all_policies_built();
 
+// Looks up, once per device, this device's copy of the static array that pxchg_buffer_stats_static keeps its
+// partial results in.  `device` must be current.  Called when a table is created, so that the exchange calls
+// find the address ready.  Defined beside the array.
+int px_prepare_static_scratch(int device);
+
 // Compute units of the current device (cached per device).
 int px_cu_count(int device);
 

@@ -22,6 +22,7 @@
 // definition of each operation in pxchg.h states.  binary32 -> binary16 uses the
 // hardware convert under the default round-to-nearest-even mode with binary16
 // denormals enabled; the packed round-toward-zero convert is never used.
+#include <atomic>
 #include <shared_mutex>
 #include <tuple>
 #include <type_traits>
@@ -1252,6 +1253,28 @@ void fill_scale(int k, int mode, int *use_div, float *kf, float *scale) {
     }
 }
 
+// Partial results for pxchg_buffer_stats_static: memory that exists from the moment the code object is loaded,
+// so that the call has nothing to allocate.  One copy per GPU, at its own address on each, looked up once per
+// device with that device current and kept; host code never uses the array's name for anything else (the name
+// is only a host-side stand-in, not a device address).
+static __device__ __align__(256) pxchg_stats scratch[PXCHG_STATS_STATIC_MAX_BLOCKS];
+constexpr int PX_MAX_DEVICES = 64;
+std::atomic<pxchg_stats *> scratch_ptr[PX_MAX_DEVICES];
+
+// The current device's copy of `scratch`; `device` must be the current device.
+int static_scratch(int device, pxchg_stats **out) {
+    if (device < 0 || device >= PX_MAX_DEVICES) return PXCHG_ERR_UNSUPPORTED;
+    pxchg_stats *p = scratch_ptr[device].load(std::memory_order_acquire);
+    if (!p) {
+        void *addr = nullptr;
+        if (hipGetSymbolAddress(&addr, HIP_SYMBOL(scratch)) != hipSuccess || !addr) return PXCHG_ERR_RUNTIME;
+        p = (pxchg_stats *)addr;
+        scratch_ptr[device].store(p, std::memory_order_release);  // every thread finds the same address
+    }
+    *out = p;
+    return PXCHG_OK;
+}
+
 // The two launches of the diagnostics; `partials` has room for one result per block of the table's chunk list.
 int launch_stats(const pxchg_table *table, const pxchg_bufset *set, pxchg_stats *partials, pxchg_stats *out,
                  hipStream_t stream) {
@@ -1271,6 +1294,11 @@ int launch_stats(const pxchg_table *table, const pxchg_bufset *set, pxchg_stats 
 }
 
 }  // namespace
+
+int px_prepare_static_scratch(int device) {
+    pxchg_stats *p = nullptr;
+    return static_scratch(device, &p);
+}
 
 int px_all_policies_built() {
 #ifdef PXCHG_ALL_POLICIES
@@ -1432,6 +1460,18 @@ int pxchg_buffer_stats(const pxchg_table *table, const pxchg_bufset *set, pxchg_
     if ((rc = check_set(table, set, -1))) return rc;
     if (!out || ((uintptr_t)out & 7u)) return PXCHG_ERR_INVALID_ARG;
     return launch_stats(table, set, px_root(table)->d_partials, out, (hipStream_t)stream);
+}
+
+int pxchg_buffer_stats_static(const pxchg_table *table, const pxchg_bufset *set, pxchg_stats *out, void *stream) {
+    Shared lock(px_registry_lock());
+    int rc = check_table(table);
+    if (rc) return rc;
+    if ((rc = check_set(table, set, -1))) return rc;
+    if (!out || ((uintptr_t)out & 7u)) return PXCHG_ERR_INVALID_ARG;
+    if (px_stats_blocks(table->n_chunks) > PXCHG_STATS_STATIC_MAX_BLOCKS) return PXCHG_ERR_UNSUPPORTED;
+    pxchg_stats *partials = nullptr;
+    if ((rc = static_scratch(table->device, &partials))) return rc;  // the table's device is the current one
+    return launch_stats(table, set, partials, out, (hipStream_t)stream);
 }
 
 }  // extern "C"

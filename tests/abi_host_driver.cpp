@@ -21,7 +21,7 @@
 namespace fake {
 int current_device = 0;
 std::map<uintptr_t, size_t> allocations;  // base -> size
-int launches = 0, get_last_error_calls = 0, synchronizes = 0;
+int launches = 0, get_last_error_calls = 0, synchronizes = 0, symbol_lookups = 0, mallocs = 0;
 bool fail_next_launch = false;
 dim3 last_grid, last_block;
 std::vector<dim3> grids;
@@ -39,6 +39,7 @@ hipError_t hipDeviceGetAttribute(int *value, hipDeviceAttribute_t, int) {
 hipError_t hipMalloc(void **ptr, size_t size) {
     *ptr = std::malloc(size ? size : 1);
     if (!*ptr) return hipErrorOutOfMemory;
+    ++fake::mallocs;
     fake::allocations[(uintptr_t)*ptr] = size;
     return hipSuccess;
 }
@@ -68,6 +69,13 @@ hipError_t hipMemGetAddressRange(hipDeviceptr_t *base, size_t *size, hipDevicept
     if (a >= it->first + it->second) return hipErrorInvalidValue;
     *base = (hipDeviceptr_t)it->first;
     *size = it->second;
+    return hipSuccess;
+}
+hipError_t hipGetSymbolAddress(void **address, const void *symbol) {
+    static pxchg_stats standin[PXCHG_STATS_STATIC_MAX_BLOCKS];  // what a device would hold
+    if (!symbol) return hipErrorInvalidSymbol;
+    ++fake::symbol_lookups;
+    *address = standin;
     return hipSuccess;
 }
 hipError_t hipLaunchKernel(const void *function, dim3 grid, dim3 block, void **args, size_t, hipStream_t) {
@@ -222,6 +230,7 @@ std::vector<int> every_hot_call(pxchg_table *table, pxchg_bufset *a, pxchg_bufse
         pxchg_easgd_round(table, 2, xs, c, 0.0625f, nullptr),
         pxchg_reduce_avg_sgd_momentum(table, 1, hin, PXCHG_AVG, PXCHG_F16, a, b, 0.01f, 0.9f, 0.0f, nullptr),
         pxchg_buffer_stats(table, h, out, nullptr),
+        pxchg_buffer_stats_static(table, h, out, nullptr),
     };
 }
 
@@ -257,7 +266,7 @@ int lifetime_and_launches() {
     fake::launches = 0;
     fake::grids.clear();
     for (int rc : every_hot_call(table, a, b, c, h, out)) CHECK(rc == PXCHG_OK);
-    CHECK(fake::launches == 9);
+    CHECK(fake::launches == 11);
     CHECK(fake::get_last_error_calls == errs_before && fake::synchronizes == syncs_before);
     for (size_t i = 0; i < 7; ++i) CHECK(fake::grids[i].x == (unsigned)n_chunks && fake::grids[i].y == 1);
     const int64_t n_blocks = (n_chunks + PXCHG_STATS_BLOCK_CHUNKS - 1) / PXCHG_STATS_BLOCK_CHUNKS;
@@ -306,6 +315,39 @@ int lifetime_and_launches() {
         for (auto *p : bufs) delete p;
     }
 
+    // ---- the allocation-free diagnostics call: same two launches, no allocation, the array's address looked up
+    // once per device (table creation did it), and a size limit of its own
+    {
+        const int mallocs = fake::mallocs, lookups = fake::symbol_lookups;
+        CHECK(lookups == 1);
+        fake::launches = 0;
+        fake::grids.clear();
+        CHECK(pxchg_buffer_stats_static(table, h, out, nullptr) == PXCHG_OK);
+        CHECK(pxchg_buffer_stats_static(table, a, out, nullptr) == PXCHG_OK);
+        CHECK(fake::launches == 4 && fake::grids[0].x == (unsigned)n_blocks && fake::grids[1].x == 1);
+        CHECK(fake::mallocs == mallocs && fake::symbol_lookups == lookups);
+        CHECK(pxchg_buffer_stats_static(table, h, nullptr, nullptr) == PXCHG_ERR_INVALID_ARG);
+        CHECK(pxchg_buffer_stats_static(table, foreign, out, nullptr) == PXCHG_ERR_SHAPE_MISMATCH);
+        // one chunk too many for the static array: refused before anything is launched; the regular call takes it
+        const int64_t limit = (int64_t)PXCHG_STATS_STATIC_MAX_BLOCKS * PXCHG_STATS_BLOCK_CHUNKS;
+        const int64_t big_counts[2] = {limit * 512, 1};
+        pxchg_table *big = nullptr;
+        CHECK(pxchg_table_create(2, big_counts, &big) == PXCHG_OK && pxchg_table_n_chunks(big) == limit + 1);
+        CHECK(pxchg_set_option(PXCHG_OPT_CHECK_RANGES, 0) == PXCHG_OK);  // no buffers of that size here
+        const void *anywhere[2] = {fa.ptrs[0], fa.ptrs[0]};
+        pxchg_bufset *bs = nullptr;
+        CHECK(pxchg_bufset_create(big, PXCHG_F16, anywhere, &bs) == PXCHG_OK);
+        CHECK(pxchg_set_option(PXCHG_OPT_CHECK_RANGES, 1) == PXCHG_OK);
+        fake::launches = 0;
+        CHECK(pxchg_buffer_stats_static(big, bs, out, nullptr) == PXCHG_ERR_UNSUPPORTED && fake::launches == 0);
+        CHECK(pxchg_buffer_stats(big, bs, out, nullptr) == PXCHG_OK && fake::launches == 2);
+        pxchg_table *fits = nullptr;   // a view of exactly the limit fits
+        CHECK(pxchg_table_view(big, 0, 1, &fits) == PXCHG_OK && pxchg_table_n_chunks(fits) == limit);
+        CHECK(pxchg_buffer_stats_static(fits, bs, out, nullptr) == PXCHG_OK);
+        CHECK(fake::grids.back().x == 1 && fake::grids[fake::grids.size() - 2].x == (unsigned)PXCHG_STATS_STATIC_MAX_BLOCKS);
+        CHECK(pxchg_table_destroy(fits) == PXCHG_OK && pxchg_bufset_destroy(bs) == PXCHG_OK && pxchg_table_destroy(big) == PXCHG_OK);
+    }
+
     // ---- wrong arguments with live handles
     {
         const pxchg_bufset *mixed[2] = {a, h};
@@ -348,7 +390,7 @@ int lifetime_and_launches() {
     CHECK(pxchg_table_set_multipliers(view, nullptr, nullptr) == PXCHG_ERR_INVALID_ARG);
     fake::launches = 0;
     for (int rc : every_hot_call(view, a, b, c, h, out)) CHECK(rc == PXCHG_OK);
-    CHECK(fake::launches == 9);
+    CHECK(fake::launches == 11);
     CHECK(pxchg_easgd(view, a, c, 0.1f, nullptr) == PXCHG_OK && fake::last_grid.x == 81);
     CHECK(pxchg_easgd(view, foreign, c, 0.1f, nullptr) == PXCHG_ERR_SHAPE_MISMATCH);
     CHECK(pxchg_table_destroy(table) == PXCHG_ERR_IN_USE);                              // views and sets alive
@@ -376,7 +418,7 @@ int lifetime_and_launches() {
         const std::vector<int> rcs = every_hot_call(table, a, b, c, h, out);
         // pack, unpack, update with h as gradient, fused reduce+update and the diagnostics use h
         CHECK(rcs[0] == PXCHG_ERR_INVALID_ARG && rcs[1] == PXCHG_ERR_INVALID_ARG && rcs[3] == PXCHG_ERR_INVALID_ARG);
-        CHECK(rcs[6] == PXCHG_ERR_INVALID_ARG && rcs[7] == PXCHG_ERR_INVALID_ARG);
+        CHECK(rcs[6] == PXCHG_ERR_INVALID_ARG && rcs[7] == PXCHG_ERR_INVALID_ARG && rcs[8] == PXCHG_ERR_INVALID_ARG);
         CHECK(rcs[2] == PXCHG_OK && rcs[4] == PXCHG_OK && rcs[5] == PXCHG_OK);
     }
     CHECK(pxchg_bufset_destroy(a) == PXCHG_OK && pxchg_bufset_destroy(b) == PXCHG_OK);
