@@ -17,11 +17,24 @@ times come from HIP events recorded on the launch stream between the stages of
 every timed step; the `roofline` object is for the kernel with the largest share
 of the step, `stages` lists all of them.
 
+Two sets of figures per stage.  `ms_per_launch` is the stage inside the step, as
+an exchange runs it: the update reads the mean the reduce has just written, the
+reduce reads what the pack has just written, and what is left of those in the
+256 MB memory-side cache helps.  `cold_ms` is the stage alone in a loop over
+rotating operand sets, so that every operand (inputs, outputs, in-place state)
+was last touched at least 1 GB of traffic ago: a pure HBM figure.  `value_cold`
+is the metric from the cold figures.
+
+`configs` holds reduce+update (and the elastic meeting) for the other benchmark
+configurations and the paper's two other model sizes, each cold (operand sets
+rotating over more than 1 GB) and warm (one operand set over and over).
+
 `extras` holds what is measured after the timed region, each over the same number
-of repetitions: the fused reduce+update and the fused elastic round, the elastic
-kernels with the center kept in the memory-side cache, the diagnostics pass, the
-same reduce+update issued layer by layer on two streams, the whole step replayed
-from a HIP graph, and weight averaging (the reduce over float32 sets).
+of repetitions: the fused reduce+update and the fused elastic round (cold), the
+elastic kernels with the center kept in the memory-side cache, the diagnostics
+pass (warm and cold), the layer-wise exchange on grouped layers, alone and
+overlapped with a stand-in gradient producer, one rank's share on an 8-GPU node,
+the whole step replayed from a HIP graph, and weight averaging.
 
 `cpu_baseline` is the CPU oracle timed on the host cores on the same workload.
 It is a reported baseline (and the only place this program touches the oracle),
@@ -32,6 +45,7 @@ from __future__ import annotations
 import argparse
 import json
 import os
+import re
 import sys
 import time
 from concurrent.futures import ThreadPoolExecutor
@@ -45,24 +59,49 @@ if ROOT not in sys.path:
 import workloads as wl  # noqa: E402
 
 HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E, published peak
+COLD_BYTES = 10 ** 9    # an operand counts as cold when this much other traffic has passed since its last use
 
-# HBM traffic per launch from hardware counters (FETCH_SIZE + WRITE_SIZE, scaled by
-# what the same counters read for a plain copy of known size); see the files named.
-MEASURED_TRAFFIC_BYTES = {
-    # stage: (bytes per launch, profile summary it comes from)
-    "pack": (2_925_961_070, "profiles/bench_alexnet_k8_hbm_counters.txt"),
-    "reduce": (1_054_182_083, "profiles/bench_alexnet_k8_hbm_counters.txt"),
-    "update": (1_075_740_713, "profiles/bench_alexnet_k8_hbm_counters.txt"),
-    "elastic": (960_996_176, "profiles/bench_alexnet_k8_hbm_counters.txt"),
+# HBM traffic per launch is read, at run time, from the committed summary of the hardware-counter runs on this
+# same workload: read and write requests between the L2 caches and the memory fabric, counted by size, which
+# gives bytes without any scale factor.  (kernel name as the summary prints it, what must also be in the row)
+TRAFFIC_PROFILE = os.path.join("profiles", "bench_alexnet_k8_request_sizes_and_utilisation.txt")
+TRAFFIC_ROWS = {
+    "pack": ("pxchg_convert_kernel<float, _Float16", ""),
+    "reduce": ("pxchg_reduce_avg_kernel<8, _Float16, _Float16", ""),
+    "update": ("pxchg_sgd_momentum_kernel<_Float16", ""),
+    "elastic": ("pxchg_easgd_kernel<1,", "false>"),
+    "fused_reduce_update": ("pxchg_reduce_avg_sgd_momentum_kernel<8, _Float16, true", ""),
+    "fused_elastic_round": ("pxchg_easgd_kernel<8,", "false>"),
 }
 
 
-def host_threads() -> int:
-    n = len(os.sched_getaffinity(0))
+def measured_traffic() -> dict:
+    """stage -> bytes per launch from the counter summary (64- and 128-byte read requests, 64-byte write
+    requests), or {} if the file is not there.  A row ends in: rd64 rd128 readMB algRdMB wr64 writeMB algWrMB ratio."""
+    path = os.path.join(ROOT, TRAFFIC_PROFILE)
+    out = {}
+    if not os.path.exists(path):
+        return out
+    for line in open(path):
+        m = re.search(r"\s(\d+)\s+(\d+)\s+[\d.]+\s+[\d.]+\s+(\d+)\s+[\d.]+\s+[\d.]+\s+[\d.]+\s*$", line)
+        if not m:
+            continue
+        for stage, (prefix, also) in TRAFFIC_ROWS.items():
+            if line.startswith(prefix) and also in line.split("[")[0] and stage not in out:
+                rd64, rd128, wr64 = (int(g) for g in m.groups())
+                out[stage] = rd64 * 64 + rd128 * 128 + wr64 * 64
+    return out
+
+
+def host_threads():
+    """(threads the oracle baseline uses, cores this process may run on).  The first is the second unless the
+    environment asks for fewer (OMP_NUM_THREADS, which a shared box sets to this job's share)."""
+    avail = len(os.sched_getaffinity(0))
+    n = avail
     env = os.environ.get("OMP_NUM_THREADS")
     if env and env.isdigit() and int(env) > 0:
         n = min(n, int(env))
-    return max(1, min(n, 16))
+    return max(1, n), avail
 
 
 def upload(tensors):
@@ -72,7 +111,7 @@ def upload(tensors):
 
 def cpu_baseline(counts, grads, w, v, xs, c, order, cfg, alpha, threads):
     """The oracle, as it stands, on the host cores: same stages, same inputs.  Returns per-stage seconds with
-    all `threads` host threads (element range split over them) and with one thread."""
+    all `threads` host threads (element range split over them, best of 3) and with one thread."""
     import ctypes
 
     import oracle
@@ -134,7 +173,7 @@ def cpu_baseline(counts, grads, w, v, xs, c, order, cfg, alpha, threads):
                 times[name] = best
         return times
 
-    return run(threads, 2), run(1, 1)
+    return run(threads, 3), run(1, 1)
 
 
 def device_facts(torch) -> dict:
@@ -153,6 +192,112 @@ def device_facts(torch) -> dict:
     return facts
 
 
+def rate(nbytes, ms):
+    gbps = nbytes / ms / 1e6
+    return {"ms": round(ms, 5), "algorithmic_bytes": int(nbytes), "GBps": round(gbps, 1),
+            "frac_of_hbm_peak": round(gbps / HBM_PEAK_GBPS, 4)}
+
+
+class Clock:
+    """HIP events on torch's current stream, which is the stream every library call below is given."""
+
+    def __init__(self, torch, reps):
+        self.torch, self.reps = torch, reps
+        self.ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+
+    def loop(self, fn, reps=None, warm=3):
+        """Mean milliseconds of fn(i) over `reps` calls issued back to back, after `warm` untimed ones."""
+        reps = reps or self.reps
+        for i in range(warm):
+            fn(i)
+        self.ev[0].record()
+        for i in range(reps):
+            fn(warm + i)
+        self.ev[1].record()
+        self.torch.cuda.synchronize()
+        return self.ev[0].elapsed_time(self.ev[1]) / reps
+
+
+def rotation(per_set_bytes, at_least=2, at_most=64):
+    """Number of operand sets to rotate over so that a set comes back only after COLD_BYTES of other traffic."""
+    return int(max(at_least, min(at_most, -(-COLD_BYTES // max(1, per_set_bytes)) + 1)))
+
+
+def bench_config(px, torch, clock, name, counts, k, transfer, lr, mu, wd, alpha, stream, seed, note=None):
+    """reduce -> update (and one elastic meeting) on one configuration's shapes: `cold` with every operand set
+    rotating over more than COLD_BYTES, `warm` with one operand set over and over (what a loop that does nothing
+    else between exchanges would see: small sets then live in the caches).  Inputs are N(0, 0.01^2) draws made on
+    the device from the configuration's seed (timing only; the parity tests use the host-drawn inputs)."""
+    n = sum(counts)
+    half = transfer == "f16"
+    wire_t, es = (torch.float16, 2) if half else (torch.float32, 4)
+    table = px.Table(counts)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(seed)
+
+    def draw(dtype):
+        flat = torch.empty(n, dtype=torch.float32, device="cuda").normal_(0.0, 0.01, generator=gen).to(dtype)
+        out, o = [], 0
+        for c_ in counts:                       # one allocation per tensor, as the model holds them
+            out.append(flat[o:o + c_].clone())
+            o += c_
+        return out
+
+    set_bytes = n * (k * es + es + 8)           # contributions, mean, parameters and velocity of one operand set
+    n_rot = rotation(set_bytes)
+    sets = []
+    for _ in range(n_rot):
+        contrib = [table.bufset(draw(wire_t)) for _ in range(k)]
+        mean = table.bufset([torch.empty(c_, dtype=wire_t, device="cuda") for c_ in counts])
+        sets.append((contrib, mean, table.bufset(draw(torch.float32)), table.bufset(draw(torch.float32))))
+    torch.cuda.synchronize()
+
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(clock.reps)]
+
+    def run(rotating):
+        def one(i, e=None):
+            contrib, mean, w_, v_ = sets[i % n_rot if rotating else 0]
+            if e:
+                e[0].record()
+            px.reduce_avg(table, contrib, mean, px.AVG, stream=stream)
+            if e:
+                e[1].record()
+            px.sgd_momentum(table, mean, w_, v_, lr, mu, wd, stream=stream)
+            if e:
+                e[2].record()
+        for i in range(3):
+            one(i)
+        for i in range(clock.reps):
+            one(3 + i, ev[i])
+        torch.cuda.synchronize()
+        r_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in ev]))
+        u_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in ev]))
+        return r_ms, u_ms
+
+    r_bytes, u_bytes = (k * es + es) * n, (es + 16) * n
+    out = {"n_params": n, "n_tensors": len(counts), "k": k, "transfer": transfer, "operand_sets": n_rot}
+    for label, rotating in (("cold", True), ("warm", False)):
+        r_ms, u_ms = run(rotating)
+        out[label] = {"reduce_ms": round(r_ms, 5), "update_ms": round(u_ms, 5),
+                      "reduce_GBps": round(r_bytes / r_ms / 1e6, 1), "update_GBps": round(u_bytes / u_ms / 1e6, 1),
+                      "reduce_update_GBps": round((r_bytes + u_bytes) / (r_ms + u_ms) / 1e6, 1),
+                      "frac_of_hbm_peak": round((r_bytes + u_bytes) / (r_ms + u_ms) / 1e6 / HBM_PEAK_GBPS, 4)}
+    if alpha:
+        # the elastic meeting: parameters of one set meet the velocity buffer of the next as "center"
+        def meet(i, rotating=True):
+            a, b = (i % n_rot, (i + 1) % n_rot) if rotating else (0, 0)
+            px.easgd(table, sets[a][2], sets[b][3], alpha, stream=stream)
+        for label, rotating in (("cold", True), ("warm", False)):
+            ms = clock.loop(lambda i: meet(i, rotating))
+            out[label]["meeting_ms"] = round(ms, 5)
+            out[label]["meeting_GBps"] = round(16 * n / ms / 1e6, 1)
+    if note:
+        out["note"] = note
+    del sets
+    torch.cuda.empty_cache()
+    return out
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -162,13 +307,17 @@ def main() -> int:
                     help="rotating sets of fresh gradients resident in HBM; 0 = as many as make the rotating "
                          "inputs exceed 1 GB (the caches hold 256 MB), at least 2 and at most 16")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-configs", action="store_true", help="leave out the other configurations and model sizes")
     ap.add_argument("--config", type=int, default=3, choices=[1, 2, 3, 4, 5],
-                    help="benchmark configuration (3 = the graded one: AlexNet-shaped, k = 8, half-precision transfer)")
+                    help="benchmark configuration of the timed step (3 = the graded one: AlexNet-shaped, k = 8, "
+                         "half-precision transfer)")
     ap.add_argument("--workload", default="alexnet", choices=["alexnet", "vggnet", "googlenet"],
                     help="tensor shapes: AlexNet (the graded workload), the VGGNet parameter count of the paper's "
                          "Table 2, or its GoogLeNet count spread over 128 small tensors")
     ap.add_argument("--chunk", type=int, default=0, help="override elements per chunk")
     ap.add_argument("--blocks-per-cu", type=int, default=-1)
+    ap.add_argument("--tuning-build", action="store_true",
+                    help="load the build of the library that holds every cache policy (tests/_build/), for --nontemporal")
     ap.add_argument("--nontemporal", type=int, default=-1)
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -178,6 +327,9 @@ def main() -> int:
 
     import torch
     import paper_1605_08325_amd as px
+    if args.tuning_build:
+        from paper_1605_08325_amd import build as px_build
+        px.binding._lib = px.open_library(px_build.ALL_POLICIES_LIB)
     px.load()  # fails loudly if libpxchg.so has not been built
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     torch.cuda.set_device(0)
@@ -192,6 +344,7 @@ def main() -> int:
     if args.workload != "alexnet" and args.config != 3:
         print("bench.py: --workload goes with --config 3 only", file=sys.stderr)
         return 2
+    graded = args.workload == "alexnet" and args.config == 3
     counts = {"alexnet": lambda: list(cfg.counts), "vggnet": wl.vggnet_counts,
               "googlenet": lambda: wl.googlenet_scale_counts(cfg.seed)}[args.workload]()
     k, n = cfg.k, sum(counts)
@@ -199,16 +352,16 @@ def main() -> int:
     wire_t, wire_es, wire_px, wire_name = ((torch.float16, 2, px.F16, "_Float16") if half
                                            else (torch.float32, 4, px.F32, "float"))
     workload_name = cfg.name if args.workload == "alexnet" else f"{args.workload}_sync_k8_f16"
-    threads = host_threads()
+    threads, cores_available = host_threads()
     table = px.Table(counts)
+    reps = args.steps
 
     # ---- synthetic inputs, resident in HBM before anything is timed
     t_gen = time.perf_counter()
     host_grads0 = None
     grad_sets, pack_sets = [], []
-    keep = []
     set_bytes = k * n * (4 + (2 if half else 0))      # one set: k float32 gradients and, if packed, k halves
-    n_sets = args.sets if args.sets > 0 else max(2, min(16, -(-10 ** 9 // set_bytes)))
+    n_sets = args.sets if args.sets > 0 else max(2, min(16, -(-COLD_BYTES // set_bytes)))
     for s in range(n_sets):
         grads = wl.gaussian_workers(counts, cfg.grad_sigma, cfg.seed, "grad", k, step=s, threads=threads)
         if s == 0:
@@ -234,12 +387,19 @@ def main() -> int:
     d_xs, d_c = [upload(x) for x in xs], upload(c)
     s_xs, s_c = [table.bufset(x) for x in d_xs], table.bufset(d_c)
     orders = wl.worker_orders(cfg5.seed, k, args.steps + args.warmup)
+    # operand sets for the cold figures: state and outputs rotate too (copies of the same values)
+    n_rot = rotation((wire_es + 8) * n, at_least=3)
+    rot_state = [(s_w, s_v, s_avg, s_c)]
+    for _ in range(n_rot - 1):
+        rot_state.append((table.bufset([t.clone() for t in d_w]), table.bufset([t.clone() for t in d_v]),
+                          table.bufset([torch.empty_like(t) for t in d_avg]), table.bufset([t.clone() for t in d_c])))
     torch.cuda.synchronize()
     t_gen = time.perf_counter() - t_gen
 
     # the launch stream, looked up once (the binding's default looks it up on every call: 3 us of host time,
     # which shows in the configurations whose kernels take 10..25 us)
     stream = torch.cuda.current_stream().cuda_stream
+    clock = Clock(torch, reps)
 
     def step(i, ev=None, st=stream):
         s = i % len(grad_sets)
@@ -274,6 +434,19 @@ def main() -> int:
     stage_ms = {nm: float(np.mean([events[i][q].elapsed_time(events[i][q + 1]) for i in range(args.steps)]))
                 for q, nm in enumerate(all_stages)}
     stage_names = all_stages if half else all_stages[1:]
+
+    # ---- every stage alone, cold: all of its operands rotate, so nothing it touches is still in a cache
+    for sw_, sv_, sa_, _ in rot_state[1:]:       # give every mean buffer real contents
+        px.reduce_avg(table, pack_sets[0], sa_, px.AVG, stream=stream)
+    cold_ms = {}
+    if half:
+        cold_ms["pack"] = clock.loop(lambda i: px.pack_fp16(table, grad_sets[i % n_sets], pack_sets[i % n_sets], stream=stream))
+    cold_ms["reduce"] = clock.loop(lambda i: px.reduce_avg(table, pack_sets[i % n_sets], rot_state[i % n_rot][2], px.AVG,
+                                                           stream=stream))
+    cold_ms["update"] = clock.loop(lambda i: px.sgd_momentum(table, rot_state[i % n_rot][2], rot_state[i % n_rot][0],
+                                                             rot_state[i % n_rot][1], cfg.lr, cfg.mu, cfg.wd, stream=stream))
+    cold_ms["elastic"] = clock.loop(lambda i: px.easgd(table, s_xs[i % k], rot_state[i % n_rot][3], alpha, stream=stream)) * k
+
     # algorithmic bytes per step and per launch
     stage_bytes = {"pack": 6 * k * n, "reduce": (wire_es * k + wire_es) * n, "update": (wire_es + 16) * n,
                    "elastic": 16 * n * k}
@@ -281,138 +454,181 @@ def main() -> int:
     kernels = {"pack": "pxchg_convert_kernel<float,_Float16>",
                "reduce": f"pxchg_reduce_avg_kernel<{k},{wire_name},{wire_name}>",
                "update": f"pxchg_sgd_momentum_kernel<{wire_name}>", "elastic": "pxchg_easgd_kernel<1>"}
+    traffic = measured_traffic() if graded and args.chunk == 0 and args.nontemporal < 0 else {}
     stages = {}
     for nm in stage_names:
         per_launch_ms = stage_ms[nm] / launches[nm]
-        ach = stage_bytes[nm] / launches[nm] / (per_launch_ms * 1e-3) / 1e9
+        per_launch_bytes = stage_bytes[nm] // launches[nm]
+        ach = per_launch_bytes / (per_launch_ms * 1e-3) / 1e9
+        cold = per_launch_bytes / (cold_ms[nm] / launches[nm] * 1e-3) / 1e9
         stages[nm] = {"kernel": kernels[nm], "launches_per_step": launches[nm], "ms_per_launch": round(per_launch_ms, 5),
-                      "algorithmic_bytes_per_launch": stage_bytes[nm] // launches[nm], "GBps": round(ach, 1),
+                      "algorithmic_bytes_per_launch": per_launch_bytes, "GBps": round(ach, 1),
                       "frac_of_hbm_peak": round(ach / HBM_PEAK_GBPS, 4),
-                      "traffic": MEASURED_TRAFFIC_BYTES.get(nm, (None, None))[0]}
+                      "cold_ms": round(cold_ms[nm] / launches[nm], 5), "cold_GBps": round(cold, 1),
+                      "cold_frac_of_hbm_peak": round(cold / HBM_PEAK_GBPS, 4),
+                      "traffic": traffic.get(nm)}
     dominant = max(stage_names, key=lambda nm: stage_ms[nm])
     d = stages[dominant]
-    if args.workload != "alexnet" or args.config != 3:
-        MEASURED_TRAFFIC_BYTES.clear()  # the counters were collected on configuration 3 only
-        for st in stages.values():
-            st["traffic"] = None
-    traffic = MEASURED_TRAFFIC_BYTES.get(dominant, (None, None))[0]
     roofline = {"bound": "hbm", "kernel": d["kernel"], "achieved": d["GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                "frac": d["frac_of_hbm_peak"], "traffic": traffic,
-                "algorithmic_bytes_per_launch": d["algorithmic_bytes_per_launch"], "ms_per_launch": d["ms_per_launch"]}
+                "frac": d["frac_of_hbm_peak"], "traffic": d["traffic"],
+                "traffic_source": (TRAFFIC_PROFILE + " (64- and 128-byte read requests and 64-byte write requests "
+                                   "between L2 and fabric, per launch; a separate counter run of this command)")
+                if d["traffic"] else None,
+                "algorithmic_bytes_per_launch": d["algorithmic_bytes_per_launch"], "ms_per_launch": d["ms_per_launch"],
+                "cold_achieved": d["cold_GBps"], "cold_frac": d["cold_frac_of_hbm_peak"], "cold_ms_per_launch": d["cold_ms"]}
 
     ru_bytes = stage_bytes["reduce"] + stage_bytes["update"]
     ru_ms = stage_ms["reduce"] + stage_ms["update"]
     value = ru_bytes / (ru_ms * 1e-3) / 1e9
+    ru_cold_ms = cold_ms["reduce"] + cold_ms["update"]
+    value_cold = ru_bytes / (ru_cold_ms * 1e-3) / 1e9
     ms_per_step = wall / args.steps * 1e3
     step_bytes = sum(stage_bytes[nm] for nm in stage_names)
 
-    # ---- fused variants (same arithmetic, fewer bytes), timed after the main region
-    fused = {}
-    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
-    for i in range(3):
-        px.reduce_avg_sgd_momentum(table, pack_sets[0], s_w, s_v, cfg.lr, cfg.mu, cfg.wd, px.AVG, wire_px,
-                                   stream=stream)
-    ev[0].record()
-    for i in range(args.steps):
-        px.reduce_avg_sgd_momentum(table, pack_sets[i % len(pack_sets)], s_w, s_v, cfg.lr, cfg.mu, cfg.wd,
-                                   px.AVG, wire_px, stream=stream)
-    ev[1].record()
-    torch.cuda.synchronize()
-    ms = ev[0].elapsed_time(ev[1]) / args.steps
-    fb = (wire_es * k + 16) * n
-    fused["reduce_update"] = {"ms": round(ms, 5), "algorithmic_bytes": fb, "GBps": round(fb / ms / 1e6, 1),
-                              "frac_of_hbm_peak": round(fb / ms / 1e6 / HBM_PEAK_GBPS, 4)}
-    for i in range(3):
-        px.easgd_round(table, [s_xs[int(j)] for j in orders[i]], s_c, alpha, stream=stream)
-    ev[0].record()
-    for i in range(args.steps):
-        px.easgd_round(table, [s_xs[int(j)] for j in orders[i]], s_c, alpha, stream=stream)
-    ev[1].record()
-    torch.cuda.synchronize()
-    ms = ev[0].elapsed_time(ev[1]) / args.steps
-    fb = (8 * k + 8) * n
-    fused["elastic_round"] = {"ms": round(ms, 5), "algorithmic_bytes": fb, "GBps": round(fb / ms / 1e6, 1),
-                              "frac_of_hbm_peak": round(fb / ms / 1e6 / HBM_PEAK_GBPS, 4)}
+    # ---- fused variants (same arithmetic, fewer bytes), timed after the main region; cold like the stages
+    extras = {}
+    ms = clock.loop(lambda i: px.reduce_avg_sgd_momentum(table, pack_sets[i % n_sets], rot_state[i % n_rot][0],
+                                                         rot_state[i % n_rot][1], cfg.lr, cfg.mu, cfg.wd, px.AVG, wire_px,
+                                                         stream=stream))
+    extras["reduce_update"] = dict(rate((wire_es * k + 16) * n, ms), traffic=traffic.get("fused_reduce_update"),
+                                   note="pxchg_reduce_avg_sgd_momentum, one launch, cold operands")
+    ms = clock.loop(lambda i: px.easgd_round(table, [s_xs[int(j)] for j in orders[i % len(orders)]], rot_state[i % n_rot][3],
+                                             alpha, stream=stream))
+    extras["elastic_round"] = dict(rate((8 * k + 8) * n, ms), traffic=traffic.get("fused_elastic_round"),
+                                   note=f"pxchg_easgd_round of {k}, one launch, cold operands")
 
     # ---- the elastic server's case: nothing but meetings, the center kept in the memory-side cache
     px.set_option(px.OPT_CENTER_RESIDENT, 1)
     try:
         def meetings(i):
-            for j in orders[i]:
+            for j in orders[i % len(orders)]:
                 px.easgd(table, s_xs[int(j)], s_c, alpha, stream=stream)
-        for i in range(3):
-            meetings(i)
-        ev[0].record()
-        for i in range(args.steps):
-            meetings(i)
-        ev[1].record()
-        torch.cuda.synchronize()
-        ms = ev[0].elapsed_time(ev[1]) / (args.steps * k)
-        fb = 16 * n
-        fused["elastic_meeting_center_resident"] = {
-            "ms": round(ms, 5), "algorithmic_bytes": fb, "GBps": round(fb / ms / 1e6, 1),
+        ms = clock.loop(meetings) / k
+        extras["elastic_meeting_center_resident"] = {
+            "ms": round(ms, 5), "algorithmic_bytes": 16 * n, "GBps": round(16 * n / ms / 1e6, 1),
             "note": "PXCHG_OPT_CENTER_RESIDENT=1, meetings back to back: the center's half of the traffic is served "
                     "by the memory-side cache where it fits (256 MB), so this is not an HBM figure"}
-        for i in range(3):
-            px.easgd_round(table, [s_xs[int(j)] for j in orders[i]], s_c, alpha, stream=stream)
-        ev[0].record()
-        for i in range(args.steps):
-            px.easgd_round(table, [s_xs[int(j)] for j in orders[i]], s_c, alpha, stream=stream)
-        ev[1].record()
-        torch.cuda.synchronize()
-        ms = ev[0].elapsed_time(ev[1]) / args.steps
-        fb = (8 * k + 8) * n
-        fused["elastic_round_center_resident"] = {"ms": round(ms, 5), "algorithmic_bytes": fb,
-                                                  "GBps": round(fb / ms / 1e6, 1)}
+        ms = clock.loop(lambda i: px.easgd_round(table, [s_xs[int(j)] for j in orders[i % len(orders)]], s_c, alpha,
+                                                 stream=stream))
+        extras["elastic_round_center_resident"] = {"ms": round(ms, 5), "algorithmic_bytes": (8 * k + 8) * n,
+                                                   "GBps": round((8 * k + 8) * n / ms / 1e6, 1)}
     finally:
         px.set_option(px.OPT_CENTER_RESIDENT, 0)
 
-    # ---- diagnostics pass over the averaged gradient (read-only: 2 bytes per element)
+    # ---- diagnostics pass (read-only: 2 bytes per element): on the mean over and over (it then sits in the
+    # memory-side cache), and cold, over the k packed sets in turn
     d_stats = torch.zeros(3, dtype=torch.int64, device="cuda")
-    for i in range(3):
-        px.buffer_stats(table, s_avg, d_stats, stream=stream)
-    ev[0].record()
-    for i in range(args.steps):
-        px.buffer_stats(table, s_avg, d_stats, stream=stream)
-    ev[1].record()
-    torch.cuda.synchronize()
-    ms = ev[0].elapsed_time(ev[1]) / args.steps
-    fused["diagnostics"] = {"ms": round(ms, 5), "algorithmic_bytes": wire_es * n,
-                            "GBps": round(wire_es * n / ms / 1e6, 1),
-                            "frac_of_hbm_peak": round(wire_es * n / ms / 1e6 / HBM_PEAK_GBPS, 4),
-                            "note": "two launches; an input under 256 MB may sit in the memory-side cache"}
+    ms = clock.loop(lambda i: px.buffer_stats(table, s_avg, d_stats, stream=stream))
+    extras["diagnostics"] = dict(rate(wire_es * n, ms), note="two launches; the same 122 MB input every time, which then "
+                                                             "sits in the memory-side cache: not an HBM figure")
+    flat_sets = [s for ps in pack_sets for s in ps]
+    ms = clock.loop(lambda i: px.buffer_stats(table, flat_sets[i % len(flat_sets)], d_stats, stream=stream))
+    extras["diagnostics_cold"] = dict(rate(wire_es * n, ms), note=f"two launches; input rotating over {len(flat_sets)} sets")
+    ms = clock.loop(lambda i: px.buffer_stats_static(table, flat_sets[i % len(flat_sets)], d_stats, stream=stream))
+    extras["diagnostics_static_scratch_cold"] = dict(rate(wire_es * n, ms), note="pxchg_buffer_stats_static, same input rotation")
 
-    # ---- the same reduce -> update issued layer by layer (weight and bias of a layer together, last layer
-    # first, as back-propagation would hand the gradients over) on two alternating side streams
-    per_layer = [table.view(i, min(2, len(counts) - i)) for i in reversed(range(0, len(counts), 2))]
+    # ---- the same reduce -> update issued on groups of layers (views of at least 8 M elements, formed from the
+    # last layer backwards as back-propagation hands gradients over; small layers share a group) on two
+    # alternating side streams.  The whole set goes through the same fork and join (one group, one side stream)
+    # for comparison, so that the ratio shows what the grouping costs and not what the stream hand-over costs.
+    groups = table.bucketed_views(8_000_000)
     main_stream = torch.cuda.current_stream()
     side = [torch.cuda.Stream(), torch.cuda.Stream()]
     go, done = torch.cuda.Event(), [torch.cuda.Event(), torch.cuda.Event()]
 
-    def per_layer_step():
+    def forked(i, tables, fused):
         go.record(main_stream)
         for st in side:
             st.wait_event(go)
-        for li, layer in enumerate(per_layer):          # a view per layer, the whole set's buffer sets
-            sp = side[li % 2].cuda_stream
-            px.reduce_avg(layer, pack_sets[0], s_avg, px.AVG, stream=sp)
-            px.sgd_momentum(layer, s_avg, s_w, s_v, cfg.lr, cfg.mu, cfg.wd, stream=sp)
-        for st, d in zip(side, done):
-            d.record(st)
-            main_stream.wait_event(d)
+        for gi, grp in enumerate(tables):               # a view per group, the whole set's buffer sets
+            sp = side[gi % 2].cuda_stream
+            if fused:
+                px.reduce_avg_sgd_momentum(grp, pack_sets[i % n_sets], s_w, s_v, cfg.lr, cfg.mu, cfg.wd, px.AVG, wire_px,
+                                           stream=sp)
+            else:
+                px.reduce_avg(grp, pack_sets[i % n_sets], s_avg, px.AVG, stream=sp)
+                px.sgd_momentum(grp, s_avg, s_w, s_v, cfg.lr, cfg.mu, cfg.wd, stream=sp)
+        for st, d_ in zip(side, done):
+            d_.record(st)
+            main_stream.wait_event(d_)
 
-    for i in range(3):
-        per_layer_step()
-    ev[0].record()
-    for i in range(args.steps):
-        per_layer_step()
-    ev[1].record()
-    torch.cuda.synchronize()
-    ms = ev[0].elapsed_time(ev[1]) / args.steps
-    fused["per_layer_two_streams"] = {"ms": round(ms, 5), "algorithmic_bytes": ru_bytes, "layers": len(per_layer),
-                                      "launches": 2 * len(per_layer), "GBps": round(ru_bytes / ms / 1e6, 1),
-                                      "frac_of_hbm_peak": round(ru_bytes / ms / 1e6 / HBM_PEAK_GBPS, 4),
-                                      "note": "reduce+update of the whole set, one view of the table per layer"}
+    ms = clock.loop(lambda i: forked(i, groups, False))
+    ms_whole = clock.loop(lambda i: forked(i, [table], False))
+    ms_f = clock.loop(lambda i: forked(i, groups, True))
+    ms_f_whole = clock.loop(lambda i: forked(i, [table], True))
+    extras["per_layer_two_streams"] = dict(rate(ru_bytes, ms), groups=len(groups), launches=2 * len(groups),
+                                           group_elems=[g.total for g in groups], whole_set_ms=round(ms_whole, 5),
+                                           ratio_to_whole_set=round(ms / ms_whole, 4),
+                                           fused_ms=round(ms_f, 5), fused_whole_set_ms=round(ms_f_whole, 5),
+                                           fused_ratio_to_whole_set=round(ms_f / ms_f_whole, 4),
+                                           note="reduce+update of the whole set, one view per group of layers, two side "
+                                                "streams; whole_set_ms: the same through the same fork and join as one "
+                                                "group; fused_*: pxchg_reduce_avg_sgd_momentum per group (one launch each)")
+
+    # ---- overlap with a gradient producer (the overlap the paper names as future work): a producer stream hands
+    # the k workers' gradients over group by group, last layers first (here: the pack of that group, which
+    # writes the k binary16 gradient sets), and an exchange stream reduces and updates each group as soon as
+    # its event fires.  exposed = what is left of the exchange after the producer's last write.
+    if half:
+        prod, exch = torch.cuda.Stream(), torch.cuda.Stream()
+        ready = [torch.cuda.Event() for _ in groups]
+        t_start, t_prod, t_end = (torch.cuda.Event(enable_timing=True) for _ in range(3))
+        fin = torch.cuda.Event()
+
+        def overlapped(i, timed=False):
+            s = i % n_sets
+            go.record(main_stream)
+            prod.wait_event(go)
+            exch.wait_event(go)
+            if timed:
+                t_start.record(prod)
+            for gi, grp in enumerate(groups):
+                px.pack_fp16(grp, grad_sets[s], pack_sets[s], stream=prod.cuda_stream)
+                ready[gi].record(prod)
+                exch.wait_event(ready[gi])
+                px.reduce_avg(grp, pack_sets[s], s_avg, px.AVG, stream=exch.cuda_stream)
+                px.sgd_momentum(grp, s_avg, s_w, s_v, cfg.lr, cfg.mu, cfg.wd, stream=exch.cuda_stream)
+            if timed:
+                t_prod.record(prod)
+                t_end.record(exch)
+            fin.record(exch)
+            main_stream.wait_event(fin)
+            main_stream.wait_stream(prod)
+
+        def serial(i, timed=False):
+            s = i % n_sets
+            if timed:
+                t_start.record(main_stream)
+            for grp in groups:
+                px.pack_fp16(grp, grad_sets[s], pack_sets[s], stream=stream)
+            if timed:
+                t_prod.record(main_stream)
+            px.reduce_avg(table, pack_sets[s], s_avg, px.AVG, stream=stream)
+            px.sgd_momentum(table, s_avg, s_w, s_v, cfg.lr, cfg.mu, cfg.wd, stream=stream)
+            if timed:
+                t_end.record(main_stream)
+
+        def timed_runs(fn):
+            for i in range(3):
+                fn(i)
+            total, exposed = [], []
+            for i in range(reps):
+                fn(3 + i, True)
+                torch.cuda.synchronize()
+                total.append(t_start.elapsed_time(t_end))
+                exposed.append(t_prod.elapsed_time(t_end))
+            return float(np.mean(total)), float(np.mean(exposed))
+
+        ov_total, ov_exposed = timed_runs(overlapped)
+        se_total, se_exposed = timed_runs(serial)
+        extras["overlap_with_producer"] = {
+            "groups": len(groups), "producer": "pack of each group on its own stream (an HBM-bound stand-in for "
+                                               "back-propagation, so it competes with the exchange for bandwidth; "
+                                               "a compute-bound producer would leave more of it to the exchange)",
+            "overlapped_total_ms": round(ov_total, 5), "exposed_exchange_ms": round(max(ov_exposed, 0.0), 5),
+            "serial_total_ms": round(se_total, 5), "serial_exchange_ms": round(se_exposed, 5),
+            "note": "exposed_exchange_ms: from the producer's last write to the end of the last update; "
+                    "serial: every group produced first, then one reduce and one update over the whole set"}
 
     # ---- one rank's real share of the exchange on a k-GPU node (the transfer legs left out): it packs its own
     # gradient (N elements), sums the k slices of N/k elements it received, and after the second leg updates
@@ -444,17 +660,18 @@ def main() -> int:
 
     for i in range(3):
         rank_step()
-    rank_ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
-    for i in range(args.steps):
+    rank_ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(reps)]
+    for i in range(reps):
         rank_step(rank_ev[i])
     torch.cuda.synchronize()
-    r_ms = [sum(e[q].elapsed_time(e[q + 1]) for e in rank_ev) / args.steps for q in range(3)]
+    r_ms = [sum(e[q].elapsed_time(e[q + 1]) for e in rank_ev) / reps for q in range(3)]
     r_bytes = [6 * n if half else 0, (wire_es * k + wire_es) * share, (wire_es + 16) * n]
-    fused["one_rank_share"] = {
+    extras["one_rank_share"] = {
         "ms": round(sum(r_ms), 5), "algorithmic_bytes": sum(r_bytes), "GBps": round(sum(r_bytes) / sum(r_ms) / 1e6, 1),
         "stages_ms": {"pack_own": round(r_ms[0], 5), "reduce_slice": round(r_ms[1], 5), "update_all": round(r_ms[2], 5)},
         "slice_elems": share,
         "note": f"pack of the rank's own gradient, reduce of {k} slices of N/{k} elements, update of all N"}
+    del slice_in, slice_out, slice_table
 
     # ---- the whole step captured once into a HIP graph and replayed (the calls allocate nothing and record
     # no memset): what is left of a step when the host's per-call cost is gone
@@ -466,55 +683,52 @@ def main() -> int:
             step(0, st=cap.cuda_stream)
     main_stream.wait_stream(cap)
     torch.cuda.synchronize()
-    for i in range(3):
-        graph.replay()
-    ev[0].record()
-    for i in range(args.steps):
-        graph.replay()
-    ev[1].record()
-    torch.cuda.synchronize()
-    ms = ev[0].elapsed_time(ev[1]) / args.steps
-    fused["step_from_hip_graph"] = {"ms": round(ms, 5), "algorithmic_bytes": step_bytes,
-                                    "GBps": round(step_bytes / ms / 1e6, 1),
-                                    "eager_ms": round(ms_per_step, 5)}
+    ms = clock.loop(lambda i: graph.replay())
+    extras["step_from_hip_graph"] = {"ms": round(ms, 5), "algorithmic_bytes": step_bytes,
+                                     "GBps": round(step_bytes / ms / 1e6, 1), "eager_ms": round(ms_per_step, 5)}
+    del graph
 
     # ---- a plain copy through the same kernel family (k = 1, no divide: out = in) as a
-    # reference for what HBM sustains here, and as the known-size kernel that the
-    # hardware-counter readings are scaled by
-    d_copy = [torch.empty(c_, dtype=torch.float32, device="cuda") for c_ in counts]
-    s_copy = table.bufset(d_copy)
-    for i in range(3):
-        px.reduce_avg(table, [grad_sets[0][i % k]], s_copy, px.SUM, stream=stream)
-    ev[0].record()
-    for i in range(args.steps):
-        px.reduce_avg(table, [grad_sets[i % len(grad_sets)][i % k]], s_copy, px.SUM, stream=stream)
-    ev[1].record()
-    torch.cuda.synchronize()
-    copy_ms = ev[0].elapsed_time(ev[1]) / args.steps
+    # reference for what HBM sustains here, and as the known-size kernel that counter readings can be checked on
+    copies = [table.bufset([torch.empty(c_, dtype=torch.float32, device="cuda") for c_ in counts]) for _ in range(3)]
+    sources = [g for gs in grad_sets for g in gs]
+    copy_ms = clock.loop(lambda i: px.reduce_avg(table, [sources[i % len(sources)]], copies[i % 3], px.SUM, stream=stream))
     copy_gbps = 8 * n / copy_ms / 1e6
 
     # ---- weight averaging (Section 4's other scheme): the same reduce over the k workers' float32 weights and
     # over their velocities (the float32 gradient buffers stand in for those), one launch each
-    for i in range(3):
-        px.reduce_avg(table, s_xs, s_copy, px.AVG, stream=stream)
-    ev[0].record()
-    for i in range(args.steps):
-        px.reduce_avg(table, s_xs if i % 2 == 0 else grad_sets[0], s_copy, px.AVG, stream=stream)
-    ev[1].record()
-    torch.cuda.synchronize()
-    ms = ev[0].elapsed_time(ev[1]) / args.steps
-    fb = (4 * k + 4) * n
-    fused["weight_averaging"] = {"ms": round(ms, 5), "algorithmic_bytes": fb, "GBps": round(fb / ms / 1e6, 1),
-                                 "frac_of_hbm_peak": round(fb / ms / 1e6 / HBM_PEAK_GBPS, 4),
-                                 "note": f"pxchg_reduce_avg over {k} float32 sets, per launch (weights, then velocities)"}
+    ms = clock.loop(lambda i: px.reduce_avg(table, s_xs if i % 2 == 0 else grad_sets[0], copies[i % 3], px.AVG, stream=stream))
+    extras["weight_averaging"] = dict(rate((4 * k + 4) * n, ms),
+                                      note=f"pxchg_reduce_avg over {k} float32 sets, per launch (weights, then velocities)")
+    del copies
+
+    # ---- the other configurations and model sizes: reduce+update (and the meeting), cold and warm
+    configs = None
+    if graded and not args.no_configs:
+        configs = {}
+        c1, c2, c4, c5 = wl.config(1), wl.config(2), wl.config(4), wl.config(5)
+        for name, cnts, kk, tr, lr_, mu_, wd_, al_, seed_, note in (
+                ("1_tiny_k2_f32", list(c1.counts), c1.k, c1.transfer, c1.lr, c1.mu, c1.wd, 0.0625, c1.seed,
+                 "12..21 MB per launch: bound by launch cost (about 4 us of host time per call), and cache-resident when warm"),
+                ("2_alexnet_k2_f32", list(c2.counts), c2.k, c2.transfer, c2.lr, c2.mu, c2.wd, 0.0, c2.seed, None),
+                ("4_many_small_k8_f16", list(c4.counts), c4.k, c4.transfer, c4.lr, c4.mu, c4.wd, 0.0625, c4.seed,
+                 "116 ragged tensors, one launch per stage; 126 MB per launch"),
+                ("5_alexnet_easgd_k8_f32", list(c5.counts), c5.k, c5.transfer, c5.lr, c5.mu, c5.wd, c5.alpha, c5.seed,
+                 "the meeting is this configuration's own step; reduce+update on its float32 buffers is weight averaging plus update"),
+                ("googlenet_count_k8_f16", wl.googlenet_scale_counts(c4.seed), 8, "f16", 0.01, 0.9, 0.0, 0.0625, c4.seed + 100,
+                 "Table 2's GoogLeNet count (13,378,280) over 128 ragged tensors"),
+                ("vggnet_k8_f16", wl.vggnet_counts(), 8, "f16", 0.01, 0.9, 0.0, 0.0625, c5.seed + 100,
+                 "Table 2's VGGNet count (138,357,544), 32 tensors")):
+            configs[name] = bench_config(px, torch, clock, name, cnts, kk, tr, lr_, mu_, wd_, al_, stream, seed_, note)
 
     # ---- the oracle on the host cores, same workload (a baseline, not a target)
     baseline = None
     if not args.no_cpu_baseline:
         t, t1 = cpu_baseline(counts, host_grads0, w, v, xs, c, [int(j) for j in orders[0]], cfg, alpha, threads)
         cpu_ru = ru_bytes / (t["reduce"] + t["update"]) / 1e9
-        baseline = {"value": round(cpu_ru, 2), "unit": "GB/s", "cores": threads, "kind": "oracle",
-                    "sample": "the full workload, one step, element range split over the threads, best of 2 "
+        baseline = {"value": round(cpu_ru, 2), "unit": "GB/s", "cores": threads, "cores_available": cores_available,
+                    "kind": "oracle",
+                    "sample": "the full workload, one step, element range split over the threads, best of 3 "
                               "per stage (same byte accounting as the GPU figure)",
                     "stage_seconds": {kk: round(vv, 4) for kk, vv in t.items()},
                     "step_GBps": round(step_bytes / sum(t.values()) / 1e9, 2),
@@ -537,18 +751,26 @@ def main() -> int:
         "config": {"workload": workload_name, "transfer_dtype": cfg.transfer, "n_params": n, "n_tensors": len(counts), "k": k,
                    "step": (f"pack x{k} -> " if half else "") + f"reduce_avg {cfg.transfer}->{cfg.transfer} -> "
                            f"sgd_momentum ({cfg.transfer} grad) -> {k} easgd meetings",
-                   "gradient_sets": len(grad_sets), "chunk_elems": px.get_option(px.OPT_CHUNK_ELEMS),
+                   "gradient_sets": len(grad_sets), "state_sets_for_cold_figures": n_rot,
+                   "chunk_elems": px.get_option(px.OPT_CHUNK_ELEMS),
                    "blocks_per_cu": px.get_option(px.OPT_BLOCKS_PER_CU),
                    "nontemporal": px.get_option(px.OPT_NONTEMPORAL),
                    "seed": cfg.seed, "numpy": np.__version__},
         "value_frac_of_hbm_peak": round(value / HBM_PEAK_GBPS, 4),
+        "value_cold": round(value_cold, 1),
+        "value_cold_frac_of_hbm_peak": round(value_cold / HBM_PEAK_GBPS, 4),
+        "value_note": "value: reduce and update inside the step, as an exchange runs them (the update reads the mean the "
+                      "reduce has just written, partly from the memory-side cache); value_cold: each of the two alone, "
+                      "every operand rotating out of the caches",
         "reduce_update_ms": round(ru_ms, 5),
+        "reduce_update_cold_ms": round(ru_cold_ms, 5),
         "step_GBps": round(step_bytes / (ms_per_step * 1e-3) / 1e9, 1),
         "roofline": roofline,
         "stages": stages,
-        "extras": fused,
+        "extras": extras,
+        "configs": configs,
         "copy_reference": {"what": "plain float32 copy of the same tensor set (pxchg_reduce_avg, k=1, sum), "
-                                   "read+write bytes", "kernel": "pxchg_reduce_avg_kernel<1,float,float>",
+                                   "read+write bytes, cold operands", "kernel": "pxchg_reduce_avg_kernel<1,float,float>",
                            "ms": round(copy_ms, 5), "bytes": 8 * n, "GBps": round(copy_gbps, 1),
                            "frac_of_hbm_peak": round(copy_gbps / HBM_PEAK_GBPS, 4)},
         "cpu_baseline": baseline,

@@ -285,8 +285,12 @@ int pxchg_reduce_avg_sgd_momentum(const pxchg_table *table, int k, const pxchg_b
  * the device, on different streams, would share that memory: give such calls
  * separate tables, or order them.
  */
+#ifndef PXCHG_STATS_WAVES
 #define PXCHG_STATS_WAVES 4            /* wavefronts, and so 64-lane accumulator groups, per block */
-#define PXCHG_STATS_BLOCK_CHUNKS 64    /* consecutive chunks per block */
+#endif
+#ifndef PXCHG_STATS_BLOCK_CHUNKS
+#define PXCHG_STATS_BLOCK_CHUNKS 32    /* consecutive chunks per block */
+#endif
 #define PXCHG_STATS_COMBINE_THREADS 1024 /* T of the final combine */
 typedef struct pxchg_stats {
     uint64_t nonfinite;
@@ -305,7 +309,7 @@ int pxchg_buffer_stats(const pxchg_table *table, const pxchg_bufset *set, pxchg_
  * copy per GPU, held until the process ends.  Same arguments, same results, bit for bit.  The call allocates and
  * frees nothing, on the device or through any library.  The array's address on the current device is looked up
  * once per device: by pxchg_table_create, or else by the first call on that device.
- * Limits: a chunk list of more than PXCHG_STATS_STATIC_MAX_BLOCKS * PXCHG_STATS_BLOCK_CHUNKS chunks (536,870,912
+ * Limits: a chunk list of more than PXCHG_STATS_STATIC_MAX_BLOCKS * PXCHG_STATS_BLOCK_CHUNKS chunks (268,435,456
  * elements at the default chunk size) is PXCHG_ERR_UNSUPPORTED and launches nothing; use pxchg_buffer_stats.
  * Every call on a GPU shares that GPU's array, whatever the table: calls that may overlap on one GPU (different
  * streams) race on it, so order them.  Nothing in the array needs clearing between calls: each call writes the

@@ -254,10 +254,11 @@ class Table:
 
     def bucketed_views(self, min_elems: int, reverse: bool = True) -> List["Table"]:
         """Views that together cover every tensor once, each a run of consecutive tensors with at least
-        `min_elems` elements (the last run formed may be shorter and is then merged into its neighbour): the
-        groups in which a layer-by-layer exchange should be issued, so that small layers share a launch.
-        reverse=True forms and returns the runs from the last tensor backwards, the order in which
-        back-propagation produces gradients."""
+        `min_elems` elements (the last run formed holds what is left and may be smaller): the groups in which
+        a layer-by-layer exchange should be issued, so that small layers share a launch.  reverse=True forms
+        and returns the runs from the last tensor backwards, the order in which back-propagation produces
+        gradients; the small last run is then the first layers, whose exchange is all that is left to wait for
+        when back-propagation ends."""
         order = list(range(len(self.counts)))
         if reverse:
             order.reverse()
@@ -269,10 +270,7 @@ class Table:
                 runs.append(cur)
                 cur, size = [], 0
         if cur:
-            if runs:
-                runs[-1].extend(cur)
-            else:
-                runs.append(cur)
+            runs.append(cur)
         return [self.view(min(r), len(r)) for r in runs]
 
     def close(self) -> None:

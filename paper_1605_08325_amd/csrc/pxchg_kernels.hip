@@ -190,6 +190,8 @@ __device__ __forceinline__ FV<U> loadv(const _Float16 *p) {
 }
 template <int NT, int U, bool SPLIT>
 __device__ __forceinline__ void storev(float *p, const FV<U> &x) {
+    static_assert(U == 1 || U == 2 || U == 4 || U == 8, "4 or 8 bytes, or one or two 16-byte vectors");
+    static_assert(!SPLIT || U == 8, "the split layout is two groups of four");
     if constexpr (U == 1) {
         stv<NT>((PX_GLOBAL float *)p, x.v[0]);
     } else if constexpr (U == 2) {
@@ -209,6 +211,10 @@ __device__ __forceinline__ void storev(float *p, const FV<U> &x) {
 }
 template <int NT, int U, bool SPLIT>
 __device__ __forceinline__ void storev(_Float16 *p, const FV<U> &x) {
+    // no narrower form exists: a lane layout with fewer than four binary16 elements per lane must not compile
+    // (the 16-byte branch below would store eight elements whatever U says)
+    static_assert(U == 4 || U == 8, "8 or 16 bytes");
+    static_assert(!SPLIT || U == 8, "the split layout is two groups of four");
     if constexpr (U == 4 || SPLIT) {
         f16x4 a;
 #pragma unroll
@@ -365,6 +371,9 @@ __global__ __launch_bounds__(64) void pxchg_convert_kernel(const PxChunk *__rest
 template <int K, typename TI, typename TO>
 constexpr int reduce_lanes() {
     if (std::is_same<TI, float>::value && std::is_same<TO, float>::value && K >= 4) return 256;
+#ifdef PXCHG_TUNE_REDUCE16_LANES  // A/B builds only (paper_1605_08325_amd/tune.py): 64 or 128
+    if (!touches_f32<TI, TO>() && !(K >= 1 && K <= 3)) return PXCHG_TUNE_REDUCE16_LANES;
+#endif
     return (touches_f32<TI, TO>() || (K >= 1 && K <= 3)) ? 64 : 128;
 }
 
@@ -569,7 +578,11 @@ struct UpdateOp {
 // Lanes beyond the working ones still take part in the element-wise paths.
 template <typename TG>
 constexpr int update_lanes() {  // 128 working lanes; as many idle ones for a binary16 gradient
+#ifdef PXCHG_TUNE_NO_IDLE  // A/B builds only: no idle wavefronts anywhere
+    return 128;
+#else
     return std::is_same<TG, _Float16>::value ? 256 : 128;
+#endif
 }
 
 template <typename TG, int NT>
@@ -661,6 +674,9 @@ struct FusedOp {
 // the split layout and k = 1 runs as two wavefronts of 4-element lanes (+4 %).
 template <int K, typename TI>
 constexpr int fused_lanes() {
+#ifdef PXCHG_TUNE_FUSED_LANES  // A/B builds only: 64 (split layout), 128 or 256 for three or more workers
+    if (K >= 3) return PXCHG_TUNE_FUSED_LANES;
+#endif
     if (std::is_same<TI, float>::value) return 256;
     return K == 1 ? 128 : K == 2 ? 64 : 256;
 }
@@ -790,17 +806,37 @@ __global__ __launch_bounds__(128) void pxchg_reduce_avg_sgd_momentum_anyk_kernel
 
 // ---------------------------------------------------------------- elastic averaging
 
-// Lanes per 512-element chunk in the elastic kernels: a wavefront should load 2..4 KiB in all, so the more
-// workers a fused round has, the narrower its lanes (a round of 8 with 4-byte lanes measured 7 % faster than
-// with the split layout of one wavefront).
+// Workgroup shape of the elastic kernels: a wavefront should load 2..4 KiB in all, so the more workers a fused
+// round has, the narrower its lanes (a round of 8 with 4-byte lanes measured 7 % faster than with the split
+// layout of one wavefront, and 6..9 % faster than with 8- or 16-byte lanes).  Rounds of five or more workers
+// also cut every chunk into two parts, one workgroup of 256 lanes each: the same 4-byte lanes in workgroups of
+// four wavefronts instead of eight measured 2 % faster (cold operands, round of 8: 710.6 against 726.2 us).
 template <int K>
-constexpr int elastic_lanes() {
-    return K <= 2 ? 128 : K <= 4 ? 256 : 512;
+constexpr int elastic_parts() {  // workgroups per chunk
+#ifdef PXCHG_TUNE_ELASTIC8_PARTS  // A/B builds only: 1 or 2
+    return K >= 5 ? PXCHG_TUNE_ELASTIC8_PARTS : 1;
+#else
+    return K >= 5 ? 2 : 1;
+#endif
+}
+template <int K>
+constexpr int elastic_lanes() {  // working lanes per workgroup
+#ifdef PXCHG_TUNE_ELASTIC8_LANES  // A/B builds only: 128, 256 or 512 lanes per chunk for rounds of five or more
+    if (K >= 5) return PXCHG_TUNE_ELASTIC8_LANES / elastic_parts<K>();
+#endif
+#ifdef PXCHG_TUNE_ELASTIC1_LANES  // A/B builds only: 64, 128 or 256 for the single meeting
+    if (K == 1) return PXCHG_TUNE_ELASTIC1_LANES;
+#endif
+    return K <= 2 ? 128 : K <= 4 ? 256 : 512 / elastic_parts<K>();
 }
 
 template <int K>
 constexpr int elastic_pad() {  // workgroup size over working lanes: one idle wavefront per working one (see update_lanes)
+#ifdef PXCHG_TUNE_NO_IDLE
+    return 1;
+#else
     return K <= 2 ? 2 : 1;
+#endif
 }
 
 struct ElasticArgs {
@@ -808,6 +844,7 @@ struct ElasticArgs {
     void *const *c;
     int k;
     float alpha;
+    int part_elems;  // elements per workgroup where a chunk is cut into parts: the table's chunk size over the parts
 };
 
 // CR ("center resident"): the center is read with plain loads and written with agent-scope stores, whatever
@@ -854,10 +891,17 @@ struct ElasticOp {
 template <int K, int NT, bool CR>
 __global__ __launch_bounds__((elastic_lanes<K>() * elastic_pad<K>())) void pxchg_easgd_kernel(const PxChunk *__restrict__ chunks,
                                                                         int n_chunks, ElasticArgs args) {
-    constexpr int U = 512 / elastic_lanes<K>(), NTH = elastic_lanes<K>() * elastic_pad<K>();
+    constexpr int PARTS = elastic_parts<K>();
+    constexpr int U = 512 / (elastic_lanes<K>() * PARTS), NTH = elastic_lanes<K>() * elastic_pad<K>();
     constexpr bool SPLIT = false;
-    for (int c = blockIdx.x; c < n_chunks; c += gridDim.x) {
-        const PxChunk ch = chunks[c];
+    for (int vc = blockIdx.x; vc < n_chunks * PARTS; vc += gridDim.x) {
+        PxChunk ch = chunks[vc / PARTS];
+        if constexpr (PARTS > 1) {  // this workgroup's part of the chunk (uniform over the workgroup)
+            const int off = (vc % PARTS) * args.part_elems;
+            if (off >= ch.len) continue;
+            ch.start += off;
+            ch.len = ch.len - off < args.part_elems ? ch.len - off : args.part_elems;
+        }
         ElasticOp<K, NT, U, CR> op;
         op.c = table_ptr<float>(args.c, ch.tensor) + ch.start;
         op.alpha = args.alpha;
@@ -902,7 +946,9 @@ __device__ __forceinline__ void stats_take(StatsAcc &a, float x) {
 // A whole 512-element chunk is therefore one 16-byte load per lane for binary16 (lane l: elements 8l..8l+7) and
 // two for float32 (4l..4l+3 and 256+4l..256+4l+3, each instruction covering a contiguous 1 KiB): the owner rule
 // is the coalesced layout.  A binary16 wavefront takes two of its chunks per trip (2 KiB of loads in flight;
-// one chunk per trip measured 9 % slower, 4 and 8 KiB 5..10 % slower).
+// one chunk per trip measured 9 % slower, 4 KiB 5 % slower).  Block shape, measured on 122 MB / 14 MB of
+// binary16 (both launches, microseconds): 4 wavefronts x 32 chunks 27.9 / 14.2, 4 x 64 27.9 / 18.0, 8 x 64
+// 28.6 / 13.6, 8 x 32 31.0 / 11.4, 16 x 64 32.9 / 11.3, 16 x 256 28.2 / 21.1, 2 x 16 29.8 / 14.3.
 constexpr int STATS_WAVES = PXCHG_STATS_WAVES, STATS_BLOCK_CHUNKS = PXCHG_STATS_BLOCK_CHUNKS;
 constexpr int STATS_COMBINE_THREADS = PXCHG_STATS_COMBINE_THREADS;
 static_assert(STATS_COMBINE_THREADS % 64 == 0 && STATS_COMBINE_THREADS <= 1024, "whole wavefronts, one workgroup");
@@ -961,7 +1007,11 @@ __global__ __launch_bounds__(STATS_WAVES * 64) void pxchg_stats_partial_kernel(c
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // the same in all 64 lanes: keep it scalar
     constexpr bool F32 = std::is_same<T, float>::value;
+#ifdef PX_STATS_TRIP
+    constexpr int G = PX_STATS_TRIP;  // chunks per trip (tuning)
+#else
     constexpr int G = F32 ? 1 : 2;  // chunks per trip
+#endif
     const int n_blocks = (n_chunks + STATS_BLOCK_CHUNKS - 1) / STATS_BLOCK_CHUNKS;
     for (int b = blockIdx.x; b < n_blocks; b += gridDim.x) {
         const int first = b * STATS_BLOCK_CHUNKS;
@@ -1141,13 +1191,17 @@ int launch_convert(const pxchg_table *t, int k, const pxchg_bufset *const *src, 
 #undef PX_CALL
 }
 
+#ifndef PXCHG_TUNE_REDUCE_POLICY  // A/B builds only: the reduce's own store policy (3, 4 or 5)
+#define PXCHG_TUNE_REDUCE_POLICY NT_LOADS_SC1_STORES
+#endif
+
 template <int K, typename TI, typename TO>
 int launch_reduce_k(const pxchg_table *t, const ReduceArgs &a, hipStream_t stream) {
     const dim3 grid = grid_for(t, t->n_chunks);
 #define PX_CALL(N)                                                                                                       \
     px_launch(pxchg_reduce_avg_kernel<K, TI, TO, N>, grid, dim3(reduce_lanes<K, TI, TO>()), stream, (const PxChunk *)t->d_chunks, \
               (int)t->n_chunks, a)
-    PX_DISPATCH_NT(NT_LOADS_SC1_STORES, PX_CALL)
+    PX_DISPATCH_NT(PXCHG_TUNE_REDUCE_POLICY, PX_CALL)
 #undef PX_CALL
 }
 
@@ -1213,11 +1267,13 @@ int launch_fused(const pxchg_table *t, int k, const FusedArgs &a, hipStream_t st
 
 template <int K, bool CR>
 int launch_elastic_kc(const pxchg_table *t, const ElasticArgs &a, hipStream_t stream) {
-    const dim3 grid = grid_for(t, t->n_chunks);
+    const dim3 grid = grid_for(t, t->n_chunks * elastic_parts<K>());
+    ElasticArgs b = a;
+    b.part_elems = (int)(t->chunk_elems / elastic_parts<K>());  // elements per workgroup
     constexpr int OWN = K == 2 ? NT_BOTH : NT_LOADS_SC1NT_STORES;
 #define PX_CALL(N)                                                                                                      \
     px_launch(pxchg_easgd_kernel<K, N, CR>, grid, dim3(elastic_lanes<K>() * elastic_pad<K>()), stream, (const PxChunk *)t->d_chunks, \
-              (int)t->n_chunks, a)
+              (int)t->n_chunks, b)
     PX_DISPATCH_NT(OWN, PX_CALL)
 #undef PX_CALL
 }
@@ -1433,6 +1489,7 @@ int pxchg_easgd_round(const pxchg_table *table, int k, pxchg_bufset *const *x, p
         a.c = (void *const *)c->d_ptrs;
         a.k = kk;
         a.alpha = alpha;
+        a.part_elems = 0;  // set per kernel shape at the launch
         switch (kk) {
             case 1: rc = launch_elastic_k<1>(table, a, s); break;
             case 2: rc = launch_elastic_k<2>(table, a, s); break;
