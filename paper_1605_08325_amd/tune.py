@@ -8,14 +8,16 @@ workgroups per chunk) is only ever compared with its alternatives in alternating
 compiles the library once per alternative (the kernels' source has `PXCHG_TUNE_*` hooks for exactly these) into
 paper_1605_08325_amd/_build/tune/<name>/libpxchg.so, and
 
-    python -m paper_1605_08325_amd.tune --run [--policies] [--shape alexnet|small]
+    python -m paper_1605_08325_amd.tune --run [--policies | --launch-shapes] [--shape alexnet|small|vggnet|googlenet]
 
 first checks that every alternative produces the same bits as the shipped shape on the same inputs, then times
 the exchange calls for each in alternating rounds and prints the medians and the spread: `cold` with every operand
 rotating over more than 1 GB (a pure HBM figure), `in step` for reduce -> update back to back on one operand
 set (what the benchmark's step does).  --policies does the same for the six cache policies with the tuning
-build of the library (tests/_build/libpxchg_allpolicies.so).  Inputs are N(0, 0.01^2) draws made on the device
-from a fixed seed, AlexNet-shaped (61 M parameters, 16 tensors, k = 8) or the 116-tensor set of 7 M.
+build of the library (tests/_build/libpxchg_allpolicies.so), --launch-shapes for the regular library under other
+chunk sizes and persistent grids (PXCHG_OPT_CHUNK_ELEMS, PXCHG_OPT_BLOCKS_PER_CU).  Inputs are N(0, 0.01^2) draws made on the device
+from a fixed seed, AlexNet-shaped (61 M parameters, 16 tensors, k = 8), the 116-tensor set of 7 M, VGGNet-shaped
+(138 M) or the GoogLeNet count (13.4 M in 128 tensors).
 The summaries under profiles/ that justify the shipped choices are this tool's output.
 """
 from __future__ import annotations
@@ -47,6 +49,10 @@ VARIANTS = {
     "round8_one_part_128_lanes": ["-DPXCHG_TUNE_ELASTIC8_PARTS=1", "-DPXCHG_TUNE_ELASTIC8_LANES=128"],
     "reduce_policy_3": ["-DPXCHG_TUNE_REDUCE_POLICY=3"],
     "reduce_policy_4": ["-DPXCHG_TUNE_REDUCE_POLICY=4"],
+    # block shapes of the diagnostics (they are part of that call's definition: the sum's bits differ, by design)
+    "diagnostics_4_waves_64_chunks": ["-DPXCHG_STATS_BLOCK_CHUNKS=64"],
+    "diagnostics_8_waves_64_chunks": ["-DPXCHG_STATS_WAVES=8", "-DPXCHG_STATS_BLOCK_CHUNKS=64"],
+    "diagnostics_16_waves_256_chunks": ["-DPXCHG_STATS_WAVES=16", "-DPXCHG_STATS_BLOCK_CHUNKS=256"],
 }
 
 
@@ -82,7 +88,8 @@ def run(args) -> int:
     import workloads as wl
 
     torch.cuda.set_device(0)
-    counts = wl.alexnet_counts() if args.shape == "alexnet" else list(wl.config(4).counts)
+    counts = {"alexnet": wl.alexnet_counts, "small": lambda: list(wl.config(4).counts), "vggnet": wl.vggnet_counts,
+              "googlenet": lambda: wl.googlenet_scale_counts(wl.config(4).seed)}[args.shape]()
     n, k = sum(counts), 8
     gen = torch.Generator(device="cuda")
     gen.manual_seed(20160526)
@@ -98,6 +105,7 @@ def run(args) -> int:
     big = n > 30_000_000
     n_in, n_state = (2, 3) if big else (10, 24)     # operand sets to rotate over: more than 1 GB between two uses
     halves = [[draw(torch.float16) for _ in range(k)] for _ in range(n_in)]
+    packed = [[[torch.empty_like(t) for t in ts] for ts in s] for s in halves] if big else None    # the pack's output
     floats = [draw(torch.float32) for _ in range(k)]
     state = [(draw(torch.float32), draw(torch.float32), draw(torch.float16), draw(torch.float32)) for _ in range(n_state)]
     pristine = [[t.clone() for t in ts] for ts in (*state[0], *floats)]
@@ -114,7 +122,13 @@ def run(args) -> int:
         torch.cuda.synchronize()
         return ev[0].elapsed_time(ev[1]) / args.reps * 1e3
 
-    if args.policies:
+    shapes = {}
+    if args.launch_shapes:
+        # the regular library under other launch shapes: elements per chunk, persistent workgroups per compute unit
+        shapes = {f"chunk {c:5d}, {w:2d} wg/CU" if w else f"chunk {c:5d}, one wg per chunk": (c, w)
+                  for c, w in ((512, 0), (1024, 0), (2048, 0), (512, 8), (512, 16), (512, 32), (1024, 8), (2048, 4), (4096, 4))}
+        libs = {nm: (px.library_path(), -1) for nm in shapes}
+    elif args.policies:
         from paper_1605_08325_amd import build as b
         libs = {f"policy {p}" if p >= 0 else "own policy": (b.ALL_POLICIES_LIB, p) for p in (-1, 0, 1, 2, 3, 4, 5)}
     else:
@@ -122,14 +136,20 @@ def run(args) -> int:
         libs = {nm: (os.path.join(TUNE_DIR, nm, "libpxchg.so"), -1) for nm in names}
     opened = {}
     results, reference = {}, None
-    columns = ["pack", "reduce", "update", "meeting", "fused r+u", "round of 8", "in-step reduce", "in-step update"]
+    columns = ["pack", "reduce", "update", "meeting", "fused r+u", "round of 8", "diagnostics", "in-step reduce",
+               "in-step update"]
+    d_stats = torch.zeros(3, dtype=torch.int64, device="cuda")
     for rnd in range(args.rounds):
         for nm, (path, policy) in libs.items():
             lib = opened.setdefault(path, px.open_library(path))
             with px.using(lib):
                 px.set_option(px.OPT_NONTEMPORAL, policy)
+                if nm in shapes:
+                    px.set_option(px.OPT_CHUNK_ELEMS, shapes[nm][0])
+                    px.set_option(px.OPT_BLOCKS_PER_CU, shapes[nm][1])
                 table = px.Table(counts)
                 hs = [[table.bufset(t) for t in s] for s in halves]
+                ps = [[table.bufset(t) for t in s] for s in packed] if big else None
                 fs = [table.bufset(t) for t in floats]
                 st = [tuple(table.bufset(t) for t in s) for s in state]
                 if rnd == 0:
@@ -154,7 +174,7 @@ def run(args) -> int:
                                     return 1
                     del sw, sv, sm, sc, sx
                 row = [
-                    loop(lambda i: px.pack_fp16(table, fs, hs[i % n_in], stream=stream)) if big else float("nan"),
+                    loop(lambda i: px.pack_fp16(table, fs, ps[i % n_in], stream=stream)) if big else float("nan"),
                     loop(lambda i: px.reduce_avg(table, hs[i % n_in], st[i % n_state][2], px.AVG, stream=stream)),
                     loop(lambda i: px.sgd_momentum(table, st[i % n_state][2], st[i % n_state][0], st[i % n_state][1], 0.01, 0.9,
                                                    0.0, stream=stream)),
@@ -162,6 +182,7 @@ def run(args) -> int:
                     loop(lambda i: px.reduce_avg_sgd_momentum(table, hs[i % n_in], st[i % n_state][0], st[i % n_state][1], 0.01,
                                                               0.9, 0.0, px.AVG, px.F16, stream=stream)),
                     loop(lambda i: px.easgd_round(table, fs, st[i % n_state][3], 0.0625, stream=stream)),
+                    loop(lambda i: px.buffer_stats(table, hs[i % n_in][i % k], d_stats, stream=stream)),
                 ]
                 # reduce -> update back to back on one state set, as the benchmark's step runs them
                 acc = [0.0, 0.0]
@@ -178,7 +199,9 @@ def run(args) -> int:
                 row += [acc[0] / args.reps * 1e3, acc[1] / args.reps * 1e3]
                 results.setdefault(nm, []).append(row)
                 px.set_option(px.OPT_NONTEMPORAL, -1)
-                del hs, fs, st, table
+                px.set_option(px.OPT_CHUNK_ELEMS, 512)
+                px.set_option(px.OPT_BLOCKS_PER_CU, 0)
+                del hs, ps, fs, st, table
         print(f"round {rnd + 1} of {args.rounds} done", flush=True)
 
     print(f"\n{args.shape}: {n} parameters in {len(counts)} tensors, k = {k}; microseconds per launch, median of "
@@ -198,8 +221,10 @@ def main() -> int:
     ap.add_argument("--build", action="store_true", help="compile the alternatives (hipcc; no GPU needed)")
     ap.add_argument("--run", action="store_true", help="check and time them on the GPU")
     ap.add_argument("--policies", action="store_true", help="time the six cache policies of the tuning build instead")
+    ap.add_argument("--launch-shapes", action="store_true",
+                    help="time the regular library under other chunk sizes and persistent grids instead")
     ap.add_argument("--variants", default="", help="comma-separated subset of: " + ", ".join(VARIANTS))
-    ap.add_argument("--shape", default="alexnet", choices=["alexnet", "small"])
+    ap.add_argument("--shape", default="alexnet", choices=["alexnet", "small", "vggnet", "googlenet"])
     ap.add_argument("--rounds", type=int, default=3)
     ap.add_argument("--reps", type=int, default=30)
     args = ap.parse_args()

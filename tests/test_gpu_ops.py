@@ -750,6 +750,48 @@ def test_views_exchange_layer_by_layer_with_the_parents_sets(px, oracle_mod):
     assert all(np.all(b == 7.0) for t, b in enumerate(back) if not 3 <= t < 6)
 
 
+def test_grouped_views_cover_the_set_and_exchange_like_the_whole_set(px, oracle_mod):
+    """Table.bucketed_views: runs of consecutive tensors of at least a given size, formed from the last tensor
+    backwards (the order in which back-propagation hands gradients over), small layers sharing a group.  The
+    AlexNet shapes give three groups; a producer stream packs each group and the exchange stream reduces and
+    updates it as soon as its event fires; the result equals the oracle on the whole set."""
+    import torch
+    counts = wl.alexnet_counts()
+    table = px.Table(counts)
+    groups = table.bucketed_views(8_000_000)
+    assert [(g.counts[0], len(g.counts)) for g in groups] == [(16_777_216, 4), (37_748_736, 2), (34_848, 10)]
+    assert sum(g.total for g in groups) == sum(counts) and sum(g.n_chunks for g in groups) == table.n_chunks
+    assert [g.total for g in table.bucketed_views(10 ** 9)] == [sum(counts)]            # one group if nothing is big enough
+    assert len(table.bucketed_views(1)) == len(counts)                                  # every tensor its own group
+    assert [len(g.counts) for g in table.bucketed_views(8_000_000, reverse=False)] == [11, 2, 3]
+    k = 3
+    grads = [_gauss(counts, 1300, w) for w in range(k)]
+    w, v = _gauss(counts, 1301, role="param"), wl.zeros_tensors(counts)
+    d_g = [to_device(g) for g in grads]
+    d_h = [empty_like_device(counts, np.float16) for _ in range(k)]
+    d_avg, d_w, d_v = empty_like_device(counts, np.float16), to_device(w), to_device(v)
+    s_g, s_h = [table.bufset(t) for t in d_g], [table.bufset(t) for t in d_h]
+    s_avg, s_w, s_v = table.bufset(d_avg), table.bufset(d_w), table.bufset(d_v)
+    producer, exchange = torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+    for gi, grp in enumerate(groups):
+        px.pack_fp16(grp, s_g, s_h, stream=producer)
+        ready = torch.cuda.Event()
+        ready.record(producer)
+        exchange.wait_event(ready)
+        if gi == 1:
+            px.reduce_avg_sgd_momentum(grp, s_h, s_w, s_v, 0.01, 0.9, 5e-4, px.AVG, px.F16, stream=exchange)
+        else:
+            px.reduce_avg(grp, s_h, s_avg, stream=exchange)
+            px.sgd_momentum(grp, s_avg, s_w, s_v, 0.01, 0.9, 5e-4, stream=exchange)
+    exchange.synchronize()
+    packed = [oracle_mod.pack_fp16_tensors(g) for g in grads]
+    avg = oracle_mod.reduce_avg_tensors(packed, np.float16)
+    oracle_mod.sgd_momentum_tensors(avg, w, v, 0.01, 0.9, 5e-4)
+    assert_bits_equal(to_host(d_w), w, "w")
+    assert_bits_equal(to_host(d_v), v, "v")
+
+
 def test_view_argument_errors(px):
     import torch
     table = px.Table([100, 200, 300])
