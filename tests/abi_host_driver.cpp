@@ -7,11 +7,14 @@
 // destroyed.  Prints "ok" and exits 0 when every check holds and the sanitizers saw nothing.
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cstdint>
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
 #include <map>
+#include <mutex>
+#include <thread>
 #include <vector>
 
 #include "pxchg.h"
@@ -20,8 +23,9 @@
 
 namespace fake {
 int current_device = 0;
+std::mutex mu;                            // the real runtime is thread-safe; so is this one
 std::map<uintptr_t, size_t> allocations;  // base -> size
-int launches = 0, get_last_error_calls = 0, synchronizes = 0, symbol_lookups = 0, mallocs = 0;
+std::atomic<int> launches{0}, get_last_error_calls{0}, synchronizes{0}, symbol_lookups{0}, mallocs{0};
 bool fail_next_launch = false;
 dim3 last_grid, last_block;
 std::vector<dim3> grids;
@@ -40,12 +44,16 @@ hipError_t hipMalloc(void **ptr, size_t size) {
     *ptr = std::malloc(size ? size : 1);
     if (!*ptr) return hipErrorOutOfMemory;
     ++fake::mallocs;
+    std::lock_guard<std::mutex> lock(fake::mu);
     fake::allocations[(uintptr_t)*ptr] = size;
     return hipSuccess;
 }
 hipError_t hipFree(void *ptr) {
     if (!ptr) return hipSuccess;
-    if (!fake::allocations.erase((uintptr_t)ptr)) return hipErrorInvalidValue;
+    {
+        std::lock_guard<std::mutex> lock(fake::mu);
+        if (!fake::allocations.erase((uintptr_t)ptr)) return hipErrorInvalidValue;
+    }
     std::free(ptr);
     return hipSuccess;
 }
@@ -63,6 +71,7 @@ hipError_t hipGetLastError(void) {
 }
 hipError_t hipMemGetAddressRange(hipDeviceptr_t *base, size_t *size, hipDeviceptr_t ptr) {
     const uintptr_t a = (uintptr_t)ptr;
+    std::lock_guard<std::mutex> lock(fake::mu);
     auto it = fake::allocations.upper_bound(a);
     if (it == fake::allocations.begin()) return hipErrorInvalidValue;
     --it;
@@ -80,6 +89,7 @@ hipError_t hipGetSymbolAddress(void **address, const void *symbol) {
 }
 hipError_t hipLaunchKernel(const void *function, dim3 grid, dim3 block, void **args, size_t, hipStream_t) {
     if (!function || !args) return hipErrorInvalidValue;
+    std::lock_guard<std::mutex> lock(fake::mu);
     if (fake::fail_next_launch) {
         fake::fail_next_launch = false;
         return hipErrorLaunchFailure;
@@ -473,11 +483,90 @@ int lifetime_and_launches() {
     return 0;
 }
 
+// Several threads use one table while others create and destroy tables, views and sets of their own, and one
+// keeps trying to destroy the shared table: calls on live handles succeed, the shared table stays (it has sets),
+// and a handle that another thread has destroyed is refused, not read.  Run under ThreadSanitizer as well.
+int threads_share_handles() {
+    const std::vector<int64_t> counts = {5000, 513, 0, 70001};
+    pxchg_table *shared = nullptr;
+    CHECK(pxchg_table_create((int)counts.size(), counts.data(), &shared) == PXCHG_OK);
+    Buffers fa(counts, 4), fb(counts, 4);
+    pxchg_bufset *a = nullptr, *b = nullptr;
+    CHECK(pxchg_bufset_create(shared, PXCHG_F32, fa.data(), &a) == PXCHG_OK);
+    CHECK(pxchg_bufset_create(shared, PXCHG_F32, fb.data(), &b) == PXCHG_OK);
+    std::atomic<int> failures{0};
+    std::atomic<pxchg_bufset *> passed_around{nullptr};
+    auto user = [&](int id) {
+        for (int i = 0; i < 300; ++i) {
+            if (pxchg_easgd(shared, a, b, 0.1f, nullptr) != PXCHG_OK) ++failures;
+            pxchg_table *view = nullptr;
+            if (pxchg_table_view(shared, id % 2, 2, &view) != PXCHG_OK) ++failures;
+            if (pxchg_easgd(view, a, b, 0.1f, nullptr) != PXCHG_OK) ++failures;
+            if (pxchg_table_destroy(view) != PXCHG_OK) ++failures;
+            if (pxchg_table_total(shared) != 5000 + 513 + 70001) ++failures;
+        }
+    };
+    auto maker = [&]() {
+        for (int i = 0; i < 100; ++i) {
+            pxchg_table *t = nullptr;
+            pxchg_bufset *x = nullptr, *y = nullptr;
+            if (pxchg_table_create((int)counts.size(), counts.data(), &t) != PXCHG_OK) ++failures;
+            if (pxchg_bufset_create(t, PXCHG_F32, fa.data(), &x) != PXCHG_OK) ++failures;
+            if (pxchg_bufset_create(t, PXCHG_F32, fb.data(), &y) != PXCHG_OK) ++failures;
+            if (pxchg_easgd(t, x, y, 0.1f, nullptr) != PXCHG_OK) ++failures;
+            if (pxchg_easgd(shared, x, y, 0.1f, nullptr) != PXCHG_ERR_SHAPE_MISMATCH) ++failures;   // another table's sets
+            if (pxchg_table_destroy(t) != PXCHG_ERR_IN_USE) ++failures;
+            // hand one set to the breaker thread, which may destroy it at any moment: whoever comes second is refused
+            pxchg_bufset *expected = nullptr;
+            const bool handed = passed_around.compare_exchange_strong(expected, y);
+            if (pxchg_bufset_destroy(x) != PXCHG_OK) ++failures;
+            if (handed) {
+                int rc;
+                while ((rc = pxchg_table_destroy(t)) == PXCHG_ERR_IN_USE) std::this_thread::yield();   // until y is gone
+                if (rc != PXCHG_OK) ++failures;
+            } else {
+                if (pxchg_bufset_destroy(y) != PXCHG_OK) ++failures;
+                if (pxchg_table_destroy(t) != PXCHG_OK) ++failures;
+            }
+        }
+    };
+    std::atomic<bool> stop{false};
+    auto breaker = [&]() {
+        while (!stop) {
+            if (pxchg_table_destroy(shared) != PXCHG_ERR_IN_USE) ++failures;     // it has sets: never goes
+            pxchg_bufset *y = passed_around.exchange(nullptr);
+            if (y) {
+                if (pxchg_bufset_destroy(y) != PXCHG_OK) ++failures;
+                if (pxchg_bufset_destroy(y) != PXCHG_ERR_INVALID_ARG) ++failures;   // twice
+                if (pxchg_easgd(shared, y, b, 0.1f, nullptr) != PXCHG_ERR_INVALID_ARG) ++failures;
+            }
+            std::this_thread::yield();
+        }
+    };
+    std::vector<std::thread> pool;
+    for (int id = 0; id < 3; ++id) pool.emplace_back(user, id);
+    pool.emplace_back(maker);
+    pool.emplace_back(maker);
+    std::thread br(breaker);
+    for (auto &t : pool) t.join();
+    stop = true;
+    br.join();
+    if (pxchg_bufset *left = passed_around.exchange(nullptr)) CHECK(pxchg_bufset_destroy(left) == PXCHG_OK);
+    CHECK(failures == 0);
+    CHECK(pxchg_bufset_destroy(a) == PXCHG_OK && pxchg_bufset_destroy(b) == PXCHG_OK);
+    CHECK(pxchg_table_destroy(shared) == PXCHG_OK);
+    return 0;
+}
+
 }  // namespace
 
-int main() {
-    if (options_and_planning()) return 1;
-    if (lifetime_and_launches()) return 1;
+int main(int argc, char **argv) {
+    const bool threads_only = argc > 1 && std::strcmp(argv[1], "threads") == 0;
+    if (!threads_only) {
+        if (options_and_planning()) return 1;
+        if (lifetime_and_launches()) return 1;
+    }
+    if (threads_share_handles()) return 1;
     if (!fake::allocations.empty()) {  // every device allocation of the library was returned
         std::printf("%zu device allocations were never freed\n", fake::allocations.size());
         return 1;

@@ -12,11 +12,10 @@ ROOT = os.path.dirname(HERE)
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 
-def test_host_code_is_clean_under_asan_and_ubsan(tmp_path):
-    exe = str(tmp_path / "abi_host")
+def build_driver(exe, sanitizers):
     csrc = os.path.join(ROOT, "paper_1605_08325_amd", "csrc")
-    cmd = [HIPCC, "--offload-arch=gfx950", "-O1", "-g", "-std=c++17",
-           "-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+    cmd = [HIPCC, "--offload-arch=gfx950", "-O1", "-g", "-std=c++17", "-pthread",
+           *[x for s_ in sanitizers for x in ("-Xarch_host", f"-fsanitize={s_}")],
            "-Xarch_host", "-fno-sanitize-recover=all",
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
            "-I", os.path.join(ROOT, "include"), "-I", csrc,
@@ -27,10 +26,27 @@ def test_host_code_is_clean_under_asan_and_ubsan(tmp_path):
     if build.returncode != 0 and "sanitize" in build.stderr and "cannot find" in build.stderr:
         pytest.skip("no sanitizer runtime for hipcc here")
     assert build.returncode == 0, build.stderr
+
+
+def test_host_code_is_clean_under_asan_and_ubsan(tmp_path):
+    exe = str(tmp_path / "abi_host")
+    build_driver(exe, ["address", "undefined"])
     # the HIP runtime keeps allocations until exit; leaks are not what this test is after
     env = dict(os.environ, ASAN_OPTIONS="detect_leaks=0")
     run = subprocess.run([exe], capture_output=True, text=True, timeout=300, env=env)
     if run.returncode != 0 and "runtime does not come first" in run.stderr:
         pytest.skip("another preloaded library precedes the sanitizer runtime in this environment")
+    assert run.returncode == 0, run.stdout + run.stderr
+    assert run.stdout.strip() == "ok"
+
+
+def test_handles_shared_between_threads_are_clean_under_tsan(tmp_path):
+    """Threads that use one table while others create and destroy their own, and one that keeps trying to destroy
+    the shared table and destroys sets handed to it: the registry's reader/writer lock orders all of it."""
+    exe = str(tmp_path / "abi_host_tsan")
+    build_driver(exe, ["thread"])
+    run = subprocess.run([exe, "threads"], capture_output=True, text=True, timeout=300)
+    if run.returncode != 0 and ("runtime does not come first" in run.stderr or "unexpected memory mapping" in run.stderr):
+        pytest.skip("ThreadSanitizer cannot start in this environment")
     assert run.returncode == 0, run.stdout + run.stderr
     assert run.stdout.strip() == "ok"
