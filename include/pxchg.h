@@ -118,6 +118,18 @@ int pxchg_plan_chunks(int n_tensors, const int64_t *counts /*host*/, int64_t chu
                       int32_t *chunk_len /*host*/, int64_t *n_chunks /*host*/);
 
 /*
+ * Host-only planning helper (no GPU needed) for a layer-wise exchange (Section 3.2 notes that the exchange could
+ * overlap with the rest of the step; back-propagation hands gradients over last layer first): cuts the tensor
+ * list into groups of consecutive tensors, each with at least `min_elems` elements in all, so that small layers
+ * share a launch; the last group formed holds what is left and may be smaller.  With `reverse` != 0 the groups
+ * are formed and listed from the last tensor backwards.  Writes up to `cap` groups into the two host arrays
+ * (first tensor and number of tensors of each group, as pxchg_table_view takes them; either may be NULL when
+ * cap == 0) and the total number of groups into *n_groups.
+ */
+int pxchg_plan_groups(int n_tensors, const int64_t *counts /*host*/, int64_t min_elems, int reverse, int cap,
+                      int32_t *group_first /*host*/, int32_t *group_n /*host*/, int *n_groups /*host*/);
+
+/*
  * Tensor table: element counts of the parameter set's tensors (Section 3.1: the
  * model's parameters are arrays in GPU memory, one per weight or bias).
  * `counts` is a host array of n_tensors non-negative counts (zero allowed).

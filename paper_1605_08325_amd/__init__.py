@@ -11,7 +11,7 @@ from .binding import (  # noqa: F401
     OPT_CHUNK_ELEMS, OPT_BLOCKS_PER_CU, OPT_CHECK_RANGES, OPT_NONTEMPORAL, OPT_CENTER_RESIDENT,
     OPT_ALL_POLICIES_BUILT, ERR_IN_USE, open_library, using,
     PxchgError, Table, BufSet,
-    load, library_path, version, set_option, get_option, plan_chunks, status_string,
+    load, library_path, version, set_option, get_option, plan_chunks, plan_groups, status_string,
     pack_fp16, unpack_fp16, reduce_avg, sgd_momentum, easgd, easgd_round,
     reduce_avg_sgd_momentum, buffer_stats, buffer_stats_static, read_stats, Stats, flush_deferred,
 )

@@ -31,6 +31,8 @@ SIGNATURES = {
     "pxchg_get_option": (_i64, [_int]),
     "pxchg_plan_chunks": (_int, [_int, ctypes.POINTER(_i64), _i64, _i64, ctypes.POINTER(ctypes.c_int32),
                                  ctypes.POINTER(_i64), ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(_i64)]),
+    "pxchg_plan_groups": (_int, [_int, ctypes.POINTER(_i64), _i64, _int, _int, ctypes.POINTER(ctypes.c_int32),
+                                 ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(_int)]),
     "pxchg_table_create": (_int, [_int, ctypes.POINTER(_i64), _pp]),
     "pxchg_table_destroy": (_int, [_vp]),
     "pxchg_table_view": (_int, [_vp, _int, _int, _pp]),
@@ -150,6 +152,21 @@ def plan_chunks(counts: Sequence[int], chunk_elems: int) -> Tuple[List[int], Lis
     return list(t[:m]), list(s[:m]), list(ln[:m])
 
 
+def plan_groups(counts: Sequence[int], min_elems: int, reverse: bool = True, lib=None) -> List[Tuple[int, int]]:
+    """Host-only: (first tensor, number of tensors) of every group of pxchg_plan_groups."""
+    lib = lib or load()
+    n = len(counts)
+    c = (_i64 * max(n, 1))(*counts)
+    total = _int(0)
+    _check(lib.pxchg_plan_groups(n, c, int(min_elems), int(bool(reverse)), 0, None, None, ctypes.byref(total)),
+           "pxchg_plan_groups")
+    m = total.value
+    first, num = (ctypes.c_int32 * max(m, 1))(), (ctypes.c_int32 * max(m, 1))()
+    _check(lib.pxchg_plan_groups(n, c, int(min_elems), int(bool(reverse)), m, first, num, ctypes.byref(total)),
+           "pxchg_plan_groups")
+    return [(int(first[i]), int(num[i])) for i in range(m)]
+
+
 def _stream_ptr(stream) -> Optional[int]:
     """None -> torch's current stream; an int is taken as a hipStream_t."""
     if stream is None:
@@ -253,25 +270,10 @@ class Table:
         return v
 
     def bucketed_views(self, min_elems: int, reverse: bool = True) -> List["Table"]:
-        """Views that together cover every tensor once, each a run of consecutive tensors with at least
-        `min_elems` elements (the last run formed holds what is left and may be smaller): the groups in which
-        a layer-by-layer exchange should be issued, so that small layers share a launch.  reverse=True forms
-        and returns the runs from the last tensor backwards, the order in which back-propagation produces
-        gradients; the small last run is then the first layers, whose exchange is all that is left to wait for
-        when back-propagation ends."""
-        order = list(range(len(self.counts)))
-        if reverse:
-            order.reverse()
-        runs, cur, size = [], [], 0
-        for t in order:
-            cur.append(t)
-            size += self.counts[t]
-            if size >= min_elems:
-                runs.append(cur)
-                cur, size = [], 0
-        if cur:
-            runs.append(cur)
-        return [self.view(min(r), len(r)) for r in runs]
+        """One view per group of pxchg_plan_groups: runs of consecutive tensors with at least `min_elems` elements
+        (the last group formed holds what is left), by default formed from the last tensor backwards, the order
+        in which back-propagation produces gradients."""
+        return [self.view(f, m) for f, m in plan_groups(self.counts, min_elems, reverse, self._lib)]
 
     def close(self) -> None:
         if self._h:

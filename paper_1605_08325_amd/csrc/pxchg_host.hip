@@ -138,6 +138,32 @@ int pxchg_plan_chunks(int n_tensors, const int64_t *counts, int64_t chunk_elems,
     return PXCHG_OK;
 }
 
+int pxchg_plan_groups(int n_tensors, const int64_t *counts, int64_t min_elems, int reverse, int cap, int32_t *group_first,
+                      int32_t *group_n, int *n_groups) {
+    if (n_tensors < 1 || !counts || !n_groups || cap < 0 || min_elems < 0) return PXCHG_ERR_INVALID_ARG;
+    if (cap > 0 && (!group_first || !group_n)) return PXCHG_ERR_INVALID_ARG;
+    for (int t = 0; t < n_tensors; ++t)
+        if (counts[t] < 0) return PXCHG_ERR_INVALID_ARG;
+    int n = 0, run = 0;      // groups closed so far; tensors in the open group
+    int64_t size = 0;        // elements in the open group
+    for (int i = 0; i < n_tensors; ++i) {
+        const int t = reverse ? n_tensors - 1 - i : i;
+        ++run;
+        size += counts[t];
+        if (size >= min_elems || i == n_tensors - 1) {   // close the group (the last one takes what is left)
+            if (n < cap) {
+                group_first[n] = reverse ? t : t - run + 1;   // a group is a run of consecutive tensors either way
+                group_n[n] = run;
+            }
+            ++n;
+            run = 0;
+            size = 0;
+        }
+    }
+    *n_groups = n;
+    return PXCHG_OK;
+}
+
 int pxchg_table_create(int n_tensors, const int64_t *counts, pxchg_table **out) {
     if (!out) return PXCHG_ERR_INVALID_ARG;
     *out = nullptr;

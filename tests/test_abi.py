@@ -117,6 +117,32 @@ def test_plan_chunks_matches_the_alexnet_table(px):
     assert len(t) == 119_076 and sum(ln) == wl.ALEXNET_PARAMS
 
 
+def test_plan_groups_cuts_the_tensor_list_into_runs_of_a_minimum_size(px):
+    import workloads as wl
+    counts = wl.alexnet_counts()
+    # from the last tensor backwards: fc8 + fc7 (20.9 M), fc6 (37.8 M), the five convolutions (2.3 M, what is left)
+    assert px.plan_groups(counts, 8_000_000) == [(12, 4), (10, 2), (0, 10)]
+    assert px.plan_groups(counts, 8_000_000, reverse=False) == [(0, 11), (11, 2), (13, 3)]
+    assert px.plan_groups(counts, 10 ** 9) == [(0, 16)]
+    assert px.plan_groups(counts, 1) == [(t, 1) for t in reversed(range(16))]
+    assert px.plan_groups(counts, 0, reverse=False) == [(t, 1) for t in range(16)]
+    for min_elems in (1, 5000, 300_000, 8_000_000, 40_000_000):
+        for reverse in (True, False):
+            groups = px.plan_groups(counts, min_elems, reverse)
+            covered = sorted(t for f, m in groups for t in range(f, f + m))
+            assert covered == list(range(16))                                   # every tensor once
+            assert all(sum(counts[f:f + m]) >= min_elems for f, m in groups[:-1])   # all but the last are big enough
+    assert px.plan_groups([0, 0, 5, 0], 3) == [(2, 2), (0, 2)]                 # empty tensors ride along
+    lib = px.load()
+    n = ctypes.c_int(0)
+    c = (ctypes.c_int64 * 2)(4, -1)
+    assert lib.pxchg_plan_groups(2, c, 1, 1, 0, None, None, ctypes.byref(n)) == 1       # negative count
+    c = (ctypes.c_int64 * 2)(4, 4)
+    assert lib.pxchg_plan_groups(2, c, 1, 1, 2, None, None, ctypes.byref(n)) == 1       # room claimed, no arrays
+    assert lib.pxchg_plan_groups(0, c, 1, 1, 0, None, None, ctypes.byref(n)) == 1
+    assert lib.pxchg_plan_groups(2, c, -1, 1, 0, None, None, ctypes.byref(n)) == 1
+
+
 def test_plan_chunks_rejects_bad_arguments(px):
     lib = px.load()
     n = ctypes.c_int64(0)
