@@ -172,6 +172,19 @@ int pxchg_table_view(const pxchg_table *parent, int first_tensor, int n_tensors,
  * under a running launch); not for the hot path.
  */
 int pxchg_table_set_multipliers(pxchg_table *table, const float *lr_mult /*host*/, const float *wd_mult /*host*/);
+/*
+ * The same controls for one table (and its views) only: PXCHG_OPT_NONTEMPORAL and PXCHG_OPT_CENTER_RESIDENT,
+ * with the values pxchg_set_option takes for them, override the process-wide setting for calls on this table;
+ * PXCHG_TABLE_OPTION_INHERIT (the state of a new table) goes back to the process-wide one.  So an elastic server's
+ * table can keep its center cached while the tables of a synchronous exchange in the same process stream.
+ * Other options are PXCHG_ERR_INVALID_ARG (the chunk size is fixed when a table is made, the rest is not per
+ * table).  pxchg_table_get_option returns the table's own value, PXCHG_TABLE_OPTION_INHERIT if it has none, and
+ * -3 for a bad handle or option.  Not for a table with calls in flight on another thread that should all see
+ * one setting: a call reads the option once, when it is made.
+ */
+#define PXCHG_TABLE_OPTION_INHERIT (-2)
+int pxchg_table_set_option(pxchg_table *table, int option, int64_t value);
+int64_t pxchg_table_get_option(const pxchg_table *table, int option);
 int64_t pxchg_table_total(const pxchg_table *table);   /* sum of counts; -1 if NULL */
 int pxchg_table_n_tensors(const pxchg_table *table);   /* -1 if NULL */
 int64_t pxchg_table_n_chunks(const pxchg_table *table); /* -1 if NULL */

@@ -15,6 +15,7 @@ F32, F16 = 0, 1
 MAX_K = 64
 OPT_CHUNK_ELEMS, OPT_BLOCKS_PER_CU, OPT_CHECK_RANGES, OPT_NONTEMPORAL, OPT_CENTER_RESIDENT = 0, 1, 2, 3, 4
 OPT_ALL_POLICIES_BUILT = 5
+TABLE_OPTION_INHERIT = -2
 ERR_IN_USE = 7
 
 _i64 = ctypes.c_int64
@@ -37,6 +38,8 @@ SIGNATURES = {
     "pxchg_table_destroy": (_int, [_vp]),
     "pxchg_table_view": (_int, [_vp, _int, _int, _pp]),
     "pxchg_table_set_multipliers": (_int, [_vp, ctypes.POINTER(_f), ctypes.POINTER(_f)]),
+    "pxchg_table_set_option": (_int, [_vp, _int, _i64]),
+    "pxchg_table_get_option": (_i64, [_vp, _int]),
     "pxchg_table_total": (_i64, [_vp]),
     "pxchg_table_n_tensors": (_int, [_vp]),
     "pxchg_table_n_chunks": (_i64, [_vp]),
@@ -253,6 +256,14 @@ class Table:
                 raise ValueError("one multiplier per tensor expected")
             return (_f * len(x))(*[float(v) for v in x])
         _check(self._lib.pxchg_table_set_multipliers(self._h, arr(lr_mult), arr(wd_mult)), "pxchg_table_set_multipliers")
+
+    def set_option(self, option: int, value: int) -> None:
+        """pxchg_table_set_option: this table's own cache policy or center-resident switch
+        (TABLE_OPTION_INHERIT: back to the process-wide setting)."""
+        _check(self._lib.pxchg_table_set_option(self._h, option, value), "pxchg_table_set_option")
+
+    def get_option(self, option: int) -> int:
+        return int(self._lib.pxchg_table_get_option(self._h, option))
 
     def bufset(self, tensors, dtype: Optional[int] = None) -> "BufSet":
         return BufSet(self, tensors, dtype)

@@ -203,6 +203,8 @@ int pxchg_table_create(int n_tensors, const int64_t *counts, pxchg_table **out) 
     t->first_tensor = 0;
     t->live_views = 0;
     t->live_sets = 0;
+    t->opt_nontemporal = PXCHG_TABLE_OPTION_INHERIT;
+    t->opt_center_resident = PXCHG_TABLE_OPTION_INHERIT;
 
     if (n_chunks > 0) {
         std::vector<PxChunk> h(n_chunks);
@@ -267,6 +269,8 @@ int pxchg_table_view(const pxchg_table *parent_c, int first_tensor, int n_tensor
     v->first_tensor = first_tensor;
     v->live_views = 0;
     v->live_sets = 0;
+    v->opt_nontemporal = PXCHG_TABLE_OPTION_INHERIT;      // unused: a view follows its parent
+    v->opt_center_resident = PXCHG_TABLE_OPTION_INHERIT;
     ++parent->live_views;
     registry()[v] = PX_KIND_TABLE;
     *out = v;
@@ -328,6 +332,34 @@ int pxchg_table_set_multipliers(pxchg_table *table, const float *lr_mult, const 
         return PXCHG_ERR_RUNTIME;
     }
     return PXCHG_OK;
+}
+
+int pxchg_table_set_option(pxchg_table *table, int option, int64_t value) {
+    Shared lock(px_registry_lock());
+    if (!px_valid(table) || table->parent) return PXCHG_ERR_INVALID_ARG;  // set them on the parent
+    switch (option) {
+        case PXCHG_OPT_NONTEMPORAL:
+            if (value != PXCHG_TABLE_OPTION_INHERIT && (value < -1 || value > 5)) return PXCHG_ERR_INVALID_ARG;
+            if (value > 0 && !px_all_policies_built()) return PXCHG_ERR_UNSUPPORTED;
+            table->opt_nontemporal = value;
+            return PXCHG_OK;
+        case PXCHG_OPT_CENTER_RESIDENT:
+            if (value != PXCHG_TABLE_OPTION_INHERIT && value != 0 && value != 1) return PXCHG_ERR_INVALID_ARG;
+            table->opt_center_resident = value;
+            return PXCHG_OK;
+        default:
+            return PXCHG_ERR_INVALID_ARG;
+    }
+}
+
+int64_t pxchg_table_get_option(const pxchg_table *table, int option) {
+    Shared lock(px_registry_lock());
+    if (!px_valid(table)) return -3;
+    switch (option) {
+        case PXCHG_OPT_NONTEMPORAL: return px_root(table)->opt_nontemporal.load();
+        case PXCHG_OPT_CENTER_RESIDENT: return px_root(table)->opt_center_resident.load();
+        default: return -3;
+    }
 }
 
 int64_t pxchg_table_total(const pxchg_table *table) {

@@ -36,6 +36,8 @@ struct pxchg_table {
     int first_tensor;         // a view covers the parent's tensors first_tensor .. first_tensor + n_tensors - 1
     int live_views;           // handles that point into this table; it cannot be destroyed before them
     int live_sets;            // (both changed only under the registry's exclusive lock)
+    std::atomic<int64_t> opt_nontemporal;      // this table's own setting, or PXCHG_TABLE_OPTION_INHERIT
+    std::atomic<int64_t> opt_center_resident;  // (a view uses its parent's)
 };
 
 // The table that owns the device-side lists, the multipliers and the buffer sets.
@@ -70,6 +72,18 @@ struct PxOptions {
     std::atomic<int64_t> center_resident;
 };
 PxOptions &px_options();
+
+// The cache policy and the center-resident switch in force for a call on `t`: the table's own setting (its
+// parent's for a view) if it has one, else the process-wide option.
+inline int64_t px_nontemporal_for(const pxchg_table *t) {
+    const int64_t own = px_root(t)->opt_nontemporal.load();
+    return own != PXCHG_TABLE_OPTION_INHERIT ? own : px_options().nontemporal.load();
+}
+inline bool px_center_resident_for(const pxchg_table *t) {
+    const int64_t own = px_root(t)->opt_center_resident.load();
+    return (own != PXCHG_TABLE_OPTION_INHERIT ? own : px_options().center_resident.load()) != 0;
+}
+
 
 // 1 if every cache policy of every kernel is compiled in (a tuning build), 0 if only each kernel's own policy and
 // the plain one are.  Defined beside the kernels.

@@ -1118,7 +1118,7 @@ constexpr int NT_BOTH = 3, NT_LOADS_SC1NT_STORES = 4, NT_LOADS_SC1_STORES = 5;
 // Expands CALL(n) for the policy to use: the caller's choice (PXCHG_OPT_NONTEMPORAL) if set, else OWN.
 #ifdef PXCHG_ALL_POLICIES
 #define PX_DISPATCH_NT(OWN, CALL)                     \
-    switch (policy_for(OWN)) {                        \
+    switch (policy_for(t, OWN)) {                     \
         case 0: return CALL(0);                       \
         case 1: return CALL(1);                       \
         case 2: return CALL(2);                       \
@@ -1128,12 +1128,12 @@ constexpr int NT_BOTH = 3, NT_LOADS_SC1NT_STORES = 4, NT_LOADS_SC1_STORES = 5;
     }
 #else
 #define PX_DISPATCH_NT(OWN, CALL)                     \
-    if (policy_for(OWN) == 0) return CALL(0);         \
+    if (policy_for(t, OWN) == 0) return CALL(0);      \
     return CALL(OWN);
 #endif
 
-int policy_for(int own) {
-    const int64_t nt = px_options().nontemporal;
+int policy_for(const pxchg_table *t, int own) {  // `t`: the table of the call (every launcher names it so)
+    const int64_t nt = px_nontemporal_for(t);
     return nt < 0 ? own : (int)nt;
 }
 
@@ -1281,7 +1281,7 @@ int launch_elastic_kc(const pxchg_table *t, const ElasticArgs &a, hipStream_t st
 template <int K>
 int launch_elastic_k(const pxchg_table *t, const ElasticArgs &a, hipStream_t stream) {
     // a center larger than the 256 MiB memory-side cache cannot stay there (measured 2.5 % slower at 553 MB)
-    if (px_options().center_resident && t->total * 4 <= ((int64_t)256 << 20)) return launch_elastic_kc<K, true>(t, a, stream);
+    if (px_center_resident_for(t) && t->total * 4 <= ((int64_t)256 << 20)) return launch_elastic_kc<K, true>(t, a, stream);
     return launch_elastic_kc<K, false>(t, a, stream);
 }
 

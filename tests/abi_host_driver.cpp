@@ -398,6 +398,8 @@ int lifetime_and_launches() {
     pxchg_bufset *on_view = nullptr;
     CHECK(pxchg_bufset_create(view, PXCHG_F32, fa.data(), &on_view) == PXCHG_ERR_INVALID_ARG);
     CHECK(pxchg_table_set_multipliers(view, nullptr, nullptr) == PXCHG_ERR_INVALID_ARG);
+    CHECK(pxchg_table_set_option(view, PXCHG_OPT_CENTER_RESIDENT, 1) == PXCHG_ERR_INVALID_ARG);     // set it on the parent
+    CHECK(pxchg_table_get_option(view, PXCHG_OPT_CENTER_RESIDENT) == PXCHG_TABLE_OPTION_INHERIT);   // reads the parent's
     fake::launches = 0;
     for (int rc : every_hot_call(view, a, b, c, h, out)) CHECK(rc == PXCHG_OK);
     CHECK(fake::launches == 11);
@@ -411,6 +413,28 @@ int lifetime_and_launches() {
     CHECK(pxchg_table_destroy(table) == PXCHG_ERR_IN_USE);                              // one view and the sets are left
     CHECK(pxchg_table_destroy(view2) == PXCHG_OK);
     CHECK(pxchg_table_destroy(table) == PXCHG_ERR_IN_USE);                              // the sets are left
+
+    // ---- per-table options: the table's own setting overrides the process-wide one; a view follows its parent
+    {
+        CHECK(pxchg_table_get_option(table, PXCHG_OPT_CENTER_RESIDENT) == PXCHG_TABLE_OPTION_INHERIT);
+        CHECK(pxchg_table_set_option(table, PXCHG_OPT_CENTER_RESIDENT, 1) == PXCHG_OK);
+        CHECK(pxchg_table_get_option(table, PXCHG_OPT_CENTER_RESIDENT) == 1);
+        CHECK(pxchg_table_get_option(other, PXCHG_OPT_CENTER_RESIDENT) == PXCHG_TABLE_OPTION_INHERIT);
+        CHECK(pxchg_get_option(PXCHG_OPT_CENTER_RESIDENT) == 0);                    // the process-wide one is untouched
+        CHECK(pxchg_easgd(table, a, c, 0.1f, nullptr) == PXCHG_OK);                // same launch shape either way
+        CHECK(pxchg_table_set_option(table, PXCHG_OPT_CENTER_RESIDENT, 2) == PXCHG_ERR_INVALID_ARG);
+        CHECK(pxchg_table_set_option(table, PXCHG_OPT_CENTER_RESIDENT, PXCHG_TABLE_OPTION_INHERIT) == PXCHG_OK);
+        CHECK(pxchg_table_set_option(table, PXCHG_OPT_NONTEMPORAL, 0) == PXCHG_OK);
+        CHECK(pxchg_table_get_option(table, PXCHG_OPT_NONTEMPORAL) == 0);
+        CHECK(pxchg_table_set_option(table, PXCHG_OPT_NONTEMPORAL, 6) == PXCHG_ERR_INVALID_ARG);
+        CHECK(pxchg_table_set_option(table, PXCHG_OPT_NONTEMPORAL, 4) ==
+              (pxchg_get_option(PXCHG_OPT_ALL_POLICIES_BUILT) ? PXCHG_OK : PXCHG_ERR_UNSUPPORTED));
+        CHECK(pxchg_table_set_option(table, PXCHG_OPT_NONTEMPORAL, PXCHG_TABLE_OPTION_INHERIT) == PXCHG_OK);
+        CHECK(pxchg_table_set_option(table, PXCHG_OPT_CHUNK_ELEMS, 1024) == PXCHG_ERR_INVALID_ARG);   // not per table
+        CHECK(pxchg_table_get_option(table, PXCHG_OPT_CHUNK_ELEMS) == -3);
+        CHECK(pxchg_table_set_option(nullptr, PXCHG_OPT_NONTEMPORAL, 0) == PXCHG_ERR_INVALID_ARG);
+        CHECK(pxchg_table_get_option((pxchg_table *)a, PXCHG_OPT_NONTEMPORAL) == -3);
+    }
 
     // ---- multipliers (a set-up call that waits for the device)
     {

@@ -480,6 +480,39 @@ def test_center_resident_option_gives_the_same_bits(px, oracle_mod, policy, offs
         px.set_option(px.OPT_NONTEMPORAL, old)
 
 
+def test_options_of_one_table_override_the_process_wide_ones(px, oracle_mod):
+    """An elastic server's table keeps its center cached and takes the plain cache policy, another table in the
+    same process streams with the kernels' own policies; neither setting leaks, and results never depend on them."""
+    t_server, t_other = px.Table(RAGGED), px.Table(RAGGED)
+    t_server.set_option(px.OPT_CENTER_RESIDENT, 1)
+    t_server.set_option(px.OPT_NONTEMPORAL, 0)
+    assert t_server.get_option(px.OPT_CENTER_RESIDENT) == 1 and t_server.get_option(px.OPT_NONTEMPORAL) == 0
+    assert t_other.get_option(px.OPT_CENTER_RESIDENT) == px.TABLE_OPTION_INHERIT
+    assert px.get_option(px.OPT_CENTER_RESIDENT) == 0 and px.get_option(px.OPT_NONTEMPORAL) == -1
+    assert t_server.view(3, 4).get_option(px.OPT_CENTER_RESIDENT) == 1           # a view follows its parent
+    with pytest.raises(px.PxchgError):
+        t_server.view(3, 4).set_option(px.OPT_CENTER_RESIDENT, 0)
+    with pytest.raises(px.PxchgError) as e:
+        t_server.set_option(px.OPT_NONTEMPORAL, 4)                               # the regular build holds -1 and 0
+    assert e.value.status == 3
+    for table in (t_server, t_other, t_server.view(0, len(RAGGED))):
+        for k in (1, 2, 8):
+            xs = [_gauss(RAGGED, 975 + k, w, role="worker") for w in range(k)]
+            c = _gauss(RAGGED, 976 + k, role="center")
+            root = t_server if table is not t_other else t_other
+            d_xs, d_c = [to_device(x) for x in xs], to_device(c)
+            sets, sc = [root.bufset(x) for x in d_xs], root.bufset(d_c)
+            px.easgd_round(table, sets, sc, 0.0625)
+            px.easgd(table, sets[0], sc, 0.0625)
+            for i in list(range(k)) + [0]:
+                oracle_mod.easgd_tensors(xs[i], c, np.float32(0.0625))
+            for i in range(k):
+                assert_bits_equal(to_host(d_xs[i]), xs[i], f"k={k} x[{i}]")
+            assert_bits_equal(to_host(d_c), c, f"k={k} center")
+    t_server.set_option(px.OPT_CENTER_RESIDENT, px.TABLE_OPTION_INHERIT)
+    assert t_server.get_option(px.OPT_CENTER_RESIDENT) == px.TABLE_OPTION_INHERIT
+
+
 # ------------------------------------------------------------------ argument errors on a live device
 
 def test_argument_errors(px):

@@ -139,3 +139,19 @@ def test_elastic(px, oracle_mod, policy, chunk, center_resident):
         for i in range(k):
             assert_bits_equal(to_host(d_xs[i]), xs[i], f"k={k} x[{i}]")
         assert_bits_equal(to_host(d_c), c, f"k={k} center")
+
+
+def test_policy_of_one_table_only(px, oracle_mod):
+    """pxchg_table_set_option with the tuning build: two tables in one process under different policies."""
+    px.set_option(px.OPT_NONTEMPORAL, -1)           # whatever the tests before left behind
+    tables = {p: px.Table(COUNTS) for p in (0, 3, 4, 5)}
+    for p, t in tables.items():
+        t.set_option(px.OPT_NONTEMPORAL, p)
+    g = [_gauss(981, w) for w in range(2)]
+    want = oracle_mod.reduce_avg_tensors(g, np.float16)
+    for p, t in tables.items():
+        d_out = empty_like_device(COUNTS, np.float16)
+        px.reduce_avg(t, [t.bufset(to_device(x)) for x in g], t.bufset(d_out))
+        assert_bits_equal(to_host(d_out), want, f"table under policy {p}")
+        assert t.get_option(px.OPT_NONTEMPORAL) == p
+    assert px.get_option(px.OPT_NONTEMPORAL) == -1
