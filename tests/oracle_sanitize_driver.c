@@ -54,6 +54,19 @@ int main(void)
     double ss;
     if (oracle_stats(a16, ORACLE_F16, N, &bad, &mx, &ss)) return 1;
     if (oracle_stats(w, ORACLE_F32, N, &bad, &mx, &ss)) return 1;
+    /* the tree-ordered diagnostics: ragged tensors incl. empty ones, blocks that end mid-list, every parameter odd */
+    {
+        const void *ts16[4] = {a16, NULL, h[1], h[2]}, *ts32[3] = {w, a32, g[0]};
+        const int64_t c16[4] = {N, 0, 700, 1}, c32[3] = {N, 513, N - 3};
+        double ordered;
+        if (oracle_stats_ordered(4, ts16, c16, ORACLE_F16, 512, 4, 32, 1024, &bad, &mx, &ordered)) return 1;
+        if (oracle_stats_ordered(4, ts16, c16, ORACLE_F16, 7, 3, 5, 64, &bad, &mx, &ordered)) return 1;
+        if (oracle_stats_ordered(3, ts32, c32, ORACLE_F32, 512, 1, 1, 128, &bad, &mx, &ordered)) return 1;
+        if (oracle_stats_ordered(3, ts32, c32, ORACLE_F32, 100000, 16, 256, 1024, &bad, &mx, &ordered)) return 1;
+        const int64_t none[2] = {0, 0};
+        if (oracle_stats_ordered(2, ts16, none, ORACLE_F16, 512, 4, 32, 1024, &bad, &mx, &ordered) || ordered != 0.0) return 1;
+        if (!oracle_stats_ordered(3, ts32, c32, ORACLE_F32, 512, 4, 32, 100, &bad, &mx, &ordered)) return 1;   /* must reject */
+    }
     for (int i = 0; i < K; ++i) { free(g[i]); free(h[i]); }
     free(w); free(v); free(a32); free(a16);
     printf("ok\n");
