@@ -25,8 +25,9 @@ rotating operand sets, so that every operand (inputs, outputs, in-place state)
 was last touched at least 1 GB of traffic ago: a pure HBM figure.  `value_cold`
 is the metric from the cold figures.
 
-`configs` holds reduce+update (and the elastic meeting) for the other benchmark
-configurations and the paper's two other model sizes, each cold (operand sets
+`configs` holds every stage (pack where the transfer is half precision, reduce,
+update, the elastic meeting) for the other benchmark configurations and the
+paper's two other model sizes, each cold (operand sets
 rotating over more than 1 GB) and warm (one operand set over and over).
 
 `extras` holds what is measured after the timed region, each over the same number
@@ -245,11 +246,13 @@ def bench_config(px, torch, clock, name, counts, k, transfer, lr, mu, wd, alpha,
 
     set_bytes = n * (k * es + es + 8)           # contributions, mean, parameters and velocity of one operand set
     n_rot = rotation(set_bytes)
-    sets = []
+    sets, grads = [], []
     for _ in range(n_rot):
         contrib = [table.bufset(draw(wire_t)) for _ in range(k)]
         mean = table.bufset([torch.empty(c_, dtype=wire_t, device="cuda") for c_ in counts])
         sets.append((contrib, mean, table.bufset(draw(torch.float32)), table.bufset(draw(torch.float32))))
+        if half:                                # the float32 gradients that the pack turns into the contributions
+            grads.append([table.bufset(draw(torch.float32)) for _ in range(k)])
     torch.cuda.synchronize()
 
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(clock.reps)]
@@ -282,6 +285,12 @@ def bench_config(px, torch, clock, name, counts, k, transfer, lr, mu, wd, alpha,
                       "reduce_GBps": round(r_bytes / r_ms / 1e6, 1), "update_GBps": round(u_bytes / u_ms / 1e6, 1),
                       "reduce_update_GBps": round((r_bytes + u_bytes) / (r_ms + u_ms) / 1e6, 1),
                       "frac_of_hbm_peak": round((r_bytes + u_bytes) / (r_ms + u_ms) / 1e6 / HBM_PEAK_GBPS, 4)}
+    if half:
+        for label, rotating in (("cold", True), ("warm", False)):
+            ms = clock.loop(lambda i: px.pack_fp16(table, grads[i % n_rot if rotating else 0],
+                                                   sets[i % n_rot if rotating else 0][0], stream=stream))
+            out[label]["pack_ms"] = round(ms, 5)
+            out[label]["pack_GBps"] = round(6 * k * n / ms / 1e6, 1)
     if alpha:
         # the elastic meeting: parameters of one set meet the velocity buffer of the next as "center"
         def meet(i, rotating=True):
@@ -293,7 +302,7 @@ def bench_config(px, torch, clock, name, counts, k, transfer, lr, mu, wd, alpha,
             out[label]["meeting_GBps"] = round(16 * n / ms / 1e6, 1)
     if note:
         out["note"] = note
-    del sets
+    del sets, grads
     torch.cuda.empty_cache()
     return out
 
