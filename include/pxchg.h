@@ -33,6 +33,7 @@
  *     fast path; other alignments are handled by a slower element-wise path.
  *   - Inputs must not overlap outputs except where a function says "in place".
  *   - All calls for one table must be made with the table's device current.
+ *   - No call throws: every failure is a status (see pxchg_status), also when memory runs out.
  */
 #ifndef PXCHG_H
 #define PXCHG_H
@@ -51,7 +52,8 @@ enum pxchg_status {
     PXCHG_ERR_SHAPE_MISMATCH = 2, /* buffer set belongs to another table, or wrong element type */
     PXCHG_ERR_UNSUPPORTED = 3,    /* k outside 1..PXCHG_MAX_K, size beyond a stated limit */
     PXCHG_ERR_NO_DEVICE = 4,      /* no usable GPU, or the table's device is not current */
-    PXCHG_ERR_RUNTIME = 5,        /* a HIP call failed (allocation, copy, launch) */
+    PXCHG_ERR_RUNTIME = 5,        /* a HIP call failed (allocation, copy, launch), or host memory ran out in a set-up
+                                     call: then nothing was created and nothing is left allocated */
     PXCHG_ERR_OUT_OF_RANGE = 6,   /* a tensor does not fit inside the device allocation it points into */
     PXCHG_ERR_IN_USE = 7          /* pxchg_table_destroy on a table that still has views or buffer sets */
 };

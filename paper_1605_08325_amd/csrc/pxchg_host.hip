@@ -2,6 +2,7 @@
 // buffer sets.  Everything here runs at set-up time; the per-exchange calls live
 // beside the kernels.
 #include <algorithm>
+#include <memory>
 #include <mutex>
 #include <new>
 #include <unordered_map>
@@ -21,6 +22,28 @@ std::atomic<uint64_t> next_table_id{1};
 
 using Shared = std::shared_lock<std::shared_mutex>;
 using Exclusive = std::unique_lock<std::shared_mutex>;
+
+// Owners for objects under construction: if a step fails, or host memory runs out (std::bad_alloc from a
+// container), what has been allocated so far is given back and the call returns a status.  No exception crosses
+// the C boundary.
+struct TableDrop {
+    void operator()(pxchg_table *t) const {
+        if (!t->parent) {
+            if (t->d_chunks) (void)hipFree(t->d_chunks);
+            if (t->d_mult) (void)hipFree(t->d_mult);
+            if (t->d_partials) (void)hipFree(t->d_partials);
+        }
+        delete t;
+    }
+};
+struct SetDrop {
+    void operator()(pxchg_bufset *s) const {
+        if (s->d_ptrs) (void)hipFree(s->d_ptrs);
+        delete s;
+    }
+};
+using TableOwner = std::unique_ptr<pxchg_table, TableDrop>;
+using SetOwner = std::unique_ptr<pxchg_bufset, SetDrop>;
 
 }  // namespace
 
@@ -43,17 +66,18 @@ PxOptions &px_options() {
 }
 
 int px_cu_count(int device) {
-    static std::mutex mu;
-    static std::vector<int> cache;
-    std::lock_guard<std::mutex> lock(mu);
+    // one word per device, filled on first use; two threads that race here look up the same number
+    constexpr int kMaxDevices = 64;
+    static std::atomic<int> cache[kMaxDevices];
     if (device < 0) return 0;
-    if ((size_t)device >= cache.size()) cache.resize(device + 1, 0);
-    if (cache[device] == 0) {
-        int n = 0;
-        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess || n <= 0) n = 256;
-        cache[device] = n;
+    if (device < kMaxDevices) {
+        const int known = cache[device].load(std::memory_order_relaxed);
+        if (known) return known;
     }
-    return cache[device];
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess || n <= 0) n = 256;
+    if (device < kMaxDevices) cache[device].store(n, std::memory_order_relaxed);
+    return n;
 }
 
 extern "C" {
@@ -164,7 +188,7 @@ int pxchg_plan_groups(int n_tensors, const int64_t *counts, int64_t min_elems, i
     return PXCHG_OK;
 }
 
-int pxchg_table_create(int n_tensors, const int64_t *counts, pxchg_table **out) {
+int pxchg_table_create(int n_tensors, const int64_t *counts, pxchg_table **out) try {
     if (!out) return PXCHG_ERR_INVALID_ARG;
     *out = nullptr;
     if (n_tensors < 1 || n_tensors > (1 << 24) || !counts) return PXCHG_ERR_INVALID_ARG;
@@ -187,8 +211,11 @@ int pxchg_table_create(int n_tensors, const int64_t *counts, pxchg_table **out) 
         return PXCHG_ERR_NO_DEVICE;
     }
 
-    pxchg_table *t = new (std::nothrow) pxchg_table();
-    if (!t) return PXCHG_ERR_RUNTIME;
+    TableOwner t(new pxchg_table());
+    t->d_chunks = nullptr;
+    t->d_mult = nullptr;
+    t->d_partials = nullptr;
+    t->parent = nullptr;
     t->id = next_table_id.fetch_add(1);
     t->device = device;
     t->n_tensors = n_tensors;
@@ -196,10 +223,6 @@ int pxchg_table_create(int n_tensors, const int64_t *counts, pxchg_table **out) 
     t->chunk_elems = chunk_elems;
     t->n_chunks = n_chunks;
     t->counts.assign(counts, counts + n_tensors);
-    t->d_chunks = nullptr;
-    t->d_mult = nullptr;
-    t->d_partials = nullptr;
-    t->parent = nullptr;
     t->first_tensor = 0;
     t->live_views = 0;
     t->live_sets = 0;
@@ -221,9 +244,7 @@ int pxchg_table_create(int n_tensors, const int64_t *counts, pxchg_table **out) 
         if (hipMalloc((void **)&t->d_chunks, n_chunks * sizeof(PxChunk)) != hipSuccess ||
             hipMemcpy(t->d_chunks, h.data(), n_chunks * sizeof(PxChunk), hipMemcpyHostToDevice) != hipSuccess ||
             hipMalloc((void **)&t->d_partials, px_stats_blocks(n_chunks) * sizeof(pxchg_stats)) != hipSuccess) {
-            if (t->d_chunks) (void)hipFree(t->d_chunks);
-            if (t->d_partials) (void)hipFree(t->d_partials);
-            delete t;
+            (void)hipGetLastError();
             return PXCHG_ERR_RUNTIME;
         }
     }
@@ -232,13 +253,15 @@ int pxchg_table_create(int n_tensors, const int64_t *counts, pxchg_table **out) 
     (void)px_prepare_static_scratch(device);
     {
         Exclusive lock(px_registry_lock());
-        registry()[t] = PX_KIND_TABLE;
+        registry()[t.get()] = PX_KIND_TABLE;
     }
-    *out = t;
+    *out = t.release();
     return PXCHG_OK;
+} catch (...) {
+    return PXCHG_ERR_RUNTIME;  // host memory ran out
 }
 
-int pxchg_table_view(const pxchg_table *parent_c, int first_tensor, int n_tensors, pxchg_table **out) {
+int pxchg_table_view(const pxchg_table *parent_c, int first_tensor, int n_tensors, pxchg_table **out) try {
     if (!out) return PXCHG_ERR_INVALID_ARG;
     *out = nullptr;
     Exclusive lock(px_registry_lock());
@@ -253,8 +276,8 @@ int pxchg_table_view(const pxchg_table *parent_c, int first_tensor, int n_tensor
         n_chunks += (parent->counts[t] + ce - 1) / ce;
         total += parent->counts[t];
     }
-    pxchg_table *v = new (std::nothrow) pxchg_table();
-    if (!v) return PXCHG_ERR_RUNTIME;
+    TableOwner v(new pxchg_table());
+    v->parent = parent;  // from here on the owner knows that this is a view: it frees no device memory
     v->id = next_table_id.fetch_add(1);
     v->device = parent->device;
     v->n_tensors = n_tensors;
@@ -265,16 +288,17 @@ int pxchg_table_view(const pxchg_table *parent_c, int first_tensor, int n_tensor
     v->d_chunks = n_chunks ? parent->d_chunks + first_chunk : nullptr;
     v->d_mult = nullptr;      // the parent's multipliers apply (looked up at each call)
     v->d_partials = nullptr;  // and the parent's partial results
-    v->parent = parent;
     v->first_tensor = first_tensor;
     v->live_views = 0;
     v->live_sets = 0;
     v->opt_nontemporal = PXCHG_TABLE_OPTION_INHERIT;      // unused: a view follows its parent
     v->opt_center_resident = PXCHG_TABLE_OPTION_INHERIT;
+    registry()[v.get()] = PX_KIND_TABLE;
     ++parent->live_views;
-    registry()[v] = PX_KIND_TABLE;
-    *out = v;
+    *out = v.release();
     return PXCHG_OK;
+} catch (...) {
+    return PXCHG_ERR_RUNTIME;  // host memory ran out
 }
 
 int pxchg_table_destroy(pxchg_table *table) {
@@ -299,7 +323,7 @@ int pxchg_table_destroy(pxchg_table *table) {
     return rc;
 }
 
-int pxchg_table_set_multipliers(pxchg_table *table, const float *lr_mult, const float *wd_mult) {
+int pxchg_table_set_multipliers(pxchg_table *table, const float *lr_mult, const float *wd_mult) try {
     Exclusive lock(px_registry_lock());  // no call may be reading d_mult while it changes
     if (!px_valid(table) || table->parent) return PXCHG_ERR_INVALID_ARG;  // set them on the parent
     int device = -1;
@@ -332,6 +356,8 @@ int pxchg_table_set_multipliers(pxchg_table *table, const float *lr_mult, const 
         return PXCHG_ERR_RUNTIME;
     }
     return PXCHG_OK;
+} catch (...) {
+    return PXCHG_ERR_RUNTIME;  // host memory ran out; the multipliers on the device are unchanged
 }
 
 int pxchg_table_set_option(pxchg_table *table, int option, int64_t value) {
@@ -375,7 +401,7 @@ int64_t pxchg_table_n_chunks(const pxchg_table *table) {
     return px_valid(table) ? table->n_chunks : -1;
 }
 
-int pxchg_bufset_create(const pxchg_table *table_c, int dtype, const void *const *ptrs, pxchg_bufset **out) {
+int pxchg_bufset_create(const pxchg_table *table_c, int dtype, const void *const *ptrs, pxchg_bufset **out) try {
     if (!out) return PXCHG_ERR_INVALID_ARG;
     *out = nullptr;
     Exclusive lock(px_registry_lock());
@@ -407,24 +433,24 @@ int pxchg_bufset_create(const pxchg_table *table_c, int dtype, const void *const
             if (a < b || a + (uintptr_t)n * es > b + size) return PXCHG_ERR_OUT_OF_RANGE;
         }
     }
-    pxchg_bufset *s = new (std::nothrow) pxchg_bufset();
-    if (!s) return PXCHG_ERR_RUNTIME;
+    SetOwner s(new pxchg_bufset());
+    s->d_ptrs = nullptr;
     s->table = table;
     s->table_id = table->id;
     s->dtype = dtype;
     s->h_ptrs.assign(ptrs, ptrs + table->n_tensors);
-    s->d_ptrs = nullptr;
     const size_t bytes = (size_t)table->n_tensors * sizeof(void *);
     if (hipMalloc((void **)&s->d_ptrs, bytes) != hipSuccess ||
         hipMemcpy(s->d_ptrs, s->h_ptrs.data(), bytes, hipMemcpyHostToDevice) != hipSuccess) {
-        if (s->d_ptrs) (void)hipFree(s->d_ptrs);
-        delete s;
+        (void)hipGetLastError();
         return PXCHG_ERR_RUNTIME;
     }
+    registry()[s.get()] = PX_KIND_BUFSET;
     ++table->live_sets;
-    registry()[s] = PX_KIND_BUFSET;
-    *out = s;
+    *out = s.release();
     return PXCHG_OK;
+} catch (...) {
+    return PXCHG_ERR_RUNTIME;  // host memory ran out
 }
 
 int pxchg_bufset_destroy(pxchg_bufset *set) {

@@ -14,6 +14,7 @@
 #include <cstring>
 #include <map>
 #include <mutex>
+#include <new>
 #include <thread>
 #include <vector>
 
@@ -29,7 +30,42 @@ std::atomic<int> launches{0}, get_last_error_calls{0}, synchronizes{0}, symbol_l
 bool fail_next_launch = false;
 dim3 last_grid, last_block;
 std::vector<dim3> grids;
+// Failure injection: the n-th host allocation (operator new) or device allocation (hipMalloc) from now fails;
+// -1 = none.  The stand-in runtime's own bookkeeping is exempt.
+long new_countdown = -1, malloc_countdown = -1;
+std::atomic<long> live_host_blocks{0};  // operator new minus operator delete
+thread_local int exempt = 0;
+struct Exempt {
+    Exempt() { ++exempt; }
+    ~Exempt() { --exempt; }
+};
 }  // namespace fake
+
+// Replacements for the global allocation functions, so that running out of host memory can be rehearsed (left
+// out with -DPXCHG_DRIVER_NO_ALLOC_HOOKS: ThreadSanitizer's runtime brings its own).
+#ifndef PXCHG_DRIVER_NO_ALLOC_HOOKS
+static void *counted_alloc(std::size_t size) {
+    if (!fake::exempt && fake::new_countdown >= 0 && fake::new_countdown-- == 0) throw std::bad_alloc();
+    void *p = std::malloc(size ? size : 1);
+    if (!p) throw std::bad_alloc();
+    ++fake::live_host_blocks;
+    return p;
+}
+static void counted_free(void *p) {
+    if (!p) return;
+    --fake::live_host_blocks;
+    std::free(p);
+}
+void *operator new(std::size_t size) { return counted_alloc(size); }
+void *operator new[](std::size_t size) { return counted_alloc(size); }
+void operator delete(void *p) noexcept { counted_free(p); }
+void operator delete[](void *p) noexcept { counted_free(p); }
+void operator delete(void *p, std::size_t) noexcept { counted_free(p); }
+void operator delete[](void *p, std::size_t) noexcept { counted_free(p); }
+constexpr int kFirstFailureKind = 0;
+#else
+constexpr int kFirstFailureKind = 1;  // device allocations only
+#endif
 
 extern "C" {
 hipError_t hipGetDevice(int *device) {
@@ -41,6 +77,9 @@ hipError_t hipDeviceGetAttribute(int *value, hipDeviceAttribute_t, int) {
     return hipSuccess;
 }
 hipError_t hipMalloc(void **ptr, size_t size) {
+    fake::Exempt exempt;
+    *ptr = nullptr;
+    if (fake::malloc_countdown >= 0 && fake::malloc_countdown-- == 0) return hipErrorOutOfMemory;
     *ptr = std::malloc(size ? size : 1);
     if (!*ptr) return hipErrorOutOfMemory;
     ++fake::mallocs;
@@ -49,6 +88,7 @@ hipError_t hipMalloc(void **ptr, size_t size) {
     return hipSuccess;
 }
 hipError_t hipFree(void *ptr) {
+    fake::Exempt exempt;
     if (!ptr) return hipSuccess;
     {
         std::lock_guard<std::mutex> lock(fake::mu);
@@ -89,6 +129,7 @@ hipError_t hipGetSymbolAddress(void **address, const void *symbol) {
 }
 hipError_t hipLaunchKernel(const void *function, dim3 grid, dim3 block, void **args, size_t, hipStream_t) {
     if (!function || !args) return hipErrorInvalidValue;
+    fake::Exempt exempt;
     std::lock_guard<std::mutex> lock(fake::mu);
     if (fake::fail_next_launch) {
         fake::fail_next_launch = false;
@@ -582,6 +623,102 @@ int threads_share_handles() {
     return 0;
 }
 
+
+// Every way a set-up call can run out of memory half-way: the n-th host allocation throws, or the n-th device
+// allocation fails, for n = 0, 1, ... until the call gets through.  Each failure must come back as a status (no
+// exception leaves the library), hand out no handle, return every device allocation made so far, and leave the
+// counts of live views and sets as they were (the objects can be destroyed afterwards), with as many host blocks
+// alive as before.
+int planted_failures = 0;  // failures met by the last exhaust()
+template <typename Call>
+int exhaust(const char *what, long &countdown, Call call) {
+    planted_failures = 0;
+    const size_t device_before = fake::allocations.size();
+    const long host_before = fake::live_host_blocks;
+    for (long n = 0;; ++n) {
+        if (n > 200) {
+            std::printf("%s: still failing after 200 allocations\n", what);
+            return 1;
+        }
+        countdown = n;
+        void *handle = (void *)0x1;
+        const int rc = call(&handle);
+        const bool fired = countdown < 0;  // the planted failure was reached
+        countdown = -1;
+        if (rc == PXCHG_OK) {
+            CHECK(handle != nullptr && handle != (void *)0x1);
+            CHECK(!fired);  // a call that got through met no failure
+            return 0;
+        }
+        CHECK(fired);
+        ++planted_failures;
+        CHECK(rc == PXCHG_ERR_RUNTIME);
+        CHECK(handle == nullptr);
+        CHECK(fake::allocations.size() == device_before);
+        CHECK(fake::live_host_blocks == host_before);  // and every host block
+    }
+}
+
+int memory_runs_out() {
+    const std::vector<int64_t> counts = {1000, 0, 513, 7, 4096};
+    Buffers f32(counts, 4);
+    for (int kind = kFirstFailureKind; kind < 2; ++kind) {
+        long &countdown = kind == 0 ? fake::new_countdown : fake::malloc_countdown;
+        pxchg_table *table = nullptr, *view = nullptr;
+        pxchg_bufset *set = nullptr;
+        if (exhaust("table_create", countdown, [&](void **h) {
+                const int rc = pxchg_table_create((int)counts.size(), counts.data(), (pxchg_table **)h);
+                table = (pxchg_table *)*h;
+                return rc;
+            }))
+            return 1;
+        // the rehearsal is not vacuous: the object, its vectors and its registry entry on the host side; the
+        // chunk list and the partial results on the device side
+        CHECK(planted_failures >= (kind == 0 ? 3 : 2));
+        if (exhaust("table_view", countdown, [&](void **h) {
+                const int rc = pxchg_table_view(table, 1, 3, (pxchg_table **)h);
+                view = (pxchg_table *)*h;
+                return rc;
+            }))
+            return 1;
+        if (exhaust("bufset_create", countdown, [&](void **h) {
+                const int rc = pxchg_bufset_create(table, PXCHG_F32, f32.data(), (pxchg_bufset **)h);
+                set = (pxchg_bufset *)*h;
+                return rc;
+            }))
+            return 1;
+        CHECK(planted_failures >= (kind == 0 ? 3 : 1));
+        // multipliers: a failure leaves the table usable and without multipliers or with the old ones
+        std::vector<float> ones(counts.size(), 1.0f);
+        for (long n = 0;; ++n) {
+            CHECK(n <= 200);
+            countdown = n;
+            const int rc = pxchg_table_set_multipliers(table, ones.data(), nullptr);
+            const bool fired = countdown < 0;
+            countdown = -1;
+            if (rc == PXCHG_OK) break;
+            CHECK(fired && rc == PXCHG_ERR_RUNTIME);
+        }
+        {   // what was built works: a launch through the view with the set
+            const int before = fake::launches;
+            pxchg_bufset *one[1] = {set};
+            pxchg_bufset *other = nullptr;
+            Buffers out(counts, 4);
+            CHECK(pxchg_bufset_create(table, PXCHG_F32, out.data(), &other) == PXCHG_OK);
+            CHECK(pxchg_reduce_avg(view, 1, one, other, PXCHG_AVG, nullptr) == PXCHG_OK);
+            CHECK(fake::launches == before + 1);
+            CHECK(pxchg_bufset_destroy(other) == PXCHG_OK);
+        }
+        // exactly one view and one set are alive: the failed attempts left nothing behind
+        CHECK(pxchg_table_destroy(table) == PXCHG_ERR_IN_USE);
+        CHECK(pxchg_table_destroy(view) == PXCHG_OK);
+        CHECK(pxchg_table_destroy(table) == PXCHG_ERR_IN_USE);
+        CHECK(pxchg_bufset_destroy(set) == PXCHG_OK);
+        CHECK(pxchg_table_destroy(table) == PXCHG_OK);
+    }
+    return 0;
+}
+
 }  // namespace
 
 int main(int argc, char **argv) {
@@ -589,6 +726,7 @@ int main(int argc, char **argv) {
     if (!threads_only) {
         if (options_and_planning()) return 1;
         if (lifetime_and_launches()) return 1;
+        if (memory_runs_out()) return 1;
     }
     if (threads_share_handles()) return 1;
     if (!fake::allocations.empty()) {  // every device allocation of the library was returned

@@ -12,14 +12,14 @@ ROOT = os.path.dirname(HERE)
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 
-def build_driver(exe, sanitizers):
+def build_driver(exe, sanitizers, defines=()):
     csrc = os.path.join(ROOT, "paper_1605_08325_amd", "csrc")
     cmd = [HIPCC, "--offload-arch=gfx950", "-O1", "-g", "-std=c++17", "-pthread",
            *[x for s_ in sanitizers for x in ("-Xarch_host", f"-fsanitize={s_}")],
            "-Xarch_host", "-fno-sanitize-recover=all",
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
            "-I", os.path.join(ROOT, "include"), "-I", csrc,
-           "-ffp-contract=off",
+           "-ffp-contract=off", *[f"-D{d}" for d in defines],
            os.path.join(csrc, "pxchg_host.hip"), os.path.join(csrc, "pxchg_kernels.hip"),
            os.path.join(HERE, "abi_host_driver.cpp"), "-o", exe]
     build = subprocess.run(cmd, capture_output=True, text=True)
@@ -44,7 +44,7 @@ def test_handles_shared_between_threads_are_clean_under_tsan(tmp_path):
     """Threads that use one table while others create and destroy their own, and one that keeps trying to destroy
     the shared table and destroys sets handed to it: the registry's reader/writer lock orders all of it."""
     exe = str(tmp_path / "abi_host_tsan")
-    build_driver(exe, ["thread"])
+    build_driver(exe, ["thread"], defines=["PXCHG_DRIVER_NO_ALLOC_HOOKS"])  # its runtime has its own operator new
     run = subprocess.run([exe, "threads"], capture_output=True, text=True, timeout=300)
     if run.returncode != 0 and ("runtime does not come first" in run.stderr or "unexpected memory mapping" in run.stderr):
         pytest.skip("ThreadSanitizer cannot start in this environment")
