@@ -340,6 +340,45 @@ struct ConvertOp {
     __device__ __forceinline__ void store(const State &st, int i) const { storev<NT, U, SP>(dst + i, st.x); }
 };
 
+// A chunk may be shared by PARTS workgroups, each taking `part_elems` consecutive elements of it (the table's
+// chunk size over PARTS, a multiple of 256, so a part starts at the same offset from 16-byte alignment as its
+// chunk).  Returns false for a part that lies beyond a short chunk's end.  Uniform over the workgroup.
+template <int PARTS>
+__device__ __forceinline__ bool take_part(PxChunk &ch, int part, int part_elems) {
+    if constexpr (PARTS > 1) {
+        const int off = part * part_elems;
+        if (off >= ch.len) return false;
+        ch.start += off;
+        ch.len = ch.len - off < part_elems ? ch.len - off : part_elems;
+    }
+    return true;
+}
+
+// Workgroups per chunk of the kernels other than the elastic ones (the PXCHG_TUNE_* macros: A/B builds only).
+// Measured with two: the update level when cold and 8 % slower inside the step, the binary16 reduce 2..3 %
+// slower, the fused reduce+update 1..3 % faster on sets of 7 M to 61 M elements and 2..8 % from 100 M on.
+constexpr int update_parts() {
+#ifdef PXCHG_TUNE_UPDATE_PARTS
+    return PXCHG_TUNE_UPDATE_PARTS;
+#else
+    return 1;
+#endif
+}
+template <int K, bool F32>
+constexpr int reduce_parts() {
+#ifdef PXCHG_TUNE_REDUCE16_PARTS  // binary16 in and out, four to eight workers
+    if (!F32 && K >= 4) return PXCHG_TUNE_REDUCE16_PARTS;
+#endif
+    return 1;
+}
+template <int K>
+constexpr int fused_parts() {  // the fused reduce+update with three to eight workers runs two workgroups per chunk
+#ifdef PXCHG_TUNE_FUSED_PARTS
+    if (K >= 3) return PXCHG_TUNE_FUSED_PARTS;
+#endif
+    return K >= 3 ? 2 : 1;
+}
+
 // Converts every tensor of every worker between binary32 and binary16.  The
 // grid covers k x n_chunks virtual chunks, worker-major.
 template <typename TI, typename TO, int NT>
@@ -374,7 +413,7 @@ constexpr int reduce_lanes() {
 #ifdef PXCHG_TUNE_REDUCE16_LANES  // A/B builds only (paper_1605_08325_amd/tune.py): 64 or 128
     if (!touches_f32<TI, TO>() && !(K >= 1 && K <= 3)) return PXCHG_TUNE_REDUCE16_LANES;
 #endif
-    return (touches_f32<TI, TO>() || (K >= 1 && K <= 3)) ? 64 : 128;
+    return (touches_f32<TI, TO>() || (K >= 1 && K <= 3)) ? 64 : 128 / reduce_parts<K, touches_f32<TI, TO>()>();
 }
 
 struct ReduceArgs {
@@ -462,11 +501,13 @@ struct ReduceOpAnyK {
 
 template <int K, typename TI, typename TO, int NT>
 __global__ __launch_bounds__((reduce_lanes<K, TI, TO>())) void pxchg_reduce_avg_kernel(
-    const PxChunk *__restrict__ chunks, int n_chunks, ReduceArgs args) {
-    constexpr int NTH = reduce_lanes<K, TI, TO>(), U = 512 / NTH;
+    const PxChunk *__restrict__ chunks, int n_chunks, ReduceArgs args, int part_elems) {
+    constexpr int PARTS = reduce_parts<K, touches_f32<TI, TO>()>();
+    constexpr int NTH = reduce_lanes<K, TI, TO>(), U = 512 / (NTH * PARTS);
     constexpr bool SPLIT = touches_f32<TI, TO>() && U == 8;
-    for (int c = blockIdx.x; c < n_chunks; c += gridDim.x) {
-        const PxChunk ch = chunks[c];
+    for (int vc = blockIdx.x; vc < n_chunks * PARTS; vc += gridDim.x) {
+        PxChunk ch = chunks[vc / PARTS];
+        if (!take_part<PARTS>(ch, vc % PARTS, part_elems)) continue;
         ReduceOp<K, TI, TO, NT, U> op;
         op.dst = table_ptr<TO>(args.out, ch.tensor) + ch.start;
         op.use_div = args.use_div;
@@ -579,19 +620,21 @@ struct UpdateOp {
 template <typename TG>
 constexpr int update_lanes() {  // 128 working lanes; as many idle ones for a binary16 gradient
 #ifdef PXCHG_TUNE_NO_IDLE  // A/B builds only: no idle wavefronts anywhere
-    return 128;
+    return 128 / update_parts();
 #else
-    return std::is_same<TG, _Float16>::value ? 256 : 128;
+    return (std::is_same<TG, _Float16>::value ? 256 : 128) / update_parts();
 #endif
 }
 
 template <typename TG, int NT>
 __global__ __launch_bounds__((update_lanes<TG>())) void pxchg_sgd_momentum_kernel(const PxChunk *__restrict__ chunks, int n_chunks,
-                                                                 UpdateArgs args) {
+                                                                 UpdateArgs args, int part_elems) {
     constexpr int U = 4, NTH = update_lanes<TG>();  // two working wavefronts of 4-element lanes
     constexpr bool SPLIT = false;
-    for (int c = blockIdx.x; c < n_chunks; c += gridDim.x) {
-        const PxChunk ch = chunks[c];
+    constexpr int PARTS = update_parts();
+    for (int vc = blockIdx.x; vc < n_chunks * PARTS; vc += gridDim.x) {
+        PxChunk ch = chunks[vc / PARTS];
+        if (!take_part<PARTS>(ch, vc % PARTS, part_elems)) continue;
         UpdateOp<TG, NT, U> op;
         op.g = table_ptr<const TG>(args.grad, ch.tensor) + ch.start;
         op.w = table_ptr<float>(args.param, ch.tensor) + ch.start;
@@ -668,26 +711,29 @@ struct FusedOp {
     }
 };
 
-// Lanes per 512-element chunk in the fused kernel.  Float32 contributions: 2-element (8-byte) lanes measured
-// 3..6 % faster than the split layout of one wavefront for every k.  Binary16 contributions: the same 256
-// lanes (8-byte accesses to w and v, 4-byte ones to the contributions) from k = 3 on (+1..5 %); k = 2 keeps
-// the split layout and k = 1 runs as two wavefronts of 4-element lanes (+4 %).
+// Lanes per workgroup in the fused kernel.  Float32 contributions: 2-element (8-byte) lanes measured
+// 3..6 % faster than the split layout of one wavefront for every k.  Binary16 contributions: the same
+// 2-element lanes (8-byte accesses to w and v, 4-byte ones to the contributions) from k = 3 on (+1..5 %), in
+// two workgroups of 128 lanes per chunk (see fused_parts); k = 2 keeps the split layout and k = 1 runs as
+// two wavefronts of 4-element lanes (+4 %).
 template <int K, typename TI>
 constexpr int fused_lanes() {
-#ifdef PXCHG_TUNE_FUSED_LANES  // A/B builds only: 64 (split layout), 128 or 256 for three or more workers
+#ifdef PXCHG_TUNE_FUSED_LANES  // A/B builds only: lanes per workgroup for three or more workers
     if (K >= 3) return PXCHG_TUNE_FUSED_LANES;
 #endif
-    if (std::is_same<TI, float>::value) return 256;
-    return K == 1 ? 128 : K == 2 ? 64 : 256;
+    if (std::is_same<TI, float>::value) return 256 / fused_parts<K>();
+    return K == 1 ? 128 : K == 2 ? 64 : 256 / fused_parts<K>();
 }
 
 template <int K, typename TI, bool WIRE16, int NT>
 __global__ __launch_bounds__((fused_lanes<K, TI>())) void pxchg_reduce_avg_sgd_momentum_kernel(
-    const PxChunk *__restrict__ chunks, int n_chunks, FusedArgs args) {
-    constexpr int NTH = fused_lanes<K, TI>(), U = 512 / NTH;
+    const PxChunk *__restrict__ chunks, int n_chunks, FusedArgs args, int part_elems) {
+    constexpr int PARTS = fused_parts<K>();
+    constexpr int NTH = fused_lanes<K, TI>(), U = 512 / (NTH * PARTS);
     constexpr bool SPLIT = U == 8;
-    for (int c = blockIdx.x; c < n_chunks; c += gridDim.x) {
-        const PxChunk ch = chunks[c];
+    for (int vc = blockIdx.x; vc < n_chunks * PARTS; vc += gridDim.x) {
+        PxChunk ch = chunks[vc / PARTS];
+        if (!take_part<PARTS>(ch, vc % PARTS, part_elems)) continue;
         FusedOp<K, TI, WIRE16, NT, U> op;
         op.w = table_ptr<float>(args.param, ch.tensor) + ch.start;
         op.v = table_ptr<float>(args.vel, ch.tensor) + ch.start;
@@ -811,8 +857,15 @@ __global__ __launch_bounds__(128) void pxchg_reduce_avg_sgd_momentum_anyk_kernel
 // layout of one wavefront, and 6..9 % faster than with 8- or 16-byte lanes).  Rounds of five or more workers
 // also cut every chunk into two parts, one workgroup of 256 lanes each: the same 4-byte lanes in workgroups of
 // four wavefronts instead of eight measured 2 % faster (cold operands, round of 8: 710.6 against 726.2 us).
+// The single meeting does the same with 16-byte lanes: one working wavefront per 256 elements instead of two per
+// 512 measured 1.5..3.6 % faster on sets of 7 M to 61 M elements and on single tensors up to 300 M, and 0.7..2 %
+// slower on the 138 M set of 32 tensors; narrower lanes in the same two parts lose 11 %.
 template <int K>
 constexpr int elastic_parts() {  // workgroups per chunk
+#ifdef PXCHG_TUNE_ELASTIC1_PARTS  // A/B builds only: 1, 2 or 4 for the single meeting
+    if (K == 1) return PXCHG_TUNE_ELASTIC1_PARTS;
+#endif
+    if (K == 1) return 2;
 #ifdef PXCHG_TUNE_ELASTIC8_PARTS  // A/B builds only: 1 or 2
     return K >= 5 ? PXCHG_TUNE_ELASTIC8_PARTS : 1;
 #else
@@ -824,10 +877,10 @@ constexpr int elastic_lanes() {  // working lanes per workgroup
 #ifdef PXCHG_TUNE_ELASTIC8_LANES  // A/B builds only: 128, 256 or 512 lanes per chunk for rounds of five or more
     if (K >= 5) return PXCHG_TUNE_ELASTIC8_LANES / elastic_parts<K>();
 #endif
-#ifdef PXCHG_TUNE_ELASTIC1_LANES  // A/B builds only: 64, 128 or 256 for the single meeting
+#ifdef PXCHG_TUNE_ELASTIC1_LANES  // A/B builds only: 64, 128 or 256 per workgroup for the single meeting
     if (K == 1) return PXCHG_TUNE_ELASTIC1_LANES;
 #endif
-    return K <= 2 ? 128 : K <= 4 ? 256 : 512 / elastic_parts<K>();
+    return K == 1 ? 64 : K == 2 ? 128 : K <= 4 ? 256 : 512 / elastic_parts<K>();
 }
 
 template <int K>
@@ -896,12 +949,7 @@ __global__ __launch_bounds__((elastic_lanes<K>() * elastic_pad<K>())) void pxchg
     constexpr bool SPLIT = false;
     for (int vc = blockIdx.x; vc < n_chunks * PARTS; vc += gridDim.x) {
         PxChunk ch = chunks[vc / PARTS];
-        if constexpr (PARTS > 1) {  // this workgroup's part of the chunk (uniform over the workgroup)
-            const int off = (vc % PARTS) * args.part_elems;
-            if (off >= ch.len) continue;
-            ch.start += off;
-            ch.len = ch.len - off < args.part_elems ? ch.len - off : args.part_elems;
-        }
+        if (!take_part<PARTS>(ch, vc % PARTS, args.part_elems)) continue;
         ElasticOp<K, NT, U, CR> op;
         op.c = table_ptr<float>(args.c, ch.tensor) + ch.start;
         op.alpha = args.alpha;
@@ -1197,10 +1245,12 @@ int launch_convert(const pxchg_table *t, int k, const pxchg_bufset *const *src, 
 
 template <int K, typename TI, typename TO>
 int launch_reduce_k(const pxchg_table *t, const ReduceArgs &a, hipStream_t stream) {
-    const dim3 grid = grid_for(t, t->n_chunks);
+    constexpr int PARTS = reduce_parts<K, touches_f32<TI, TO>()>();
+    const dim3 grid = grid_for(t, t->n_chunks * PARTS);
+    const int part_elems = (int)(t->chunk_elems / PARTS);
 #define PX_CALL(N)                                                                                                       \
     px_launch(pxchg_reduce_avg_kernel<K, TI, TO, N>, grid, dim3(reduce_lanes<K, TI, TO>()), stream, (const PxChunk *)t->d_chunks, \
-              (int)t->n_chunks, a)
+              (int)t->n_chunks, a, part_elems)
     PX_DISPATCH_NT(PXCHG_TUNE_REDUCE_POLICY, PX_CALL)
 #undef PX_CALL
 }
@@ -1232,10 +1282,11 @@ int launch_reduce(const pxchg_table *t, int k, const ReduceArgs &a, hipStream_t 
 
 template <int K, typename TI, bool WIRE16>
 int launch_fused_k(const pxchg_table *t, const FusedArgs &a, hipStream_t stream) {
-    const dim3 grid = grid_for(t, t->n_chunks);
+    const dim3 grid = grid_for(t, t->n_chunks * fused_parts<K>());
+    const int part_elems = (int)(t->chunk_elems / fused_parts<K>());
 #define PX_CALL(N)                                                                                                   \
     px_launch(pxchg_reduce_avg_sgd_momentum_kernel<K, TI, WIRE16, N>, grid, dim3(fused_lanes<K, TI>()), stream, \
-              (const PxChunk *)t->d_chunks, (int)t->n_chunks, a)
+              (const PxChunk *)t->d_chunks, (int)t->n_chunks, a, part_elems)
     PX_DISPATCH_NT(NT_BOTH, PX_CALL)
 #undef PX_CALL
 }
@@ -1287,10 +1338,12 @@ int launch_elastic_k(const pxchg_table *t, const ElasticArgs &a, hipStream_t str
 
 template <typename TG>
 int launch_update(const pxchg_table *t, const UpdateArgs &a, hipStream_t stream) {
-    const dim3 grid = grid_for(t, t->n_chunks);
+    const dim3 grid = grid_for(t, t->n_chunks * update_parts());
+    const int part_elems = (int)(t->chunk_elems / update_parts());
     constexpr int OWN = std::is_same<TG, _Float16>::value ? NT_LOADS_SC1NT_STORES : NT_BOTH;
-#define PX_CALL(N) \
-    px_launch(pxchg_sgd_momentum_kernel<TG, N>, grid, dim3(update_lanes<TG>()), stream, (const PxChunk *)t->d_chunks, (int)t->n_chunks, a)
+#define PX_CALL(N)                                                                                                          \
+    px_launch(pxchg_sgd_momentum_kernel<TG, N>, grid, dim3(update_lanes<TG>()), stream, (const PxChunk *)t->d_chunks, (int)t->n_chunks, a, \
+              part_elems)
     PX_DISPATCH_NT(OWN, PX_CALL)
 #undef PX_CALL
 }

@@ -40,10 +40,18 @@ VARIANTS = {
     "shipped": [],
     "no_idle_wavefronts": ["-DPXCHG_TUNE_NO_IDLE"],
     "reduce16_64_lanes": ["-DPXCHG_TUNE_REDUCE16_LANES=64"],
-    "fused_64_lanes_split": ["-DPXCHG_TUNE_FUSED_LANES=64"],
-    "fused_128_lanes": ["-DPXCHG_TUNE_FUSED_LANES=128"],
-    "meeting_64_lanes": ["-DPXCHG_TUNE_ELASTIC1_LANES=64"],
-    "meeting_256_lanes": ["-DPXCHG_TUNE_ELASTIC1_LANES=256"],
+    "fused_one_part_256_lanes": ["-DPXCHG_TUNE_FUSED_PARTS=1"],
+    "fused_one_part_64_lanes_split": ["-DPXCHG_TUNE_FUSED_PARTS=1", "-DPXCHG_TUNE_FUSED_LANES=64"],
+    "fused_one_part_128_lanes": ["-DPXCHG_TUNE_FUSED_PARTS=1", "-DPXCHG_TUNE_FUSED_LANES=128"],
+    "meeting_one_part_128_lanes": ["-DPXCHG_TUNE_ELASTIC1_PARTS=1", "-DPXCHG_TUNE_ELASTIC1_LANES=128"],
+    "meeting_one_part_64_lanes": ["-DPXCHG_TUNE_ELASTIC1_PARTS=1", "-DPXCHG_TUNE_ELASTIC1_LANES=64"],
+    "meeting_one_part_256_lanes": ["-DPXCHG_TUNE_ELASTIC1_PARTS=1", "-DPXCHG_TUNE_ELASTIC1_LANES=256"],
+    "meeting_2_parts_128_lanes": ["-DPXCHG_TUNE_ELASTIC1_PARTS=2", "-DPXCHG_TUNE_ELASTIC1_LANES=128"],
+    "meeting_4_parts_64_lanes": ["-DPXCHG_TUNE_ELASTIC1_PARTS=4", "-DPXCHG_TUNE_ELASTIC1_LANES=64"],
+    # two workgroups per chunk for the kernels that ship with one
+    "update_2_parts": ["-DPXCHG_TUNE_UPDATE_PARTS=2"],
+    "update_2_parts_no_idle": ["-DPXCHG_TUNE_UPDATE_PARTS=2", "-DPXCHG_TUNE_NO_IDLE"],
+    "reduce16_2_parts": ["-DPXCHG_TUNE_REDUCE16_PARTS=2"],
     "round8_one_part_512_lanes": ["-DPXCHG_TUNE_ELASTIC8_PARTS=1"],
     "round8_one_part_256_lanes": ["-DPXCHG_TUNE_ELASTIC8_PARTS=1", "-DPXCHG_TUNE_ELASTIC8_LANES=256"],
     "round8_one_part_128_lanes": ["-DPXCHG_TUNE_ELASTIC8_PARTS=1", "-DPXCHG_TUNE_ELASTIC8_LANES=128"],

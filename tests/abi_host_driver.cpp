@@ -319,7 +319,8 @@ int lifetime_and_launches() {
     for (int rc : every_hot_call(table, a, b, c, h, out)) CHECK(rc == PXCHG_OK);
     CHECK(fake::launches == 11);
     CHECK(fake::get_last_error_calls == errs_before && fake::synchronizes == syncs_before);
-    for (size_t i = 0; i < 7; ++i) CHECK(fake::grids[i].x == (unsigned)n_chunks && fake::grids[i].y == 1);
+    // one workgroup per chunk, two for the single meeting (call 4)
+    for (size_t i = 0; i < 7; ++i) CHECK(fake::grids[i].x == (unsigned)(i == 4 ? 2 * n_chunks : n_chunks) && fake::grids[i].y == 1);
     const int64_t n_blocks = (n_chunks + PXCHG_STATS_BLOCK_CHUNKS - 1) / PXCHG_STATS_BLOCK_CHUNKS;
     CHECK(fake::grids[7].x == (unsigned)n_blocks && fake::grids[8].x == 1);
     CHECK(fake::last_block.x == PXCHG_STATS_COMBINE_THREADS);
@@ -339,7 +340,7 @@ int lifetime_and_launches() {
         // a persistent grid: n workgroups per compute unit (the stand-in device has 256 units)
         CHECK(pxchg_set_option(PXCHG_OPT_BLOCKS_PER_CU, 1) == PXCHG_OK);
         CHECK(pxchg_pack_fp16(table, 3, src, dst, nullptr) == PXCHG_OK && fake::last_grid.x == 249);
-        CHECK(pxchg_easgd(table, a, c, 0.5f, nullptr) == PXCHG_OK && fake::last_grid.x == (unsigned)n_chunks);
+        CHECK(pxchg_easgd(table, a, c, 0.5f, nullptr) == PXCHG_OK && fake::last_grid.x == (unsigned)(2 * n_chunks));
         CHECK(pxchg_set_option(PXCHG_OPT_BLOCKS_PER_CU, 0) == PXCHG_OK);
         CHECK(pxchg_bufset_destroy(s2) == PXCHG_OK && pxchg_bufset_destroy(s3) == PXCHG_OK);
     }
@@ -444,7 +445,7 @@ int lifetime_and_launches() {
     fake::launches = 0;
     for (int rc : every_hot_call(view, a, b, c, h, out)) CHECK(rc == PXCHG_OK);
     CHECK(fake::launches == 11);
-    CHECK(pxchg_easgd(view, a, c, 0.1f, nullptr) == PXCHG_OK && fake::last_grid.x == 81);
+    CHECK(pxchg_easgd(view, a, c, 0.1f, nullptr) == PXCHG_OK && fake::last_grid.x == 2 * 81);
     CHECK(pxchg_easgd(view, foreign, c, 0.1f, nullptr) == PXCHG_ERR_SHAPE_MISMATCH);
     CHECK(pxchg_table_destroy(table) == PXCHG_ERR_IN_USE);                              // views and sets alive
     for (int rc : every_hot_call(view, a, b, c, h, out)) CHECK(rc == PXCHG_OK);         // nothing was torn down
