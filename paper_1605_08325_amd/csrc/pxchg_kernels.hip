@@ -341,7 +341,7 @@ struct ConvertOp {
 };
 
 // A chunk may be shared by PARTS workgroups, each taking `part_elems` consecutive elements of it (the table's
-// chunk size over PARTS, a multiple of 256, so a part starts at the same offset from 16-byte alignment as its
+// chunk size over PARTS, a multiple of 64, so a part starts at the same offset from 16-byte alignment as its
 // chunk).  Returns false for a part that lies beyond a short chunk's end.  Uniform over the workgroup.
 template <int PARTS>
 __device__ __forceinline__ bool take_part(PxChunk &ch, int part, int part_elems) {
@@ -858,29 +858,29 @@ __global__ __launch_bounds__(128) void pxchg_reduce_avg_sgd_momentum_anyk_kernel
 // also cut every chunk into two parts, one workgroup of 256 lanes each: the same 4-byte lanes in workgroups of
 // four wavefronts instead of eight measured 2 % faster (cold operands, round of 8: 710.6 against 726.2 us).
 // The single meeting does the same with 16-byte lanes: one working wavefront per 256 elements instead of two per
-// 512 measured 1.5..3.6 % faster on sets of 7 M to 61 M elements and on single tensors up to 300 M, and 0.7..2 %
+// 512 measured 1.5..3.6 % faster on sets of 7 M to 61 M elements and on single tensors up to 300 M, and 0.7..2.5 %
 // slower on the 138 M set of 32 tensors; narrower lanes in the same two parts lose 11 %.
-template <int K>
+template <int K, bool CR>
 constexpr int elastic_parts() {  // workgroups per chunk
 #ifdef PXCHG_TUNE_ELASTIC1_PARTS  // A/B builds only: 1, 2 or 4 for the single meeting
     if (K == 1) return PXCHG_TUNE_ELASTIC1_PARTS;
 #endif
-    if (K == 1) return 2;
+    if (K == 1) return CR ? 1 : 2;  // with the center kept cached, one workgroup per chunk is the faster shape (5 %)
 #ifdef PXCHG_TUNE_ELASTIC8_PARTS  // A/B builds only: 1 or 2
     return K >= 5 ? PXCHG_TUNE_ELASTIC8_PARTS : 1;
 #else
     return K >= 5 ? 2 : 1;
 #endif
 }
-template <int K>
+template <int K, bool CR>
 constexpr int elastic_lanes() {  // working lanes per workgroup
 #ifdef PXCHG_TUNE_ELASTIC8_LANES  // A/B builds only: 128, 256 or 512 lanes per chunk for rounds of five or more
-    if (K >= 5) return PXCHG_TUNE_ELASTIC8_LANES / elastic_parts<K>();
+    if (K >= 5) return PXCHG_TUNE_ELASTIC8_LANES / elastic_parts<K, CR>();
 #endif
 #ifdef PXCHG_TUNE_ELASTIC1_LANES  // A/B builds only: 64, 128 or 256 per workgroup for the single meeting
     if (K == 1) return PXCHG_TUNE_ELASTIC1_LANES;
 #endif
-    return K == 1 ? 64 : K == 2 ? 128 : K <= 4 ? 256 : 512 / elastic_parts<K>();
+    return K == 1 ? 128 / elastic_parts<K, CR>() : K == 2 ? 128 : K <= 4 ? 256 : 512 / elastic_parts<K, CR>();
 }
 
 template <int K>
@@ -942,10 +942,10 @@ struct ElasticOp {
 };
 
 template <int K, int NT, bool CR>
-__global__ __launch_bounds__((elastic_lanes<K>() * elastic_pad<K>())) void pxchg_easgd_kernel(const PxChunk *__restrict__ chunks,
+__global__ __launch_bounds__((elastic_lanes<K, CR>() * elastic_pad<K>())) void pxchg_easgd_kernel(const PxChunk *__restrict__ chunks,
                                                                         int n_chunks, ElasticArgs args) {
-    constexpr int PARTS = elastic_parts<K>();
-    constexpr int U = 512 / (elastic_lanes<K>() * PARTS), NTH = elastic_lanes<K>() * elastic_pad<K>();
+    constexpr int PARTS = elastic_parts<K, CR>();
+    constexpr int U = 512 / (elastic_lanes<K, CR>() * PARTS), NTH = elastic_lanes<K, CR>() * elastic_pad<K>();
     constexpr bool SPLIT = false;
     for (int vc = blockIdx.x; vc < n_chunks * PARTS; vc += gridDim.x) {
         PxChunk ch = chunks[vc / PARTS];
@@ -1318,12 +1318,12 @@ int launch_fused(const pxchg_table *t, int k, const FusedArgs &a, hipStream_t st
 
 template <int K, bool CR>
 int launch_elastic_kc(const pxchg_table *t, const ElasticArgs &a, hipStream_t stream) {
-    const dim3 grid = grid_for(t, t->n_chunks * elastic_parts<K>());
+    const dim3 grid = grid_for(t, t->n_chunks * elastic_parts<K, CR>());
     ElasticArgs b = a;
-    b.part_elems = (int)(t->chunk_elems / elastic_parts<K>());  // elements per workgroup
+    b.part_elems = (int)(t->chunk_elems / elastic_parts<K, CR>());  // elements per workgroup
     constexpr int OWN = K == 2 ? NT_BOTH : NT_LOADS_SC1NT_STORES;
 #define PX_CALL(N)                                                                                                      \
-    px_launch(pxchg_easgd_kernel<K, N, CR>, grid, dim3(elastic_lanes<K>() * elastic_pad<K>()), stream, (const PxChunk *)t->d_chunks, \
+    px_launch(pxchg_easgd_kernel<K, N, CR>, grid, dim3(elastic_lanes<K, CR>() * elastic_pad<K>()), stream, (const PxChunk *)t->d_chunks, \
               (int)t->n_chunks, b)
     PX_DISPATCH_NT(OWN, PX_CALL)
 #undef PX_CALL
