@@ -211,11 +211,16 @@ __device__ __forceinline__ void storev(float *p, const FV<U> &x) {
 }
 template <int NT, int U, bool SPLIT>
 __device__ __forceinline__ void storev(_Float16 *p, const FV<U> &x) {
-    // no narrower form exists: a lane layout with fewer than four binary16 elements per lane must not compile
-    // (the 16-byte branch below would store eight elements whatever U says)
-    static_assert(U == 4 || U == 8, "8 or 16 bytes");
+    // a lane layout with any other number of binary16 elements per lane must not compile (the 16-byte branch
+    // below would store eight elements whatever U says)
+    static_assert(U == 2 || U == 4 || U == 8, "4, 8 or 16 bytes");
     static_assert(!SPLIT || U == 8, "the split layout is two groups of four");
-    if constexpr (U == 4 || SPLIT) {
+    if constexpr (U == 2) {
+        f16x2 a;
+        a[0] = (_Float16)x.v[0];  // round to nearest even
+        a[1] = (_Float16)x.v[1];
+        stv<NT>((PX_GLOBAL f16x2 *)p, a);
+    } else if constexpr (U == 4 || SPLIT) {
         f16x4 a;
 #pragma unroll
         for (int i = 0; i < 4; ++i) a[i] = (_Float16)x.v[i];  // round to nearest even
@@ -402,7 +407,8 @@ __global__ __launch_bounds__(64) void pxchg_convert_kernel(const PxChunk *__rest
 // ---------------------------------------------------------------- reduce + average
 
 // Lanes per 512-element chunk in the reduce kernels.  Binary16 in and out with four or more workers runs as
-// two wavefronts of 4-element (8-byte) lanes, measured 5..8 % faster than one wavefront of 8-element lanes;
+// two wavefronts of 4-element (8-byte) lanes, measured 2..8 % faster than one wavefront of 8-element lanes and
+// 6 % faster than four wavefronts of 2-element lanes;
 // with fewer workers a wavefront would have too little in flight that way (k = 1: 30 % slower), so those keep
 // one wavefront of 8-element lanes.  Float32 in and out with four or more workers: 2-element (8-byte) lanes,
 // +1..3 % over the split layout of one wavefront, which every other combination with float32 on either side
@@ -410,7 +416,7 @@ __global__ __launch_bounds__(64) void pxchg_convert_kernel(const PxChunk *__rest
 template <int K, typename TI, typename TO>
 constexpr int reduce_lanes() {
     if (std::is_same<TI, float>::value && std::is_same<TO, float>::value && K >= 4) return 256;
-#ifdef PXCHG_TUNE_REDUCE16_LANES  // A/B builds only (paper_1605_08325_amd/tune.py): 64 or 128
+#ifdef PXCHG_TUNE_REDUCE16_LANES  // A/B builds only (paper_1605_08325_amd/tune.py): 64, 128 or 256
     if (!touches_f32<TI, TO>() && !(K >= 1 && K <= 3)) return PXCHG_TUNE_REDUCE16_LANES;
 #endif
     return (touches_f32<TI, TO>() || (K >= 1 && K <= 3)) ? 64 : 128 / reduce_parts<K, touches_f32<TI, TO>()>();

@@ -52,6 +52,7 @@ VARIANTS = {
     "update_2_parts": ["-DPXCHG_TUNE_UPDATE_PARTS=2"],
     "update_2_parts_no_idle": ["-DPXCHG_TUNE_UPDATE_PARTS=2", "-DPXCHG_TUNE_NO_IDLE"],
     "reduce16_2_parts": ["-DPXCHG_TUNE_REDUCE16_PARTS=2"],
+    "reduce16_256_lanes": ["-DPXCHG_TUNE_REDUCE16_LANES=256"],
     "round8_4_parts_128_lanes": ["-DPXCHG_TUNE_ELASTIC8_PARTS=4"],
     "round8_one_part_512_lanes": ["-DPXCHG_TUNE_ELASTIC8_PARTS=1"],
     "round8_one_part_256_lanes": ["-DPXCHG_TUNE_ELASTIC8_PARTS=1", "-DPXCHG_TUNE_ELASTIC8_LANES=256"],
