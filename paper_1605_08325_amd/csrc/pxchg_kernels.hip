@@ -384,16 +384,34 @@ constexpr int fused_parts() {  // the fused reduce+update with three to eight wo
     return K >= 3 ? 2 : 1;
 }
 
-// Converts every tensor of every worker between binary32 and binary16.  The
-// grid covers k x n_chunks virtual chunks, worker-major.
+// Converts every tensor of every worker between binary32 and binary16.  The grid covers k x n_chunks virtual
+// chunks, worker-major.  One wavefront in the split layout per chunk (A/B builds: other lanes, or several
+// workgroups per chunk).
+constexpr int convert_parts() {
+#ifdef PXCHG_TUNE_CONVERT_PARTS
+    return PXCHG_TUNE_CONVERT_PARTS;
+#else
+    return 1;
+#endif
+}
+constexpr int convert_lanes() {  // per workgroup
+#ifdef PXCHG_TUNE_CONVERT_LANES
+    return PXCHG_TUNE_CONVERT_LANES;
+#else
+    return 64;
+#endif
+}
 template <typename TI, typename TO, int NT>
-__global__ __launch_bounds__(64) void pxchg_convert_kernel(const PxChunk *__restrict__ chunks, int n_chunks,
-                                                           int64_t n_virtual, ConvertArgs args) {
-    constexpr int U = 8, NTH = 64;
-    constexpr bool SPLIT = true;  // float32 on one side
+__global__ __launch_bounds__(convert_lanes()) void pxchg_convert_kernel(const PxChunk *__restrict__ chunks, int n_chunks,
+                                                                        int64_t n_virtual, ConvertArgs args, int part_elems) {
+    constexpr int PARTS = convert_parts(), NTH = convert_lanes(), U = 512 / (NTH * PARTS);
+    constexpr bool SPLIT = U == 8;  // float32 on one side
+    const int64_t per_worker = (int64_t)n_chunks * PARTS;
     for (int64_t vc = blockIdx.x; vc < n_virtual; vc += gridDim.x) {
-        const int w = (int)(vc / n_chunks);
-        const PxChunk ch = chunks[vc - (int64_t)w * n_chunks];
+        const int w = (int)(vc / per_worker);
+        const int rest = (int)(vc - (int64_t)w * per_worker);
+        PxChunk ch = chunks[rest / PARTS];
+        if (!take_part<PARTS>(ch, rest % PARTS, part_elems)) continue;
         ConvertOp<TI, TO, NT, U> op;
         op.src = table_ptr<const TI>(args.src[w], ch.tensor) + ch.start;
         op.dst = table_ptr<TO>(args.dst[w], ch.tensor) + ch.start;
@@ -1236,11 +1254,13 @@ int launch_convert(const pxchg_table *t, int k, const pxchg_bufset *const *src, 
         for (int j = i + 1; j < k; ++j)
             if (dst[i] == dst[j]) return PXCHG_ERR_INVALID_ARG;
     if (t->n_chunks == 0) return PXCHG_OK;
-    const int64_t n_virtual = t->n_chunks * k;
+    const int64_t n_virtual = t->n_chunks * k * convert_parts();
     const dim3 grid = grid_for(t, n_virtual);
+    const int part_elems = (int)(t->chunk_elems / convert_parts());
     constexpr int OWN = sizeof(TO) < sizeof(TI) ? NT_LOADS_SC1NT_STORES : NT_LOADS_SC1_STORES;
-#define PX_CALL(N) \
-    px_launch(pxchg_convert_kernel<TI, TO, N>, grid, dim3(64), stream, (const PxChunk *)t->d_chunks, (int)t->n_chunks, n_virtual, a)
+#define PX_CALL(N)                                                                                                      \
+    px_launch(pxchg_convert_kernel<TI, TO, N>, grid, dim3(convert_lanes()), stream, (const PxChunk *)t->d_chunks, (int)t->n_chunks, \
+              n_virtual, a, part_elems)
     PX_DISPATCH_NT(OWN, PX_CALL)
 #undef PX_CALL
 }

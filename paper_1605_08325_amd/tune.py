@@ -39,6 +39,8 @@ TUNE_DIR = os.path.join(HERE, "_build", "tune")
 VARIANTS = {
     "shipped": [],
     "no_idle_wavefronts": ["-DPXCHG_TUNE_NO_IDLE"],
+    "pack_128_lanes": ["-DPXCHG_TUNE_CONVERT_LANES=128"],
+    "pack_2_parts": ["-DPXCHG_TUNE_CONVERT_PARTS=2"],
     "reduce16_64_lanes": ["-DPXCHG_TUNE_REDUCE16_LANES=64"],
     "fused_one_part_256_lanes": ["-DPXCHG_TUNE_FUSED_PARTS=1"],
     "fused_one_part_64_lanes_split": ["-DPXCHG_TUNE_FUSED_PARTS=1", "-DPXCHG_TUNE_FUSED_LANES=64"],
