@@ -447,6 +447,22 @@ def test_results_do_not_depend_on_launch_shape(px, oracle_mod, chunk, bpc):
         assert_bits_equal(to_host(d_x), x_, "elastic launch shape")
         assert_bits_equal(to_host(d_c), c_, "elastic launch shape")
         assert_bits_equal(to_host(d_w), w_, "elastic round launch shape")
+        # the kernels that run two workgroups per chunk: fused reduce+update of 8, elastic round of 5
+        w2, v2 = _gauss(RAGGED, 956, role="param"), _gauss(RAGGED, 957, sigma=1e-3, role="velocity")
+        d_w2, d_v2 = to_device(w2), to_device(v2)
+        px.reduce_avg_sgd_momentum(table, sets, table.bufset(d_w2), table.bufset(d_v2), 0.01, 0.9, 5e-4, wire_dtype=px.F16)
+        oracle_mod.sgd_momentum_tensors(avg, w2, v2, 0.01, 0.9, 5e-4)
+        assert_bits_equal(to_host(d_w2), w2, "fused launch shape")
+        assert_bits_equal(to_host(d_v2), v2, "fused launch shape")
+        xs5 = [_gauss(RAGGED, 960 + i, role="worker") for i in range(5)]
+        c5 = _gauss(RAGGED, 959, role="center")
+        d_xs5, d_c5 = [to_device(x) for x in xs5], to_device(c5)
+        px.easgd_round(table, [table.bufset(d) for d in d_xs5], table.bufset(d_c5), 0.0625)
+        for x in xs5:
+            oracle_mod.easgd_tensors(x, c5, 0.0625)
+        assert_bits_equal(to_host(d_c5), c5, "round of 5 launch shape")
+        for i in range(5):
+            assert_bits_equal(to_host(d_xs5[i]), xs5[i], "round of 5 launch shape")
     finally:
         px.set_option(px.OPT_CHUNK_ELEMS, old[0])
         px.set_option(px.OPT_BLOCKS_PER_CU, old[1])
