@@ -65,8 +65,8 @@ enum pxchg_mode { PXCHG_AVG = 0, PXCHG_SUM = 1 };  /* divide the sum by k, or no
 enum pxchg_option {
     PXCHG_OPT_CHUNK_ELEMS = 0,   /* elements per work chunk for tables created afterwards;
                                     multiple of 512, 512..1048576; default 512 */
-    PXCHG_OPT_BLOCKS_PER_CU = 1, /* 0 (default): one workgroup per chunk; n>0: n persistent
-                                    workgroups per compute unit, each looping over chunks */
+    PXCHG_OPT_BLOCKS_PER_CU = 1, /* 0 (default): one workgroup per chunk (two for some kernels, each taking half
+                                    of it); n>0: n persistent workgroups per compute unit, each looping over chunks */
     PXCHG_OPT_CHECK_RANGES = 2,  /* 1 (default): pxchg_bufset_create verifies that each tensor lies
                                     inside one device allocation */
     PXCHG_OPT_NONTEMPORAL = 3,   /* -1 (default): each kernel's own measured-best policy; 0: plain loads and
