@@ -33,7 +33,8 @@
 
 namespace {
 
-// A workgroup takes one 512-element chunk, and every memory instruction of a
+// A workgroup takes one 512-element chunk (or half of one, in the kernels that
+// run two workgroups per chunk: see take_part), and every memory instruction of a
 // wavefront covers one contiguous stretch (1 KiB for 16-byte lanes).  Three lane
 // layouts do that, chosen per kernel by measurement on MI355X (the rule of thumb
 // behind the choices: a wavefront should have 2..4 KiB of loads in flight, and
