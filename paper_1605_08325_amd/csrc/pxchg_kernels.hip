@@ -85,6 +85,28 @@ __device__ __forceinline__ T *table_ptr(void *const *table, int tensor) {
     return (T *)((void *const PX_CONST *)table)[tensor];
 }
 
+// On tables of many small tensors the reduce fetches its pointers lane-parallel instead: lane i of every wavefront
+// reads operand i's pointer for the chunk's tensor with ONE vector load, and the wavefront then reads lanes 0..K
+// out.  A workgroup's K + 1 scalar loads become one vector load.  Where the scalar loads miss their cache for most
+// chunks (few chunks per tensor) that measured 3..7 % on the reduce: 116 tensors in 7 M elements 25.5 against 26.4
+// us, 128 in 13.4 M 44.7 against 46.2, 512 in 7 M 23.7 against 25.1, 2048 in 61 M 177 against 187.  With many chunks
+// per tensor it is level or slower (AlexNet shapes 181 against 177, in step 171 against 168; VGGNet shapes in step
+// 393 against 382), so the launch picks by the table's average (lane_parallel_pointers below).  The other kernels
+// keep the scalar loads at any tensor count: the same change cost the update 7 %, the meeting 18 %, the fused
+// reduce+update 2..6 % and the pack 4 % (the round of 8: level, 5 % faster with 2048 tensors).
+// A/B builds: PXCHG_TUNE_REDUCE_POINTERS = 0 (always scalar) or 1 (always lane-parallel).
+// (The lane's table is picked with a chain of selects over the kernel's own arguments: an array of tables handed
+// to a helper ends up in scratch memory and costs 15..45 %.)
+__device__ __forceinline__ uintptr_t table_entry(const void *const *tab, int tensor) {  // a vector load
+    return (uintptr_t)((const void *const PX_GLOBAL *)tab)[tensor];
+}
+template <typename T>
+__device__ __forceinline__ T *lane_pointer(uintptr_t mine, int i) {  // lane i's value; i is the same in every lane
+    const unsigned lo = __builtin_amdgcn_readlane((unsigned)mine, i);
+    const unsigned hi = __builtin_amdgcn_readlane((unsigned)(mine >> 32), i);
+    return (T *)(((uintptr_t)hi << 32) | lo);
+}
+
 template <int U>
 struct FV {
     float v[U];
@@ -266,6 +288,31 @@ __device__ __forceinline__ void vector_step(const Op &op, int i) {
     op.template store<SP>(st, i);
 }
 
+// Lanes that cooperate on a chunk, out of a workgroup of THREADS of which the first WORK have vector work.  As
+// shipped every lane takes part (the idle wavefronts help only where a chunk goes element by element); in the A/B
+// builds with PXCHG_TUNE_IDLE_EXIT the idle wavefronts leave at kernel entry instead, before they load anything
+// (1), or after they have read the chunk's descriptor and before they read any pointer (2).
+#if defined(PXCHG_TUNE_IDLE_EXIT) && PXCHG_TUNE_IDLE_EXIT == 1
+#define PX_IDLE_WAVEFRONTS(WORK, THREADS)                      \
+    static_assert((WORK) % 64 == 0, "whole wavefronts");       \
+    if ((int)threadIdx.x >= (WORK)) return;                    \
+    constexpr int NTH = (WORK)
+#define PX_IDLE_AFTER_DESCRIPTOR(ch)
+#elif defined(PXCHG_TUNE_IDLE_EXIT) && PXCHG_TUNE_IDLE_EXIT == 2  // they read the chunk's descriptor, then leave
+#define PX_IDLE_WAVEFRONTS(WORK, THREADS)                      \
+    static_assert((WORK) % 64 == 0, "whole wavefronts");       \
+    constexpr int PX_WORK = (WORK);                            \
+    constexpr int NTH = (WORK)
+#define PX_IDLE_AFTER_DESCRIPTOR(ch)                           \
+    if ((int)threadIdx.x >= PX_WORK) {                         \
+        asm volatile("" ::"s"((ch).len));                      \
+        continue;                                              \
+    }
+#else
+#define PX_IDLE_WAVEFRONTS(WORK, THREADS) constexpr int NTH = (THREADS)
+#define PX_IDLE_AFTER_DESCRIPTOR(ch)
+#endif
+
 // Walks one chunk with NTH cooperating lanes (`tid` is the lane's index among them): an element-wise head
 // until every operand is aligned, U-element vector steps, an element-wise tail.  `head` < 0 means the operands
 // cannot be aligned together and the whole chunk goes element by element.  With SPLIT (U = 8) the vector part
@@ -441,6 +488,15 @@ constexpr int reduce_lanes() {
     return (touches_f32<TI, TO>() || (K >= 1 && K <= 3)) ? 64 : 128 / reduce_parts<K, touches_f32<TI, TO>()>();
 }
 
+// Workgroup size of the reduce kernels: the working lanes, plus idle wavefronts in A/B builds only.
+template <int K, typename TI, typename TO>
+constexpr int reduce_threads() {
+#ifdef PXCHG_TUNE_REDUCE16_IDLE  // idle wavefronts for binary16 in and out with four to eight workers
+    if (!touches_f32<TI, TO>() && K >= 4) return reduce_lanes<K, TI, TO>() + 64 * PXCHG_TUNE_REDUCE16_IDLE;
+#endif
+    return reduce_lanes<K, TI, TO>();
+}
+
 struct ReduceArgs {
     const void *const *contrib[PXCHG_MAX_K];
     void *const *out;
@@ -524,22 +580,36 @@ struct ReduceOpAnyK {
     __device__ __forceinline__ void store(const State &st, int i) const { storev<NT, U, SP>(dst + i, st.s); }
 };
 
-template <int K, typename TI, typename TO, int NT>
-__global__ __launch_bounds__((reduce_lanes<K, TI, TO>())) void pxchg_reduce_avg_kernel(
+template <int K, typename TI, typename TO, int NT, bool LANE_POINTERS>
+__global__ __launch_bounds__((reduce_threads<K, TI, TO>())) void pxchg_reduce_avg_kernel(
     const PxChunk *__restrict__ chunks, int n_chunks, ReduceArgs args, int part_elems) {
     constexpr int PARTS = reduce_parts<K, touches_f32<TI, TO>()>();
-    constexpr int NTH = reduce_lanes<K, TI, TO>(), U = 512 / (NTH * PARTS);
+    constexpr int U = 512 / (reduce_lanes<K, TI, TO>() * PARTS);
+    PX_IDLE_WAVEFRONTS((reduce_lanes<K, TI, TO>()), (reduce_threads<K, TI, TO>()));
     constexpr bool SPLIT = touches_f32<TI, TO>() && U == 8;
     for (int vc = blockIdx.x; vc < n_chunks * PARTS; vc += gridDim.x) {
         PxChunk ch = chunks[vc / PARTS];
+        PX_IDLE_AFTER_DESCRIPTOR(ch)
         if (!take_part<PARTS>(ch, vc % PARTS, part_elems)) continue;
         ReduceOp<K, TI, TO, NT, U> op;
-        op.dst = table_ptr<TO>(args.out, ch.tensor) + ch.start;
         op.use_div = args.use_div;
         op.kf = args.kf;
         op.scale = args.scale;
+        if constexpr (LANE_POINTERS) {
+            const int lane = threadIdx.x & 63;
+            const void *const *tab = (const void *const *)args.out;  // lanes K.. (lane K's is the one read out)
 #pragma unroll
-        for (int w = 0; w < K; ++w) op.src[w] = table_ptr<const TI>(args.contrib[w], ch.tensor) + ch.start;
+            for (int w = 0; w < K; ++w)
+                if (lane == w) tab = args.contrib[w];
+            const uintptr_t mine = table_entry(tab, ch.tensor);
+            op.dst = lane_pointer<TO>(mine, K) + ch.start;
+#pragma unroll
+            for (int w = 0; w < K; ++w) op.src[w] = lane_pointer<const TI>(mine, w) + ch.start;
+        } else {
+            op.dst = table_ptr<TO>(args.out, ch.tensor) + ch.start;
+#pragma unroll
+            for (int w = 0; w < K; ++w) op.src[w] = table_ptr<const TI>(args.contrib[w], ch.tensor) + ch.start;
+        }
         int head = head_of((uintptr_t)op.dst, sizeof(TO));
         unsigned bad = misalign_after<U>((uintptr_t)op.dst, sizeof(TO), head);
 #pragma unroll
@@ -644,6 +714,9 @@ struct UpdateOp {
 // Lanes beyond the working ones still take part in the element-wise paths.
 template <typename TG>
 constexpr int update_lanes() {  // 128 working lanes; as many idle ones for a binary16 gradient
+#ifdef PXCHG_TUNE_UPDATE_THREADS  // A/B builds only: workgroup size for a binary16 gradient (128 lanes work)
+    if (std::is_same<TG, _Float16>::value) return PXCHG_TUNE_UPDATE_THREADS;
+#endif
 #ifdef PXCHG_TUNE_NO_IDLE  // A/B builds only: no idle wavefronts anywhere
     return 128 / update_parts();
 #else
@@ -654,11 +727,13 @@ constexpr int update_lanes() {  // 128 working lanes; as many idle ones for a bi
 template <typename TG, int NT>
 __global__ __launch_bounds__((update_lanes<TG>())) void pxchg_sgd_momentum_kernel(const PxChunk *__restrict__ chunks, int n_chunks,
                                                                  UpdateArgs args, int part_elems) {
-    constexpr int U = 4, NTH = update_lanes<TG>();  // two working wavefronts of 4-element lanes
+    constexpr int U = 4;  // two working wavefronts of 4-element lanes (one per workgroup in the A/B build with two parts)
     constexpr bool SPLIT = false;
     constexpr int PARTS = update_parts();
+    PX_IDLE_WAVEFRONTS(128 / PARTS, update_lanes<TG>());
     for (int vc = blockIdx.x; vc < n_chunks * PARTS; vc += gridDim.x) {
         PxChunk ch = chunks[vc / PARTS];
+        PX_IDLE_AFTER_DESCRIPTOR(ch)
         if (!take_part<PARTS>(ch, vc % PARTS, part_elems)) continue;
         UpdateOp<TG, NT, U> op;
         op.g = table_ptr<const TG>(args.grad, ch.tensor) + ch.start;
@@ -750,18 +825,30 @@ constexpr int fused_lanes() {
     return K == 1 ? 128 : K == 2 ? 64 : 256 / fused_parts<K>();
 }
 
+template <int K, typename TI>
+constexpr int fused_threads() {  // the working lanes, plus idle wavefronts in A/B builds only
+#ifdef PXCHG_TUNE_FUSED_IDLE
+    if (K >= 3) return fused_lanes<K, TI>() + 64 * PXCHG_TUNE_FUSED_IDLE;
+#endif
+    return fused_lanes<K, TI>();
+}
+
 template <int K, typename TI, bool WIRE16, int NT>
-__global__ __launch_bounds__((fused_lanes<K, TI>())) void pxchg_reduce_avg_sgd_momentum_kernel(
+__global__ __launch_bounds__((fused_threads<K, TI>())) void pxchg_reduce_avg_sgd_momentum_kernel(
     const PxChunk *__restrict__ chunks, int n_chunks, FusedArgs args, int part_elems) {
     constexpr int PARTS = fused_parts<K>();
-    constexpr int NTH = fused_lanes<K, TI>(), U = 512 / (NTH * PARTS);
+    constexpr int U = 512 / (fused_lanes<K, TI>() * PARTS);
+    PX_IDLE_WAVEFRONTS((fused_lanes<K, TI>()), (fused_threads<K, TI>()));
     constexpr bool SPLIT = U == 8;
     for (int vc = blockIdx.x; vc < n_chunks * PARTS; vc += gridDim.x) {
         PxChunk ch = chunks[vc / PARTS];
+        PX_IDLE_AFTER_DESCRIPTOR(ch)
         if (!take_part<PARTS>(ch, vc % PARTS, part_elems)) continue;
         FusedOp<K, TI, WIRE16, NT, U> op;
         op.w = table_ptr<float>(args.param, ch.tensor) + ch.start;
         op.v = table_ptr<float>(args.vel, ch.tensor) + ch.start;
+#pragma unroll
+        for (int q = 0; q < K; ++q) op.src[q] = table_ptr<const TI>(args.contrib[q], ch.tensor) + ch.start;
         op.use_div = args.use_div;
         op.kf = args.kf;
         op.scale = args.scale;
@@ -769,8 +856,6 @@ __global__ __launch_bounds__((fused_lanes<K, TI>())) void pxchg_reduce_avg_sgd_m
         op.mu = args.mu;
         op.wd = args.wd;
         tensor_rates(args.mult, ch.tensor, op.lr, op.wd);
-#pragma unroll
-        for (int q = 0; q < K; ++q) op.src[q] = table_ptr<const TI>(args.contrib[q], ch.tensor) + ch.start;
         int head = head_of((uintptr_t)op.src[0], sizeof(TI));
         unsigned bad = misalign_after<U>((uintptr_t)op.w, 4, head) | misalign_after<U>((uintptr_t)op.v, 4, head);
 #pragma unroll
@@ -908,12 +993,23 @@ constexpr int elastic_lanes() {  // working lanes per workgroup
     return K == 1 ? 128 / elastic_parts<K, CR>() : K == 2 ? 128 : K <= 4 ? 256 : 512 / elastic_parts<K, CR>();
 }
 
-template <int K>
-constexpr int elastic_pad() {  // workgroup size over working lanes: one idle wavefront per working one (see update_lanes)
+// Workgroup size over working lanes.  Idle wavefronts (see update_lanes): one per working wavefront for the fused
+// round of two and for the meeting with the center kept cached, two for the single meeting, whose workgroups
+// then are one working wavefront and two idle ones (measured against one idle wavefront: -1.7 % at 61 M, -2.1 % at
+// 138 M, -1.5 % at 7 M and 13 M; three idle ones are level at 61 M and 4 % slower at 138 M, five and more lose 40 %
+// and upwards).
+template <int K, bool CR>
+constexpr int elastic_pad() {
+#ifdef PXCHG_TUNE_ELASTIC1_PAD  // A/B builds only: 1..6 for the single meeting
+    if (K == 1) return PXCHG_TUNE_ELASTIC1_PAD;
+#endif
+#ifdef PXCHG_TUNE_ELASTIC8_PAD  // A/B builds only: 1 or 2 for rounds of five or more
+    if (K >= 5) return PXCHG_TUNE_ELASTIC8_PAD;
+#endif
 #ifdef PXCHG_TUNE_NO_IDLE
     return 1;
 #else
-    return K <= 2 ? 2 : 1;
+    return K == 1 && !CR ? 3 : K <= 2 ? 2 : 1;
 #endif
 }
 
@@ -967,17 +1063,19 @@ struct ElasticOp {
 };
 
 template <int K, int NT, bool CR>
-__global__ __launch_bounds__((elastic_lanes<K, CR>() * elastic_pad<K>())) void pxchg_easgd_kernel(const PxChunk *__restrict__ chunks,
+__global__ __launch_bounds__((elastic_lanes<K, CR>() * elastic_pad<K, CR>())) void pxchg_easgd_kernel(const PxChunk *__restrict__ chunks,
                                                                         int n_chunks, ElasticArgs args) {
     constexpr int PARTS = elastic_parts<K, CR>();
-    constexpr int U = 512 / (elastic_lanes<K, CR>() * PARTS), NTH = elastic_lanes<K, CR>() * elastic_pad<K>();
+    constexpr int U = 512 / (elastic_lanes<K, CR>() * PARTS);
+    PX_IDLE_WAVEFRONTS((elastic_lanes<K, CR>()), (elastic_lanes<K, CR>() * elastic_pad<K, CR>()));
     constexpr bool SPLIT = false;
     for (int vc = blockIdx.x; vc < n_chunks * PARTS; vc += gridDim.x) {
         PxChunk ch = chunks[vc / PARTS];
+        PX_IDLE_AFTER_DESCRIPTOR(ch)
         if (!take_part<PARTS>(ch, vc % PARTS, args.part_elems)) continue;
         ElasticOp<K, NT, U, CR> op;
-        op.c = table_ptr<float>(args.c, ch.tensor) + ch.start;
         op.alpha = args.alpha;
+        op.c = table_ptr<float>(args.c, ch.tensor) + ch.start;
 #pragma unroll
         for (int q = 0; q < K; ++q) op.x[q] = table_ptr<float>(args.x[q], ch.tensor) + ch.start;
         int head = head_of((uintptr_t)op.c, 4);
@@ -1270,16 +1368,32 @@ int launch_convert(const pxchg_table *t, int k, const pxchg_bufset *const *src, 
 #define PXCHG_TUNE_REDUCE_POLICY NT_LOADS_SC1_STORES
 #endif
 
-template <int K, typename TI, typename TO>
-int launch_reduce_k(const pxchg_table *t, const ReduceArgs &a, hipStream_t stream) {
+// Whether the reduce should fetch its pointers lane-parallel on this table (or view): tensors of at most 512 chunks
+// on average.  Measured: better up to 204 chunks per tensor, level at 1027, worse from 7400 on.
+bool lane_parallel_pointers(const pxchg_table *t) {
+#ifdef PXCHG_TUNE_REDUCE_POINTERS
+    return PXCHG_TUNE_REDUCE_POINTERS != 0;
+#else
+    return t->n_chunks <= (int64_t)512 * t->n_tensors;
+#endif
+}
+
+template <int K, typename TI, typename TO, bool LANE_POINTERS>
+int launch_reduce_kp(const pxchg_table *t, const ReduceArgs &a, hipStream_t stream) {
     constexpr int PARTS = reduce_parts<K, touches_f32<TI, TO>()>();
     const dim3 grid = grid_for(t, t->n_chunks * PARTS);
     const int part_elems = (int)(t->chunk_elems / PARTS);
-#define PX_CALL(N)                                                                                                       \
-    px_launch(pxchg_reduce_avg_kernel<K, TI, TO, N>, grid, dim3(reduce_lanes<K, TI, TO>()), stream, (const PxChunk *)t->d_chunks, \
-              (int)t->n_chunks, a, part_elems)
+#define PX_CALL(N)                                                                                                \
+    px_launch(pxchg_reduce_avg_kernel<K, TI, TO, N, LANE_POINTERS>, grid, dim3(reduce_threads<K, TI, TO>()), stream, \
+              (const PxChunk *)t->d_chunks, (int)t->n_chunks, a, part_elems)
     PX_DISPATCH_NT(PXCHG_TUNE_REDUCE_POLICY, PX_CALL)
 #undef PX_CALL
+}
+
+template <int K, typename TI, typename TO>
+int launch_reduce_k(const pxchg_table *t, const ReduceArgs &a, hipStream_t stream) {
+    return lane_parallel_pointers(t) ? launch_reduce_kp<K, TI, TO, true>(t, a, stream)
+                                     : launch_reduce_kp<K, TI, TO, false>(t, a, stream);
 }
 
 template <typename TI, typename TO>
@@ -1312,7 +1426,7 @@ int launch_fused_k(const pxchg_table *t, const FusedArgs &a, hipStream_t stream)
     const dim3 grid = grid_for(t, t->n_chunks * fused_parts<K>());
     const int part_elems = (int)(t->chunk_elems / fused_parts<K>());
 #define PX_CALL(N)                                                                                                   \
-    px_launch(pxchg_reduce_avg_sgd_momentum_kernel<K, TI, WIRE16, N>, grid, dim3(fused_lanes<K, TI>()), stream, \
+    px_launch(pxchg_reduce_avg_sgd_momentum_kernel<K, TI, WIRE16, N>, grid, dim3(fused_threads<K, TI>()), stream, \
               (const PxChunk *)t->d_chunks, (int)t->n_chunks, a, part_elems)
     PX_DISPATCH_NT(NT_BOTH, PX_CALL)
 #undef PX_CALL
@@ -1350,7 +1464,7 @@ int launch_elastic_kc(const pxchg_table *t, const ElasticArgs &a, hipStream_t st
     b.part_elems = (int)(t->chunk_elems / elastic_parts<K, CR>());  // elements per workgroup
     constexpr int OWN = K == 2 ? NT_BOTH : NT_LOADS_SC1NT_STORES;
 #define PX_CALL(N)                                                                                                      \
-    px_launch(pxchg_easgd_kernel<K, N, CR>, grid, dim3(elastic_lanes<K, CR>() * elastic_pad<K>()), stream, (const PxChunk *)t->d_chunks, \
+    px_launch(pxchg_easgd_kernel<K, N, CR>, grid, dim3(elastic_lanes<K, CR>() * elastic_pad<K, CR>()), stream, (const PxChunk *)t->d_chunks, \
               (int)t->n_chunks, b)
     PX_DISPATCH_NT(OWN, PX_CALL)
 #undef PX_CALL

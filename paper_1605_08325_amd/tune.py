@@ -39,17 +39,31 @@ TUNE_DIR = os.path.join(HERE, "_build", "tune")
 VARIANTS = {
     "shipped": [],
     "no_idle_wavefronts": ["-DPXCHG_TUNE_NO_IDLE"],
+    "update_1_idle_wavefront": ["-DPXCHG_TUNE_UPDATE_THREADS=192"],
+    "update_4_idle_wavefronts": ["-DPXCHG_TUNE_UPDATE_THREADS=384"],
+    "meeting_1_idle_wavefront": ["-DPXCHG_TUNE_ELASTIC1_PAD=2"],
+    "meeting_3_idle_wavefronts": ["-DPXCHG_TUNE_ELASTIC1_PAD=4"],
+    "meeting_5_idle_wavefronts": ["-DPXCHG_TUNE_ELASTIC1_PAD=6"],
+    "idle_wavefronts_leave_at_entry": ["-DPXCHG_TUNE_IDLE_EXIT=1"],
+    "idle_wavefronts_leave_after_descriptor": ["-DPXCHG_TUNE_IDLE_EXIT=2"],
+    "reduce16_2_idle_leave_after_descriptor": ["-DPXCHG_TUNE_REDUCE16_IDLE=2", "-DPXCHG_TUNE_IDLE_EXIT=2"],
+    "fused_1_idle_leave_after_descriptor": ["-DPXCHG_TUNE_FUSED_IDLE=1", "-DPXCHG_TUNE_IDLE_EXIT=2"],
+    "reduce16_2_idle_wavefronts": ["-DPXCHG_TUNE_REDUCE16_IDLE=2"],
+    "fused_1_idle_wavefront": ["-DPXCHG_TUNE_FUSED_IDLE=1"],
+    "round8_4_idle_wavefronts": ["-DPXCHG_TUNE_ELASTIC8_PAD=2"],
+    "reduce_pointers_by_scalar_loads": ["-DPXCHG_TUNE_REDUCE_POINTERS=0"],
+    "reduce_pointers_lane_parallel": ["-DPXCHG_TUNE_REDUCE_POINTERS=1"],
     "pack_128_lanes": ["-DPXCHG_TUNE_CONVERT_LANES=128"],
     "pack_2_parts": ["-DPXCHG_TUNE_CONVERT_PARTS=2"],
     "reduce16_64_lanes": ["-DPXCHG_TUNE_REDUCE16_LANES=64"],
     "fused_one_part_256_lanes": ["-DPXCHG_TUNE_FUSED_PARTS=1"],
     "fused_one_part_64_lanes_split": ["-DPXCHG_TUNE_FUSED_PARTS=1", "-DPXCHG_TUNE_FUSED_LANES=64"],
     "fused_one_part_128_lanes": ["-DPXCHG_TUNE_FUSED_PARTS=1", "-DPXCHG_TUNE_FUSED_LANES=128"],
-    "meeting_one_part_128_lanes": ["-DPXCHG_TUNE_ELASTIC1_PARTS=1", "-DPXCHG_TUNE_ELASTIC1_LANES=128"],
-    "meeting_one_part_64_lanes": ["-DPXCHG_TUNE_ELASTIC1_PARTS=1", "-DPXCHG_TUNE_ELASTIC1_LANES=64"],
-    "meeting_one_part_256_lanes": ["-DPXCHG_TUNE_ELASTIC1_PARTS=1", "-DPXCHG_TUNE_ELASTIC1_LANES=256"],
-    "meeting_2_parts_128_lanes": ["-DPXCHG_TUNE_ELASTIC1_PARTS=2", "-DPXCHG_TUNE_ELASTIC1_LANES=128"],
-    "meeting_4_parts_64_lanes": ["-DPXCHG_TUNE_ELASTIC1_PARTS=4", "-DPXCHG_TUNE_ELASTIC1_LANES=64"],
+    "meeting_one_part_128_lanes": ["-DPXCHG_TUNE_ELASTIC1_PARTS=1", "-DPXCHG_TUNE_ELASTIC1_LANES=128", "-DPXCHG_TUNE_ELASTIC1_PAD=2"],
+    "meeting_one_part_64_lanes": ["-DPXCHG_TUNE_ELASTIC1_PARTS=1", "-DPXCHG_TUNE_ELASTIC1_LANES=64", "-DPXCHG_TUNE_ELASTIC1_PAD=2"],
+    "meeting_one_part_256_lanes": ["-DPXCHG_TUNE_ELASTIC1_PARTS=1", "-DPXCHG_TUNE_ELASTIC1_LANES=256", "-DPXCHG_TUNE_ELASTIC1_PAD=2"],
+    "meeting_2_parts_128_lanes": ["-DPXCHG_TUNE_ELASTIC1_PARTS=2", "-DPXCHG_TUNE_ELASTIC1_LANES=128", "-DPXCHG_TUNE_ELASTIC1_PAD=2"],
+    "meeting_4_parts_64_lanes": ["-DPXCHG_TUNE_ELASTIC1_PARTS=4", "-DPXCHG_TUNE_ELASTIC1_LANES=64", "-DPXCHG_TUNE_ELASTIC1_PAD=2"],
     # two workgroups per chunk for the kernels that ship with one
     "update_2_parts": ["-DPXCHG_TUNE_UPDATE_PARTS=2"],
     "update_2_parts_no_idle": ["-DPXCHG_TUNE_UPDATE_PARTS=2", "-DPXCHG_TUNE_NO_IDLE"],
