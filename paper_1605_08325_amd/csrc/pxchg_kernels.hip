@@ -91,7 +91,7 @@ __device__ __forceinline__ T *table_ptr(void *const *table, int tensor) {
 // chunks (few chunks per tensor) that measured 3..7 % on the reduce: 116 tensors in 7 M elements 25.5 against 26.4
 // us, 128 in 13.4 M 44.7 against 46.2, 512 in 7 M 23.7 against 25.1, 2048 in 61 M 177 against 187.  With many chunks
 // per tensor it is level or slower (AlexNet shapes 181 against 177, in step 171 against 168; VGGNet shapes in step
-// 393 against 382), so the launch picks by the table's average (lane_parallel_pointers below).  The other kernels
+// 393 against 382), so the launch picks by the table's average (small_tensors below).  The other kernels
 // keep the scalar loads at any tensor count: the same change cost the update 7 %, the meeting 18 %, the fused
 // reduce+update 2..6 % and the pack 4 % (the round of 8: level, 5 % faster with 2048 tensors).
 // A/B builds: PXCHG_TUNE_REDUCE_POINTERS = 0 (always scalar) or 1 (always lane-parallel).
@@ -825,20 +825,25 @@ constexpr int fused_lanes() {
     return K == 1 ? 128 : K == 2 ? 64 : 256 / fused_parts<K>();
 }
 
-template <int K, typename TI>
-constexpr int fused_threads() {  // the working lanes, plus idle wavefronts in A/B builds only
-#ifdef PXCHG_TUNE_FUSED_IDLE
+// Workgroup size of the fused kernel: the working lanes, and for three or more workers on tables of large tensors
+// (IDLE; see small_tensors below) one idle wavefront (see update_lanes), measured 2..3 % faster there (61 M in 16
+// tensors 293 against 299 us, in 116 tensors 292 against 301, 138 M in 32 tensors 667 against 683) and up to 11 %
+// slower on tables of many small tensors (61 M in 2048 tensors), which therefore run without; two idle wavefronts
+// lose 4 %.
+template <int K, typename TI, bool IDLE>
+constexpr int fused_threads() {
+#ifdef PXCHG_TUNE_FUSED_IDLE  // A/B builds only: that many idle wavefronts on every table
     if (K >= 3) return fused_lanes<K, TI>() + 64 * PXCHG_TUNE_FUSED_IDLE;
 #endif
-    return fused_lanes<K, TI>();
+    return fused_lanes<K, TI>() + (K >= 3 && IDLE ? 64 : 0);
 }
 
-template <int K, typename TI, bool WIRE16, int NT>
-__global__ __launch_bounds__((fused_threads<K, TI>())) void pxchg_reduce_avg_sgd_momentum_kernel(
+template <int K, typename TI, bool WIRE16, int NT, bool IDLE>
+__global__ __launch_bounds__((fused_threads<K, TI, IDLE>())) void pxchg_reduce_avg_sgd_momentum_kernel(
     const PxChunk *__restrict__ chunks, int n_chunks, FusedArgs args, int part_elems) {
     constexpr int PARTS = fused_parts<K>();
     constexpr int U = 512 / (fused_lanes<K, TI>() * PARTS);
-    PX_IDLE_WAVEFRONTS((fused_lanes<K, TI>()), (fused_threads<K, TI>()));
+    PX_IDLE_WAVEFRONTS((fused_lanes<K, TI>()), (fused_threads<K, TI, IDLE>()));
     constexpr bool SPLIT = U == 8;
     for (int vc = blockIdx.x; vc < n_chunks * PARTS; vc += gridDim.x) {
         PxChunk ch = chunks[vc / PARTS];
@@ -1368,13 +1373,17 @@ int launch_convert(const pxchg_table *t, int k, const pxchg_bufset *const *src, 
 #define PXCHG_TUNE_REDUCE_POLICY NT_LOADS_SC1_STORES
 #endif
 
-// Whether the reduce should fetch its pointers lane-parallel on this table (or view): tensors of at most 512 chunks
-// on average.  Measured: better up to 204 chunks per tensor, level at 1027, worse from 7400 on.
+// A table (or view) of many small tensors: at most 512 chunks per tensor on average.  Two launch choices follow it.
+// The reduce fetches its pointers lane-parallel on such tables (measured: better up to 204 chunks per tensor, level
+// at 1027, worse from 7400 on); the fused reduce+update has an idle wavefront on the others (better from 1027
+// chunks per tensor on, level at 233, worse at 58 and below).
+bool small_tensors(const pxchg_table *t) { return t->n_chunks <= (int64_t)512 * t->n_tensors; }
+
 bool lane_parallel_pointers(const pxchg_table *t) {
 #ifdef PXCHG_TUNE_REDUCE_POINTERS
     return PXCHG_TUNE_REDUCE_POINTERS != 0;
 #else
-    return t->n_chunks <= (int64_t)512 * t->n_tensors;
+    return small_tensors(t);
 #endif
 }
 
@@ -1421,15 +1430,23 @@ int launch_reduce(const pxchg_table *t, int k, const ReduceArgs &a, hipStream_t 
     }
 }
 
-template <int K, typename TI, bool WIRE16>
-int launch_fused_k(const pxchg_table *t, const FusedArgs &a, hipStream_t stream) {
+template <int K, typename TI, bool WIRE16, bool IDLE>
+int launch_fused_ki(const pxchg_table *t, const FusedArgs &a, hipStream_t stream) {
     const dim3 grid = grid_for(t, t->n_chunks * fused_parts<K>());
     const int part_elems = (int)(t->chunk_elems / fused_parts<K>());
-#define PX_CALL(N)                                                                                                   \
-    px_launch(pxchg_reduce_avg_sgd_momentum_kernel<K, TI, WIRE16, N>, grid, dim3(fused_threads<K, TI>()), stream, \
+#define PX_CALL(N)                                                                                                        \
+    px_launch(pxchg_reduce_avg_sgd_momentum_kernel<K, TI, WIRE16, N, IDLE>, grid, dim3(fused_threads<K, TI, IDLE>()), stream, \
               (const PxChunk *)t->d_chunks, (int)t->n_chunks, a, part_elems)
     PX_DISPATCH_NT(NT_BOTH, PX_CALL)
 #undef PX_CALL
+}
+
+template <int K, typename TI, bool WIRE16>
+int launch_fused_k(const pxchg_table *t, const FusedArgs &a, hipStream_t stream) {
+    if constexpr (K >= 3) {
+        if (!small_tensors(t)) return launch_fused_ki<K, TI, WIRE16, true>(t, a, stream);
+    }
+    return launch_fused_ki<K, TI, WIRE16, false>(t, a, stream);
 }
 
 template <typename TI, bool WIRE16>

@@ -46,10 +46,10 @@ VARIANTS = {
     "meeting_5_idle_wavefronts": ["-DPXCHG_TUNE_ELASTIC1_PAD=6"],
     "idle_wavefronts_leave_at_entry": ["-DPXCHG_TUNE_IDLE_EXIT=1"],
     "idle_wavefronts_leave_after_descriptor": ["-DPXCHG_TUNE_IDLE_EXIT=2"],
-    "reduce16_2_idle_leave_after_descriptor": ["-DPXCHG_TUNE_REDUCE16_IDLE=2", "-DPXCHG_TUNE_IDLE_EXIT=2"],
-    "fused_1_idle_leave_after_descriptor": ["-DPXCHG_TUNE_FUSED_IDLE=1", "-DPXCHG_TUNE_IDLE_EXIT=2"],
     "reduce16_2_idle_wavefronts": ["-DPXCHG_TUNE_REDUCE16_IDLE=2"],
+    "fused_no_idle_wavefront": ["-DPXCHG_TUNE_FUSED_IDLE=0"],
     "fused_1_idle_wavefront": ["-DPXCHG_TUNE_FUSED_IDLE=1"],
+    "fused_2_idle_wavefronts": ["-DPXCHG_TUNE_FUSED_IDLE=2"],
     "round8_4_idle_wavefronts": ["-DPXCHG_TUNE_ELASTIC8_PAD=2"],
     "reduce_pointers_by_scalar_loads": ["-DPXCHG_TUNE_REDUCE_POINTERS=0"],
     "reduce_pointers_lane_parallel": ["-DPXCHG_TUNE_REDUCE_POINTERS=1"],
