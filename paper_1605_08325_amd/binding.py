@@ -84,6 +84,12 @@ def open_library(path: str) -> ctypes.CDLL:
         raise ImportError(
             f"{path} is missing: build it with `python -m paper_1605_08325_amd.build` "
             "(hipcc, gfx950); this package has no CPU or eager fallback")
+    try:
+        # torch first: it brings a HIP runtime of its own, and the library must bind to the same one, or the two
+        # runtimes do not know each other's allocations (every call then answers "no usable GPU")
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     lib = ctypes.CDLL(path)
     for name, (res, args) in SIGNATURES.items():
         fn = getattr(lib, name)

@@ -87,6 +87,31 @@ def test_conversions_and_reduce(px, oracle_mod, policy, chunk):
                 px.reduce_avg(table, sets[in_dt], table.bufset(d_out))
                 assert_bits_equal(to_host(d_out), oracle_mod.reduce_avg_tensors(host[in_dt], out_dt),
                                   f"reduce k={kk} {in_dt.__name__}->{out_dt.__name__}")
+    if chunk == 512:
+        _reduce_on_a_table_of_large_tensors(px, oracle_mod)
+
+
+# One tensor of more than 512 chunks: the launch then takes the reduce that reads its pointers with scalar loads
+# (the tables above, of many small tensors, take the one that fetches them lane-parallel) and the fused
+# reduce+update with an idle wavefront.
+LARGE = [300_001]
+
+
+def _reduce_on_a_table_of_large_tensors(px, oracle_mod):
+    table = px.Table(LARGE)
+    assert table.n_chunks > 512 * len(LARGE)
+    for kk in (1, 3, 8):
+        g32 = [[a.copy() for a in wl.gaussian_tensors(LARGE, 0.01, 970, "grad", w)] for w in range(kk)]
+        g16 = [oracle_mod.pack_fp16_tensors(t) for t in g32]
+        sets = {np.float32: [table.bufset(to_device(t)) for t in g32],
+                np.float16: [table.bufset(to_device(t)) for t in g16]}
+        host = {np.float32: g32, np.float16: g16}
+        for in_dt in (np.float32, np.float16):
+            for out_dt in (np.float32, np.float16):
+                d_out = empty_like_device(LARGE, out_dt)
+                px.reduce_avg(table, sets[in_dt], table.bufset(d_out))
+                assert_bits_equal(to_host(d_out), oracle_mod.reduce_avg_tensors(host[in_dt], out_dt),
+                                  f"large tensor, reduce k={kk} {in_dt.__name__}->{out_dt.__name__}")
 
 
 @pytest.mark.parametrize("chunk", [512, 2048, 8192])
@@ -118,6 +143,22 @@ def test_updates(px, oracle_mod, policy, chunk):
                 oracle_mod.sgd_momentum_tensors(avg, w_, v_, 0.01, 0.9, 5e-4)
                 assert_bits_equal(to_host(d_w), w_, f"fused k={k} {in_dt.__name__} wire {wire_np.__name__} w")
                 assert_bits_equal(to_host(d_v), v_, f"fused k={k} {in_dt.__name__} wire {wire_np.__name__} v")
+    if chunk == 512:  # the fused kernel's build with an idle wavefront (tables of large tensors)
+        table = px.Table(LARGE)
+        for k in (3, 8):
+            g32 = [[a.copy() for a in wl.gaussian_tensors(LARGE, 0.01, 980 + k, "grad", w)] for w in range(k)]
+            for in_dt in (np.float16, np.float32):
+                contrib = [[a.astype(in_dt) for a in t] for t in g32]
+                sets = [table.bufset(to_device(t)) for t in contrib]
+                w_ = [a.copy() for a in wl.gaussian_tensors(LARGE, 0.01, 981, "param")]
+                v_ = [a.copy() for a in wl.gaussian_tensors(LARGE, 1e-3, 982, "velocity")]
+                d_w, d_v = to_device(w_), to_device(v_)
+                px.reduce_avg_sgd_momentum(table, sets, table.bufset(d_w), table.bufset(d_v), 0.01, 0.9, 5e-4,
+                                           px.AVG, px.F16)
+                avg = oracle_mod.reduce_avg_tensors(contrib, np.float16)
+                oracle_mod.sgd_momentum_tensors(avg, w_, v_, 0.01, 0.9, 5e-4)
+                assert_bits_equal(to_host(d_w), w_, f"large tensor, fused k={k} {in_dt.__name__} w")
+                assert_bits_equal(to_host(d_v), v_, f"large tensor, fused k={k} {in_dt.__name__} v")
 
 
 @pytest.mark.parametrize("center_resident", [0, 1])
