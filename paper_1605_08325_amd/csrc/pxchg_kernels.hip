@@ -494,13 +494,21 @@ constexpr int reduce_lanes() {
     return (touches_f32<TI, TO>() || (K >= 1 && K <= 3)) ? 64 : 128 / reduce_parts<K, touches_f32<TI, TO>()>();
 }
 
-// Workgroup size of the reduce kernels: the working lanes, plus idle wavefronts in A/B builds only.
-template <int K, typename TI, typename TO>
+// How a launch of the reduce treats its table (see small_tensors and large_tensors below).
+enum ReduceMode { REDUCE_PLAIN = 0, REDUCE_LANE_POINTERS = 1, REDUCE_IDLE_WAVEFRONTS = 2 };
+
+// Workgroup size of the reduce kernels: the working lanes, and for binary16 in and out with four to eight workers
+// on tables of large tensors two idle wavefronts (see update_lanes).  Measured there: 61 M in 16 tensors 171.2
+// against 175.9 us cold and 164.3 against 167.6 inside the step, 138 M in 32 tensors 378 against 396 and 365 against
+// 373; single tensors of 7 M to 100 M elements level to 6 % faster.  With a hundred tensors and more they cost
+// 4..8 % instead (61 M in 116 tensors 177 against 170; 7 M in 116 tensors 26.8 against 25.5; 13.4 M in 128 tensors
+// 48.6 against 45.0), and with 16 tensors in 7 M 2 %: hence only on tables of large tensors.
+template <int K, typename TI, typename TO, int MODE>
 constexpr int reduce_threads() {
-#ifdef PXCHG_TUNE_REDUCE16_IDLE  // idle wavefronts for binary16 in and out with four to eight workers
+#ifdef PXCHG_TUNE_REDUCE16_IDLE  // A/B builds only: that many idle wavefronts on every table
     if (!touches_f32<TI, TO>() && K >= 4) return reduce_lanes<K, TI, TO>() + 64 * PXCHG_TUNE_REDUCE16_IDLE;
 #endif
-    return reduce_lanes<K, TI, TO>();
+    return reduce_lanes<K, TI, TO>() + (MODE == REDUCE_IDLE_WAVEFRONTS && !touches_f32<TI, TO>() && K >= 4 ? 128 : 0);
 }
 
 struct ReduceArgs {
@@ -586,12 +594,12 @@ struct ReduceOpAnyK {
     __device__ __forceinline__ void store(const State &st, int i) const { storev<NT, U, SP>(dst + i, st.s); }
 };
 
-template <int K, typename TI, typename TO, int NT, bool LANE_POINTERS>
-__global__ __launch_bounds__((reduce_threads<K, TI, TO>())) void pxchg_reduce_avg_kernel(
+template <int K, typename TI, typename TO, int NT, int MODE>
+__global__ __launch_bounds__((reduce_threads<K, TI, TO, MODE>())) void pxchg_reduce_avg_kernel(
     const PxChunk *__restrict__ chunks, int n_chunks, ReduceArgs args, int part_elems) {
     constexpr int PARTS = reduce_parts<K, touches_f32<TI, TO>()>();
     constexpr int U = 512 / (reduce_lanes<K, TI, TO>() * PARTS);
-    PX_IDLE_WAVEFRONTS((reduce_lanes<K, TI, TO>()), (reduce_threads<K, TI, TO>()));
+    PX_IDLE_WAVEFRONTS((reduce_lanes<K, TI, TO>()), (reduce_threads<K, TI, TO, MODE>()));
     constexpr bool SPLIT = touches_f32<TI, TO>() && U == 8;
     for (int vc = blockIdx.x; vc < n_chunks * PARTS; vc += gridDim.x) {
         PxChunk ch = chunks[vc / PARTS];
@@ -601,7 +609,7 @@ __global__ __launch_bounds__((reduce_threads<K, TI, TO>())) void pxchg_reduce_av
         op.use_div = args.use_div;
         op.kf = args.kf;
         op.scale = args.scale;
-        if constexpr (LANE_POINTERS) {
+        if constexpr (MODE == REDUCE_LANE_POINTERS) {
             const int lane = threadIdx.x & 63;
             const void *const *tab = (const void *const *)args.out;  // lanes K.. (lane K's is the one read out)
 #pragma unroll
@@ -1385,21 +1393,26 @@ int launch_convert(const pxchg_table *t, int k, const pxchg_bufset *const *src, 
 // chunks per tensor on, level at 233, worse at 58 and below).
 bool small_tensors(const pxchg_table *t) { return t->n_chunks <= (int64_t)512 * t->n_tensors; }
 
-bool lane_parallel_pointers(const pxchg_table *t) {
-#ifdef PXCHG_TUNE_REDUCE_POINTERS
-    return PXCHG_TUNE_REDUCE_POINTERS != 0;
+// A table (or view) of large tensors: at least 4096 chunks per tensor on average (2 M elements at the default chunk
+// size).  The binary16 reduce runs with idle wavefronts on such tables (measured: better at 7400 and 8400 chunks
+// per tensor and on single tensors, worse at 1027 and below).
+bool large_tensors(const pxchg_table *t) { return t->n_chunks >= (int64_t)4096 * t->n_tensors; }
+
+int reduce_mode(const pxchg_table *t) {
+#ifdef PXCHG_TUNE_REDUCE_POINTERS  // A/B builds only: 0 scalar loads on every table, 1 lane-parallel on every table
+    return PXCHG_TUNE_REDUCE_POINTERS != 0 ? REDUCE_LANE_POINTERS : REDUCE_PLAIN;
 #else
-    return small_tensors(t);
+    return small_tensors(t) ? REDUCE_LANE_POINTERS : large_tensors(t) ? REDUCE_IDLE_WAVEFRONTS : REDUCE_PLAIN;
 #endif
 }
 
-template <int K, typename TI, typename TO, bool LANE_POINTERS>
-int launch_reduce_kp(const pxchg_table *t, const ReduceArgs &a, hipStream_t stream) {
+template <int K, typename TI, typename TO, int MODE>
+int launch_reduce_km(const pxchg_table *t, const ReduceArgs &a, hipStream_t stream) {
     constexpr int PARTS = reduce_parts<K, touches_f32<TI, TO>()>();
     const dim3 grid = grid_for(t, t->n_chunks * PARTS);
     const int part_elems = (int)(t->chunk_elems / PARTS);
 #define PX_CALL(N)                                                                                                \
-    px_launch(pxchg_reduce_avg_kernel<K, TI, TO, N, LANE_POINTERS>, grid, dim3(reduce_threads<K, TI, TO>()), stream, \
+    px_launch(pxchg_reduce_avg_kernel<K, TI, TO, N, MODE>, grid, dim3(reduce_threads<K, TI, TO, MODE>()), stream, \
               (const PxChunk *)t->d_chunks, (int)t->n_chunks, a, part_elems)
     PX_DISPATCH_NT(PXCHG_TUNE_REDUCE_POLICY, PX_CALL)
 #undef PX_CALL
@@ -1407,8 +1420,12 @@ int launch_reduce_kp(const pxchg_table *t, const ReduceArgs &a, hipStream_t stre
 
 template <int K, typename TI, typename TO>
 int launch_reduce_k(const pxchg_table *t, const ReduceArgs &a, hipStream_t stream) {
-    return lane_parallel_pointers(t) ? launch_reduce_kp<K, TI, TO, true>(t, a, stream)
-                                     : launch_reduce_kp<K, TI, TO, false>(t, a, stream);
+    const int mode = reduce_mode(t);
+    if (mode == REDUCE_LANE_POINTERS) return launch_reduce_km<K, TI, TO, REDUCE_LANE_POINTERS>(t, a, stream);
+    if constexpr (!touches_f32<TI, TO>() && K >= 4) {  // the only kernels whose shape the third mode changes
+        if (mode == REDUCE_IDLE_WAVEFRONTS) return launch_reduce_km<K, TI, TO, REDUCE_IDLE_WAVEFRONTS>(t, a, stream);
+    }
+    return launch_reduce_km<K, TI, TO, REDUCE_PLAIN>(t, a, stream);
 }
 
 template <typename TI, typename TO>

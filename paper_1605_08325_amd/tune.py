@@ -46,7 +46,10 @@ VARIANTS = {
     "meeting_5_idle_wavefronts": ["-DPXCHG_TUNE_ELASTIC1_PAD=6"],
     "idle_wavefronts_leave_at_entry": ["-DPXCHG_TUNE_IDLE_EXIT=1"],
     "idle_wavefronts_leave_after_descriptor": ["-DPXCHG_TUNE_IDLE_EXIT=2"],
+    "reduce16_no_idle_wavefronts": ["-DPXCHG_TUNE_REDUCE16_IDLE=0"],
+    "reduce16_1_idle_wavefront": ["-DPXCHG_TUNE_REDUCE16_IDLE=1"],
     "reduce16_2_idle_wavefronts": ["-DPXCHG_TUNE_REDUCE16_IDLE=2"],
+    "reduce16_3_idle_wavefronts": ["-DPXCHG_TUNE_REDUCE16_IDLE=3"],
     "fused_no_idle_wavefront": ["-DPXCHG_TUNE_FUSED_IDLE=0"],
     "fused_1_idle_wavefront": ["-DPXCHG_TUNE_FUSED_IDLE=1"],
     "fused_2_idle_wavefronts": ["-DPXCHG_TUNE_FUSED_IDLE=2"],

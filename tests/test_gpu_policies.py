@@ -95,6 +95,7 @@ def test_conversions_and_reduce(px, oracle_mod, policy, chunk):
 # (the tables above, of many small tensors, take the one that fetches them lane-parallel) and the fused
 # reduce+update with an idle wavefront.
 LARGE = [300_001]
+HUGE = [2_100_003]
 
 
 def _reduce_on_a_table_of_large_tensors(px, oracle_mod):
@@ -112,6 +113,15 @@ def _reduce_on_a_table_of_large_tensors(px, oracle_mod):
                 px.reduce_avg(table, sets[in_dt], table.bufset(d_out))
                 assert_bits_equal(to_host(d_out), oracle_mod.reduce_avg_tensors(host[in_dt], out_dt),
                                   f"large tensor, reduce k={kk} {in_dt.__name__}->{out_dt.__name__}")
+    # from 4096 chunks per tensor on, the binary16 reduce of four or more workers runs with idle wavefronts
+    table = px.Table(HUGE)
+    assert table.n_chunks >= 4096 * len(HUGE)
+    for kk in (4, 8):
+        g16 = [oracle_mod.pack_fp16_tensors([a.copy() for a in wl.gaussian_tensors(HUGE, 0.01, 975, "grad", w)])
+               for w in range(kk)]
+        d_out = empty_like_device(HUGE, np.float16)
+        px.reduce_avg(table, [table.bufset(to_device(t)) for t in g16], table.bufset(d_out))
+        assert_bits_equal(to_host(d_out), oracle_mod.reduce_avg_tensors(g16, np.float16), f"huge tensor, reduce k={kk}")
 
 
 @pytest.mark.parametrize("chunk", [512, 2048, 8192])
