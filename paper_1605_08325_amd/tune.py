@@ -58,7 +58,7 @@ VARIANTS = {
     "reduce_pointers_lane_parallel": ["-DPXCHG_TUNE_REDUCE_POINTERS=1"],
     "pack_128_lanes": ["-DPXCHG_TUNE_CONVERT_LANES=128"],
     "pack_2_parts": ["-DPXCHG_TUNE_CONVERT_PARTS=2"],
-    "reduce16_64_lanes": ["-DPXCHG_TUNE_REDUCE16_LANES=64"],
+    "reduce16_64_lanes": ["-DPXCHG_TUNE_REDUCE16_LANES=64", "-DPXCHG_TUNE_REDUCE16_IDLE=0"],
     "fused_one_part_256_lanes": ["-DPXCHG_TUNE_FUSED_PARTS=1"],
     "fused_one_part_64_lanes_split": ["-DPXCHG_TUNE_FUSED_PARTS=1", "-DPXCHG_TUNE_FUSED_LANES=64"],
     "fused_one_part_128_lanes": ["-DPXCHG_TUNE_FUSED_PARTS=1", "-DPXCHG_TUNE_FUSED_LANES=128"],
@@ -70,8 +70,8 @@ VARIANTS = {
     # two workgroups per chunk for the kernels that ship with one
     "update_2_parts": ["-DPXCHG_TUNE_UPDATE_PARTS=2"],
     "update_2_parts_no_idle": ["-DPXCHG_TUNE_UPDATE_PARTS=2", "-DPXCHG_TUNE_NO_IDLE"],
-    "reduce16_2_parts": ["-DPXCHG_TUNE_REDUCE16_PARTS=2"],
-    "reduce16_256_lanes": ["-DPXCHG_TUNE_REDUCE16_LANES=256"],
+    "reduce16_2_parts": ["-DPXCHG_TUNE_REDUCE16_PARTS=2", "-DPXCHG_TUNE_REDUCE16_IDLE=0"],
+    "reduce16_256_lanes": ["-DPXCHG_TUNE_REDUCE16_LANES=256", "-DPXCHG_TUNE_REDUCE16_IDLE=0"],
     "round8_4_parts_128_lanes": ["-DPXCHG_TUNE_ELASTIC8_PARTS=4"],
     "round8_one_part_512_lanes": ["-DPXCHG_TUNE_ELASTIC8_PARTS=1"],
     "round8_one_part_256_lanes": ["-DPXCHG_TUNE_ELASTIC8_PARTS=1", "-DPXCHG_TUNE_ELASTIC8_LANES=256"],
