@@ -35,3 +35,19 @@ def test_host_threads_reports_what_is_used_and_what_is_there(monkeypatch):
     assert used == min(3, available) and available == len(os.sched_getaffinity(0))
     monkeypatch.delenv("OMP_NUM_THREADS")
     assert bench.host_threads() == (available, available)
+
+
+def test_every_tuning_alternative_names_a_hook_that_the_kernel_source_has():
+    """paper_1605_08325_amd/tune.py builds its alternatives with -D flags; a flag whose macro the source no longer
+    tests would build the shipped library under another name and the A/B table would compare it with itself."""
+    import re
+    from paper_1605_08325_amd import tune
+    csrc = os.path.join(ROOT, "paper_1605_08325_amd", "csrc")
+    source = "".join(open(os.path.join(csrc, f)).read() for f in os.listdir(csrc) if f.endswith((".hip", ".h"))) + \
+        open(os.path.join(ROOT, "include", "pxchg.h")).read()
+    assert tune.VARIANTS["shipped"] == []
+    for name, flags in tune.VARIANTS.items():
+        for flag in flags:
+            m = re.fullmatch(r"-D(PXCHG_[A-Z0-9_]+)(=\d+)?", flag)
+            assert m, (name, flag)
+            assert re.search(r"#\s*(ifdef|ifndef|if|elif)\b[^\n]*\b" + m.group(1) + r"\b", source), (name, m.group(1))
