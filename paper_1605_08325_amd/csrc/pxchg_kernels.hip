@@ -439,7 +439,8 @@ constexpr int fused_parts() {  // the fused reduce+update with three to eight wo
 }
 
 // Converts every tensor of every worker between binary32 and binary16.  The grid covers k x n_chunks virtual
-// chunks, worker-major.  One wavefront in the split layout per chunk (A/B builds: other lanes, or several
+// chunks, worker-major (chunk-major, where consecutive workgroups take one chunk of consecutive workers and each
+// XCD so stays with one worker's buffers, measured 2 % slower).  One wavefront in the split layout per chunk (A/B builds: other lanes, or several
 // workgroups per chunk).
 constexpr int convert_parts() {
 #ifdef PXCHG_TUNE_CONVERT_PARTS
