@@ -83,7 +83,7 @@ enum pxchg_option {
                                     center with plain loads and write it with agent-scope stores, so that
                                     a center that fits the memory-side cache (256 MB) stays there from one
                                     meeting to the next, as on a server that does nothing but meet workers
-                                    (a meeting is then 12 % faster, a fused round 8..15 %); tables whose
+                                    (a meeting is then 7 % faster, a fused round of 8 workers 8 %); tables whose
                                     center is larger than that cache stream as with 0.  What is left
                                     dirty in that cache is written back during whatever runs next.
                                     Results never depend on it */
