@@ -719,14 +719,18 @@ struct UpdateOp {
     }
 };
 
-// Idle wavefronts.  Two kernels run faster when their workgroups are launched with more wavefronts than have
-// work: the extra ones find nothing to do in the vector part of a 512-element chunk and leave at once, and what
-// they change is the pace at which the dispatcher starts working wavefronts.  Measured against the same kernel
-// without them, in one run each and on sets from 7 M to 138 M elements: the update with a binary16 gradient
-// +1..2.5 % and the elastic meeting +1.5..3.5 % with as many idle wavefronts as working ones.  It is not a
-// general rule: the update with a float32 gradient lost 6 % in the exchange, the reduce gained 2 % on the
-// 61 M set and lost 12 % on small ones, pack lost 20 %, the fused kernels 1..7 %, so those have none.
-// Lanes beyond the working ones still take part in the element-wise paths.
+// Idle wavefronts.  Several kernels run faster when their workgroups are launched with more wavefronts than have
+// work.  The extra ones run the prelude like the others (the chunk's descriptor and pointers), find nothing to do
+// in the vector part of a 512-element chunk and end; lanes beyond the working ones only ever take part in the
+// element-wise paths.  Measured against the same kernel without them, in one run each, on sets from 7 M to 138 M
+// elements: the update with a binary16 gradient (as many idle wavefronts as working ones) 1.5..2.5 %, the single
+// elastic meeting (two per working one) 4..7 %, and on tables of large tensors the fused reduce+update of three
+// or more workers (one) 2..3 % and the binary16 reduce of four or more (two) 2..4 %.  The counts are optima, one
+// more or one less is 1..4 % slower.  Idle wavefronts that leave at kernel entry, or right after reading the
+// descriptor, give about half of the gain (A/B build PXCHG_TUNE_IDLE_EXIT): what helps is that they stay for the
+// prelude.  It is not a general rule: the update with a float32 gradient lost 6 % in the exchange, the pack 20 %,
+// the round of 8 workers 8 %, the float32 reduce 1..6 %; the reduce and the fused kernel lose 4..11 % with them on
+// tables of many tensors.  Those run without.
 template <typename TG>
 constexpr int update_lanes() {  // 128 working lanes; as many idle ones for a binary16 gradient
 #ifdef PXCHG_TUNE_UPDATE_THREADS  // A/B builds only: workgroup size for a binary16 gradient (128 lanes work)
